@@ -1,0 +1,209 @@
+/*
+ * permuquant.h -- C ABI of the MI355X (gfx950) per-group-quantized linear layer.
+ *
+ * The library implements the data-parallel hot path of PermuQuant: calibration statistics
+ * and permutation selection (paper Sec. 3.2-3.3), offline weight quantization in the
+ * selected channel order, dynamic per-group activation quantization, and the low-bit GEMM
+ * of the reordered quantized linear layer (paper Eq. 8).
+ *
+ * Conventions
+ *   - X is [M, K] row-major (tokens x input channels), W is [N, K] row-major (output x input
+ *     channels), Y[M, N] = X * W^T.  The paper writes Y = X W with W as in x out; its
+ *     P^T W is a column permutation of W here.
+ *   - K is the reduction (channel) dimension, `group` the group size g along K (the paper's
+ *     d and g; the paper's K = d/g is the number of groups).
+ *   - bf16 tensors are passed as const void* to 16-bit elements.
+ *   - Unless a parameter says "host", every pointer is DEVICE memory owned by the caller and
+ *     must stay valid until the work queued on `stream` has finished.  Tensor pointers must be
+ *     16-byte aligned.  The library allocates nothing; scratch memory comes in through
+ *     `workspace` (size from pq_workspace_bytes()).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls are
+ *     asynchronous on it unless stated otherwise.
+ *   - All arguments are validated on the host before anything is launched.  Every function
+ *     returns PQ_OK or a negative error code; pq_last_error() gives the message of the last
+ *     failure on the calling thread.  No C++ exception crosses this boundary.
+ *   - Inputs must be finite (no NaN/Inf); behaviour on non-finite inputs is unspecified.
+ *
+ * Stored formats (what parity is checked on)
+ *   codes   two 4-bit containers per byte, element k = 2j in the low nibble, 2j+1 in the high.
+ *           NVFP4: nibble = sign << 3 | E2M1 index (values 0, .5, 1, 1.5, 2, 3, 4, 6).
+ *           INT4 / INT3: 4-bit two's complement of z, z in [-Q, Q], Q = 7 / 3.
+ *   scales  row-major [rows, K / group]: NVFP4 one E4M3 byte (bias 7, max 448) per 16
+ *           channels; INT one float per group (Eq. 1: s = max|x| / Q).
+ *   tensor scale  NVFP4 only: one float per tensor, T = max|.| / (448 * 6).
+ *
+ * Quantizer arithmetic (every step one IEEE binary32 operation, round-to-nearest-even):
+ *   INT     s = amax / Q;  inv = s normal ? 1 / s : 0;  z = clip(rint(x * inv), -Q, Q)
+ *   NVFP4   encT = T normal ? 1 / T : 0;  t = (amax * encT) / 6;  s_b = E4M3_rne_sat(t);
+ *           d = value(s_b) * T;  inv = d normal ? 1 / d : 0;
+ *           code = sign(x) << 3 | E2M1_rne_sat(|x * inv|)     (ties to the even code)
+ */
+#ifndef PERMUQUANT_H
+#define PERMUQUANT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { PQ_FMT_NVFP4 = 0, PQ_FMT_INT4 = 1, PQ_FMT_INT3 = 2 } pq_format;
+
+typedef enum {
+  PQ_OP_CALIB_MOMENTS = 0,
+  PQ_OP_SELECT_PERM = 1,
+  PQ_OP_QUANTIZE_WEIGHTS = 2,
+  PQ_OP_QUANTIZE_ACT = 3,
+  PQ_OP_QGEMM = 4,
+  PQ_OP_QUANT_ERROR = 5
+} pq_op;
+
+#define PQ_OK 0
+#define PQ_ERR_NULL (-1)      /* a required pointer is NULL                                   */
+#define PQ_ERR_SHAPE (-2)     /* non-positive size, K % group != 0, ld < K, misaligned pointer */
+#define PQ_ERR_FORMAT (-3)    /* unknown format, or a (format, group) pair that is not offered */
+#define PQ_ERR_WORKSPACE (-4) /* workspace NULL or smaller than pq_workspace_bytes()          */
+#define PQ_ERR_HIP (-5)       /* the HIP runtime reported an error                            */
+
+#define PQ_MAX_ALPHAS 15
+
+/* Offered (format, group) pairs: NVFP4 with 16; INT4 and INT3 with 32, 64, 128 or 256.
+ * K must be a multiple of the group size (hence of 16).                                     */
+
+/* Message of the last failure on this thread ("" if none). Never NULL. Host memory owned by
+ * the library, valid until the next failing call on the same thread.                        */
+const char* pq_last_error(void);
+
+/* Library version, major * 100 + minor. */
+int pq_version(void);
+
+/* Bytes of workspace `op` needs for these sizes (0 if none).  Arguments an operation does not
+ * depend on may be 0.  Returns 0 for invalid arguments (the operation itself reports them). */
+size_t pq_workspace_bytes(pq_op op, pq_format fmt, int group, int64_t M, int64_t N, int64_t K,
+                          int n_batches);
+
+/*
+ * Per-input-channel second moments (paper Sec. 3.2, Assumption 1: mu_i^2 = E[x_i^2]; Sec. 3.3,
+ * Eq. 9 uses them for activations and for the matching weight channels).  A common factor
+ * does not change the sort, so sums of squares are kept instead of means.
+ *
+ *   sumsq[i] += sum_r x[r, i]^2   (fp64; squares of bf16 values are exact, accumulation fp64)
+ *   absmax[0] = max(absmax[0], max |x|)   if absmax != NULL (feeds the NVFP4 tensor scale)
+ *
+ * x: bf16 [rows, ld] with ld >= K.  sumsq: double [K], in/out -- the caller zero-fills it
+ * before the first batch; call once per calibration batch, and once with x = W, rows = N.
+ * absmax: float [1], in/out, >= 0 (zero-filled by the caller), may be NULL.
+ * workspace: pq_workspace_bytes(PQ_OP_CALIB_MOMENTS, ., ., rows, 0, K, 0) bytes; contents
+ * are scratch.  Results are deterministic (fixed summation order for fixed sizes).
+ */
+int pq_calib_moments(const void* x_bf16, int64_t rows, int64_t K, int64_t ld, double* sumsq,
+                     float* absmax, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Permutation selection (paper Sec. 3.3: joint score Eq. 9, alpha grid search, acceptance rule).
+ *
+ * For every alpha_j: key_i = alpha_j * ln(act_sumsq[i]) + (1 - alpha_j) * ln(w_sumsq[i]) (a
+ * term with zero weight is left out; a zero sum sorts last), channels sorted by descending key
+ * (Prop. 1), equal keys by ascending index.  Each candidate order pi and the original order are
+ * scored by
+ *     E(pi) = ||X - Xhat_pi||^2 / ||X||^2 + ||W - What_pi||^2 / ||W||^2
+ * over all calibration batches (each tensor quantized with this library's quantizer in the
+ * order pi, fp64 accumulation).  The candidate with the smallest E wins (ties: smallest j); it
+ * is accepted iff it differs from the identity, E_orig > 0 and
+ * (E_orig - E_best) / E_orig > tau.  perm_out receives the accepted order, else the identity.
+ * perm[j] = original channel that moves to position j.
+ *
+ * act_sumsq, w_sumsq: double [K] from pq_calib_moments.
+ * x_calib: HOST array of n_batches DEVICE pointers, each bf16 [M, K] contiguous.
+ * w_bf16: bf16 [N, K] contiguous.
+ * act_tensor_scale / w_tensor_scale: NVFP4 only (host floats, T of the header comment; the
+ * activation one comes from the calibration absmax, the weight one from max|W|); ignored for INT.
+ * alphas: HOST array of n_alpha values in [0, 1], 1 <= n_alpha <= PQ_MAX_ALPHAS.
+ * perm_out: int32 [K] device.  report: HOST struct, filled on return.
+ * This call synchronises `stream` once before returning (the decision is taken on the host).
+ */
+typedef struct {
+  int accepted;                  /* 1 if perm_out holds a reordering, 0 if the identity   */
+  int alpha_index;               /* index of the best candidate in alphas                 */
+  double e_orig;                 /* E of the original order                               */
+  double e_best;                 /* E of the best candidate                               */
+  double e_cand[PQ_MAX_ALPHAS];  /* E of every candidate                                  */
+  double sum_x2;                 /* ||X||^2 over the calibration batches                  */
+  double sum_w2;                 /* ||W||^2                                               */
+} pq_select_report;
+
+int pq_select_perm(pq_format fmt, int group, const double* act_sumsq, const double* w_sumsq,
+                   int64_t K, const void* const* x_calib, int n_batches, int64_t M,
+                   const void* w_bf16, int64_t N, float act_tensor_scale, float w_tensor_scale,
+                   const double* alphas, int n_alpha, double tau, int32_t* perm_out,
+                   pq_select_report* report, void* workspace, size_t workspace_bytes,
+                   void* stream);
+
+/*
+ * Squared quantization error of one tensor in a given channel order (paper Eq. 3 on a finite
+ * sample; the building block of E above, also what "quantization error with / without the
+ * permutation" reports):   err_out[0] = sum_{r,k} (x[r, perm[k]] - xhat)^2   (fp64).
+ * x: bf16 [rows, K] contiguous.  perm: int32 [K] or NULL (identity).  tensor_scale: host float,
+ * NVFP4 only.  err_out: double [1] device, overwritten.
+ */
+int pq_quant_error(pq_format fmt, int group, const void* x_bf16, int64_t rows, int64_t K,
+                   const int32_t* perm, float tensor_scale, double* err_out, void* workspace,
+                   size_t workspace_bytes, void* stream);
+
+/*
+ * Offline weight quantization in the selected channel order (paper Sec. 3.3 "Runtime-free
+ * deployment": the permutation of W's input channels is applied offline; Eq. 1-2 per row and
+ * group).  Element k of output row n is W[n, perm[k]].
+ *
+ * w_bf16: bf16 [N, K] contiguous.  perm: int32 [K] or NULL (identity).
+ * codes: uint8 [N, K/2].  scales: uint8 [N, K/16] (NVFP4) or float [N, K/group] (INT).
+ * tensor_scale_out: float [1] device; NVFP4: receives fl32(max|W| / 2688); INT: receives 1.0f.
+ */
+int pq_quantize_weights(pq_format fmt, int group, const void* w_bf16, int64_t N, int64_t K,
+                        const int32_t* perm, uint8_t* codes, void* scales,
+                        float* tensor_scale_out, void* stream);
+
+/*
+ * Dynamic per-group activation quantization of one batch of token rows (paper Sec. 3.1 Eq. 1-2,
+ * applied online per token as in App. A.3; Eq. 8's Q(XP)).
+ *
+ * x_bf16: bf16 [M, ld], ld >= K, ld % 8 == 0.
+ * perm: NULL when the producer already emits the permuted order (the deployment case, paper
+ * Sec. 3.3); non-NULL gathers x[m, perm[k]] on load (slower; calibration / test convenience).
+ * tensor_scale: float [1] device, NVFP4 only (static, from calibration); ignored for INT.
+ * codes: uint8 [M, K/2].  scales: uint8 [M, K/16] (NVFP4) or float [M, K/group] (INT).
+ */
+int pq_quantize_act(pq_format fmt, int group, const void* x_bf16, int64_t M, int64_t K,
+                    int64_t ld, const int32_t* perm, const float* tensor_scale, uint8_t* codes,
+                    void* scales, void* stream);
+
+/*
+ * Low-bit GEMM of the reordered quantized layer (paper Eq. 8):
+ *   Y[m, n] = Ta * Tw * sum_g sa[m, g] * sw[n, g] * sum_{k in g} a[m, k] * w[n, k]
+ * with fp32 accumulation over the whole of K and one rounding (nearest-even) to bf16 at the
+ * store.  Both operands must be in the same channel order and use the same (fmt, group).
+ *
+ * a_codes [M, K/2], a_scales [M, K/group], w_codes [N, K/2], w_scales [N, K/group] as stored by
+ * the quantizers above; a_tensor_scale / w_tensor_scale: float [1] device (NVFP4; ignored for
+ * INT, may be NULL).  y_bf16: bf16 [M, ldy], ldy >= N, ldy % 8 == 0.
+ * INT scales must be of the form fl32(h / Q) with h a bf16 value, which is what the quantizers
+ * above produce from bf16 inputs (the kernel folds h exactly into its fp16 MFMA operands).
+ * workspace: pq_workspace_bytes(PQ_OP_QGEMM, fmt, group, M, N, K, 0) bytes.
+ */
+int pq_qgemm(pq_format fmt, int group, const uint8_t* a_codes, const void* a_scales,
+             const float* a_tensor_scale, const uint8_t* w_codes, const void* w_scales,
+             const float* w_tensor_scale, int64_t M, int64_t N, int64_t K, void* y_bf16,
+             int64_t ldy, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Same product with the fp32 accumulator stored unrounded: y_f32 is float [M, ldy].  For
+ * checking the accumulation against an fp64 reference before the bf16 rounding.           */
+int pq_qgemm_f32(pq_format fmt, int group, const uint8_t* a_codes, const void* a_scales,
+                 const float* a_tensor_scale, const uint8_t* w_codes, const void* w_scales,
+                 const float* w_tensor_scale, int64_t M, int64_t N, int64_t K, float* y_f32,
+                 int64_t ldy, void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PERMUQUANT_H */

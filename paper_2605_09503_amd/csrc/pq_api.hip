@@ -1,0 +1,219 @@
+// C ABI entry points: host-side validation, then dispatch to the kernel launchers.
+// Every check happens before anything is queued on the stream.
+#include <stdio.h>
+#include <string.h>
+
+#include "pq_host.h"
+
+namespace pq {
+
+static thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+int check_hip(hipError_t e, const char* what) {
+  if (e == hipSuccess) return PQ_OK;
+  return fail(PQ_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+int check_format(pq_format fmt, int group, int64_t K) {
+  if (fmt != PQ_FMT_NVFP4 && fmt != PQ_FMT_INT4 && fmt != PQ_FMT_INT3)
+    return fail(PQ_ERR_FORMAT, "unknown format %d", (int)fmt);
+  if (fmt == PQ_FMT_NVFP4) {
+    if (group != 16) return fail(PQ_ERR_FORMAT, "NVFP4 uses groups of 16, got %d", group);
+  } else if (group != 32 && group != 64 && group != 128 && group != 256) {
+    return fail(PQ_ERR_FORMAT, "INT formats offer group 32, 64, 128 or 256, got %d", group);
+  }
+  if (K <= 0) return fail(PQ_ERR_SHAPE, "K must be positive, got %lld", (long long)K);
+  if (K % group) return fail(PQ_ERR_SHAPE, "K=%lld is not a multiple of group=%d", (long long)K, group);
+  return PQ_OK;
+}
+
+}  // namespace pq
+
+using namespace pq;
+
+extern "C" {
+
+const char* pq_last_error(void) { return g_err; }
+
+int pq_version(void) { return 100; }
+
+size_t pq_workspace_bytes(pq_op op, pq_format fmt, int group, int64_t M, int64_t N, int64_t K,
+                          int n_batches) {
+  switch (op) {
+    case PQ_OP_CALIB_MOMENTS:
+      if (M <= 0 || K <= 0) return 0;
+      return moments_workspace_bytes(M, K);
+    case PQ_OP_SELECT_PERM:
+      if (M <= 0 || N <= 0 || K <= 0 || n_batches <= 0) return 0;
+      return select_workspace_bytes(M, N, K, n_batches);
+    case PQ_OP_QUANT_ERROR:
+      if (M <= 0) return 0;
+      return quant_error_workspace_bytes(M);
+    case PQ_OP_QGEMM:
+      if (M <= 0 || N <= 0 || K <= 0 || group <= 0) return 0;
+      return qgemm_workspace_bytes(fmt, group, M, N, K);
+    default:
+      return 0;
+  }
+}
+
+int pq_calib_moments(const void* x, int64_t rows, int64_t K, int64_t ld, double* sumsq,
+                     float* absmax, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!x || !sumsq) return fail(PQ_ERR_NULL, "pq_calib_moments: x and sumsq must not be NULL");
+  if (rows <= 0 || K <= 0) return fail(PQ_ERR_SHAPE, "pq_calib_moments: rows=%lld K=%lld must be positive",
+                                        (long long)rows, (long long)K);
+  if (K % 8 || ld % 8) return fail(PQ_ERR_SHAPE, "pq_calib_moments: K=%lld and ld=%lld must be multiples of 8",
+                                   (long long)K, (long long)ld);
+  if (ld < K) return fail(PQ_ERR_SHAPE, "pq_calib_moments: ld=%lld < K=%lld", (long long)ld, (long long)K);
+  if (!aligned16(x)) return fail(PQ_ERR_SHAPE, "pq_calib_moments: x must be 16-byte aligned");
+  size_t need = moments_workspace_bytes(rows, K);
+  if (!workspace || workspace_bytes < need)
+    return fail(PQ_ERR_WORKSPACE, "pq_calib_moments: workspace of %zu bytes needed, %zu given", need,
+                workspace ? workspace_bytes : (size_t)0);
+  return launch_moments(x, rows, K, ld, sumsq, absmax, workspace, as_stream(stream));
+}
+
+int pq_select_perm(pq_format fmt, int group, const double* act_sumsq, const double* w_sumsq,
+                   int64_t K, const void* const* x_calib, int n_batches, int64_t M,
+                   const void* w_bf16, int64_t N, float act_tensor_scale, float w_tensor_scale,
+                   const double* alphas, int n_alpha, double tau, int32_t* perm_out,
+                   pq_select_report* report, void* workspace, size_t workspace_bytes,
+                   void* stream) {
+  if (!act_sumsq || !w_sumsq || !x_calib || !w_bf16 || !alphas || !perm_out || !report)
+    return fail(PQ_ERR_NULL, "pq_select_perm: a required pointer is NULL");
+  int rc = check_format(fmt, group, K);
+  if (rc) return rc;
+  if (M <= 0 || N <= 0) return fail(PQ_ERR_SHAPE, "pq_select_perm: M=%lld N=%lld must be positive",
+                                    (long long)M, (long long)N);
+  if (n_batches <= 0) return fail(PQ_ERR_SHAPE, "pq_select_perm: n_batches=%d must be positive", n_batches);
+  if (n_alpha <= 0 || n_alpha > PQ_MAX_ALPHAS)
+    return fail(PQ_ERR_SHAPE, "pq_select_perm: n_alpha=%d outside 1..%d", n_alpha, PQ_MAX_ALPHAS);
+  if (K > 65536) return fail(PQ_ERR_SHAPE, "pq_select_perm: K=%lld above the supported 65536", (long long)K);
+  for (int j = 0; j < n_alpha; ++j)
+    if (!(alphas[j] >= 0.0 && alphas[j] <= 1.0))
+      return fail(PQ_ERR_SHAPE, "pq_select_perm: alphas[%d]=%g outside [0, 1]", j, alphas[j]);
+  if (!(tau == tau)) return fail(PQ_ERR_SHAPE, "pq_select_perm: tau is NaN");
+  for (int b = 0; b < n_batches; ++b) {
+    if (!x_calib[b]) return fail(PQ_ERR_NULL, "pq_select_perm: x_calib[%d] is NULL", b);
+    if (!aligned16(x_calib[b])) return fail(PQ_ERR_SHAPE, "pq_select_perm: x_calib[%d] must be 16-byte aligned", b);
+  }
+  if (!aligned16(w_bf16)) return fail(PQ_ERR_SHAPE, "pq_select_perm: w must be 16-byte aligned");
+  size_t need = select_workspace_bytes(M, N, K, n_batches);
+  if (!workspace || workspace_bytes < need)
+    return fail(PQ_ERR_WORKSPACE, "pq_select_perm: workspace of %zu bytes needed, %zu given", need,
+                workspace ? workspace_bytes : (size_t)0);
+  return run_select(fmt, group, act_sumsq, w_sumsq, K, x_calib, n_batches, M, w_bf16, N,
+                    act_tensor_scale, w_tensor_scale, alphas, n_alpha, tau, perm_out, report,
+                    workspace, as_stream(stream));
+}
+
+int pq_quant_error(pq_format fmt, int group, const void* x, int64_t rows, int64_t K,
+                   const int32_t* perm, float tensor_scale, double* err_out, void* workspace,
+                   size_t workspace_bytes, void* stream) {
+  if (!x || !err_out) return fail(PQ_ERR_NULL, "pq_quant_error: x and err_out must not be NULL");
+  int rc = check_format(fmt, group, K);
+  if (rc) return rc;
+  if (rows <= 0) return fail(PQ_ERR_SHAPE, "pq_quant_error: rows=%lld must be positive", (long long)rows);
+  if (K > 65536) return fail(PQ_ERR_SHAPE, "pq_quant_error: K=%lld above the supported 65536", (long long)K);
+  if (!aligned16(x)) return fail(PQ_ERR_SHAPE, "pq_quant_error: x must be 16-byte aligned");
+  size_t need = quant_error_workspace_bytes(rows);
+  if (!workspace || workspace_bytes < need)
+    return fail(PQ_ERR_WORKSPACE, "pq_quant_error: workspace of %zu bytes needed, %zu given", need,
+                workspace ? workspace_bytes : (size_t)0);
+  return run_quant_error(fmt, group, x, rows, K, perm, tensor_scale, err_out, workspace,
+                         as_stream(stream));
+}
+
+int pq_quantize_weights(pq_format fmt, int group, const void* w, int64_t N, int64_t K,
+                        const int32_t* perm, uint8_t* codes, void* scales, float* tensor_scale_out,
+                        void* stream) {
+  if (!w || !codes || !scales || !tensor_scale_out)
+    return fail(PQ_ERR_NULL, "pq_quantize_weights: a required pointer is NULL");
+  int rc = check_format(fmt, group, K);
+  if (rc) return rc;
+  if (N <= 0) return fail(PQ_ERR_SHAPE, "pq_quantize_weights: N=%lld must be positive", (long long)N);
+  if (!aligned16(w) || !aligned16(codes) || !aligned16(scales))
+    return fail(PQ_ERR_SHAPE, "pq_quantize_weights: tensors must be 16-byte aligned");
+  hipStream_t st = as_stream(stream);
+  if (fmt == PQ_FMT_NVFP4) {
+    rc = launch_absmax_to_tensor_scale(w, N * K, tensor_scale_out, st);
+  } else {
+    rc = launch_fill_float(tensor_scale_out, 1.0f, st);
+  }
+  if (rc) return rc;
+  return launch_quantize_rows(fmt, group, w, N, K, K, perm, tensor_scale_out, codes, scales, st);
+}
+
+int pq_quantize_act(pq_format fmt, int group, const void* x, int64_t M, int64_t K, int64_t ld,
+                    const int32_t* perm, const float* tensor_scale, uint8_t* codes, void* scales,
+                    void* stream) {
+  if (!x || !codes || !scales) return fail(PQ_ERR_NULL, "pq_quantize_act: a required pointer is NULL");
+  int rc = check_format(fmt, group, K);
+  if (rc) return rc;
+  if (fmt == PQ_FMT_NVFP4 && !tensor_scale)
+    return fail(PQ_ERR_NULL, "pq_quantize_act: NVFP4 needs the per-tensor scale");
+  if (M <= 0) return fail(PQ_ERR_SHAPE, "pq_quantize_act: M=%lld must be positive", (long long)M);
+  if (ld < K || ld % 8)
+    return fail(PQ_ERR_SHAPE, "pq_quantize_act: ld=%lld must be >= K=%lld and a multiple of 8",
+                (long long)ld, (long long)K);
+  if (!aligned16(x) || !aligned16(codes) || !aligned16(scales))
+    return fail(PQ_ERR_SHAPE, "pq_quantize_act: tensors must be 16-byte aligned");
+  return launch_quantize_rows(fmt, group, x, M, K, ld, perm, tensor_scale, codes, scales,
+                              as_stream(stream));
+}
+
+static int qgemm_common(pq_format fmt, int group, const uint8_t* a_codes, const void* a_scales,
+                        const float* a_ts, const uint8_t* w_codes, const void* w_scales,
+                        const float* w_ts, int64_t M, int64_t N, int64_t K, void* y, int64_t ldy,
+                        bool out_f32, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!a_codes || !a_scales || !w_codes || !w_scales || !y)
+    return fail(PQ_ERR_NULL, "pq_qgemm: a required pointer is NULL");
+  int rc = check_format(fmt, group, K);
+  if (rc) return rc;
+  if (fmt == PQ_FMT_NVFP4 && (!a_ts || !w_ts))
+    return fail(PQ_ERR_NULL, "pq_qgemm: NVFP4 needs both per-tensor scales");
+  if (M <= 0 || N <= 0) return fail(PQ_ERR_SHAPE, "pq_qgemm: M=%lld N=%lld must be positive",
+                                    (long long)M, (long long)N);
+  if (K % 32) return fail(PQ_ERR_SHAPE, "pq_qgemm: K=%lld must be a multiple of 32", (long long)K);
+  if (M > (1 << 24) || N > (1 << 24) || K > (1 << 24))
+    return fail(PQ_ERR_SHAPE, "pq_qgemm: a dimension exceeds 2^24");
+  if (ldy < N || ldy % 8)
+    return fail(PQ_ERR_SHAPE, "pq_qgemm: ldy=%lld must be >= N=%lld and a multiple of 8",
+                (long long)ldy, (long long)N);
+  if (!aligned16(a_codes) || !aligned16(w_codes) || !aligned16(a_scales) || !aligned16(w_scales) ||
+      !aligned16(y))
+    return fail(PQ_ERR_SHAPE, "pq_qgemm: tensors must be 16-byte aligned");
+  size_t need = qgemm_workspace_bytes(fmt, group, M, N, K);
+  if (need && (!workspace || workspace_bytes < need))
+    return fail(PQ_ERR_WORKSPACE, "pq_qgemm: workspace of %zu bytes needed, %zu given", need,
+                workspace ? workspace_bytes : (size_t)0);
+  if (need && !aligned16(workspace)) return fail(PQ_ERR_SHAPE, "pq_qgemm: workspace must be 16-byte aligned");
+  return run_qgemm(fmt, group, a_codes, a_scales, a_ts, w_codes, w_scales, w_ts, M, N, K, y, ldy,
+                   out_f32, workspace, as_stream(stream));
+}
+
+int pq_qgemm(pq_format fmt, int group, const uint8_t* a_codes, const void* a_scales,
+             const float* a_tensor_scale, const uint8_t* w_codes, const void* w_scales,
+             const float* w_tensor_scale, int64_t M, int64_t N, int64_t K, void* y_bf16, int64_t ldy,
+             void* workspace, size_t workspace_bytes, void* stream) {
+  return qgemm_common(fmt, group, a_codes, a_scales, a_tensor_scale, w_codes, w_scales,
+                      w_tensor_scale, M, N, K, y_bf16, ldy, false, workspace, workspace_bytes, stream);
+}
+
+int pq_qgemm_f32(pq_format fmt, int group, const uint8_t* a_codes, const void* a_scales,
+                 const float* a_tensor_scale, const uint8_t* w_codes, const void* w_scales,
+                 const float* w_tensor_scale, int64_t M, int64_t N, int64_t K, float* y_f32,
+                 int64_t ldy, void* workspace, size_t workspace_bytes, void* stream) {
+  return qgemm_common(fmt, group, a_codes, a_scales, a_tensor_scale, w_codes, w_scales,
+                      w_tensor_scale, M, N, K, y_f32, ldy, true, workspace, workspace_bytes, stream);
+}
+
+}  // extern "C"

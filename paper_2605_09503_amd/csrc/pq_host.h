@@ -1,0 +1,54 @@
+// Host-side plumbing shared by the entry points: error reporting, argument checks,
+// workspace carving.  Nothing here is exported; the C ABI lives in include/permuquant.h.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdarg.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/permuquant.h"
+
+namespace pq {
+
+// Records a message for pq_last_error() and returns `code`.
+int fail(int code, const char* fmt, ...);
+
+// hipGetLastError / API status -> PQ_ERR_HIP with the runtime's text.
+int check_hip(hipError_t e, const char* what);
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// PQ_OK, or the error for an unknown format / unsupported (format, group) pair / K % group.
+int check_format(pq_format fmt, int group, int64_t K);
+
+inline hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
+
+// ---- kernel launchers (one per source file) --------------------------------------------
+size_t moments_workspace_bytes(int64_t rows, int64_t K);
+int launch_moments(const void* x, int64_t rows, int64_t K, int64_t ld, double* sumsq, float* absmax,
+                   void* ws, hipStream_t st);
+
+int launch_absmax_to_tensor_scale(const void* x, int64_t n_elems, float* tensor_scale_out,
+                                  hipStream_t st);
+int launch_fill_float(float* p, float v, hipStream_t st);
+int launch_quantize_rows(pq_format fmt, int group, const void* x, int64_t rows, int64_t K, int64_t ld,
+                         const int32_t* perm, const float* tensor_scale, uint8_t* codes, void* scales,
+                         hipStream_t st);
+
+size_t select_workspace_bytes(int64_t M, int64_t N, int64_t K, int n_batches);
+size_t quant_error_workspace_bytes(int64_t rows);
+int run_select(pq_format fmt, int group, const double* act_sumsq, const double* w_sumsq, int64_t K,
+               const void* const* x_calib, int n_batches, int64_t M, const void* w, int64_t N,
+               float act_ts, float w_ts, const double* alphas, int n_alpha, double tau,
+               int32_t* perm_out, pq_select_report* report, void* ws, hipStream_t st);
+int run_quant_error(pq_format fmt, int group, const void* x, int64_t rows, int64_t K,
+                    const int32_t* perm, float ts, double* err_out, void* ws, hipStream_t st);
+
+size_t qgemm_workspace_bytes(pq_format fmt, int group, int64_t M, int64_t N, int64_t K);
+int run_qgemm(pq_format fmt, int group, const uint8_t* a_codes, const void* a_scales,
+              const float* a_ts, const uint8_t* w_codes, const void* w_scales, const float* w_ts,
+              int64_t M, int64_t N, int64_t K, void* y, int64_t ldy, bool out_f32, void* ws,
+              hipStream_t st);
+
+}  // namespace pq

@@ -1,0 +1,353 @@
+// Permutation selection (paper Sec. 3.3): joint second-moment score (Eq. 9), descending sort
+// (Prop. 1), calibration error of every candidate order, alpha search and acceptance rule.
+//
+// Kernels
+//   key_kernel        key[j][i] = alpha_j ln Sa[i] + (1 - alpha_j) ln Sw[i], fp64; a term whose
+//                     weight is zero is skipped.
+//   rank_kernel       stable descending sort by counting: rank(i) = #{j : key_j > key_i or
+//                     (key_j == key_i and j < i)}; perm[rank(i)] = i.  O(K^2) compares, K <= 65536,
+//                     keys staged through LDS; no data-dependent control flow, fully deterministic.
+//   quant_error_kernel one workgroup per row: the row is staged in LDS once, then for every
+//                     candidate order its channels are gathered from LDS, quantized with the same
+//                     lane-cooperative quantizer as the runtime kernels, dequantized, and the
+//                     squared error accumulated in fp64.  HBM traffic is one read of the tensor
+//                     for all candidates.
+//   reduce_rows_kernel fixed-order sum of the per-row errors (deterministic).
+// The final argmin / acceptance decision is a handful of scalar operations and runs on the host.
+#include <string.h>
+
+#include <vector>
+
+#include "pq_device.h"
+#include "pq_host.h"
+
+namespace pq {
+
+constexpr int kMaxCand = PQ_MAX_ALPHAS + 1;   // identity + candidates
+
+__global__ __launch_bounds__(256) void key_kernel(const double* __restrict__ sa,
+                                                  const double* __restrict__ sw, int64_t K,
+                                                  double alpha, double* __restrict__ key) {
+  int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= K) return;
+  double k = 0.0;
+  if (alpha != 0.0) k += alpha * log(sa[i]);
+  if (alpha != 1.0) k += (1.0 - alpha) * log(sw[i]);
+  key[i] = k;
+}
+
+__global__ __launch_bounds__(256) void rank_kernel(const double* __restrict__ key, int K,
+                                                   int32_t* __restrict__ perm) {
+  __shared__ double tile[256];
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  const double ki = (i < K) ? key[i] : 0.0;
+  int rank = 0;
+  for (int j0 = 0; j0 < K; j0 += 256) {
+    int j = j0 + threadIdx.x;
+    tile[threadIdx.x] = (j < K) ? key[j] : 0.0;
+    __syncthreads();
+    int n = min(256, K - j0);
+    for (int t = 0; t < n; ++t) {
+      double kj = tile[t];
+      int jj = j0 + t;
+      rank += (kj > ki || (kj == ki && jj < i)) ? 1 : 0;
+    }
+    __syncthreads();
+  }
+  if (i < K) perm[rank] = i;
+}
+
+__global__ __launch_bounds__(256) void iota_kernel(int32_t* p, int K) {
+  int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < K) p[i] = i;
+}
+
+// moved[c] = number of positions where cand c differs from the identity
+__global__ __launch_bounds__(256) void count_moved_kernel(const int32_t* __restrict__ cands, int K,
+                                                          int* __restrict__ moved) {
+  const int32_t* p = cands + (int64_t)blockIdx.x * K;
+  int n = 0;
+  for (int i = threadIdx.x; i < K; i += 256) n += (p[i] != i);
+  __shared__ int red[256];
+  red[threadIdx.x] = n;
+  __syncthreads();
+  for (int s = 128; s > 0; s >>= 1) {
+    if (threadIdx.x < s) red[threadIdx.x] += red[threadIdx.x + s];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) moved[blockIdx.x] = red[0];
+}
+
+// out[0] = sum(a[0..K)), out[1] = sum(b[0..K)), fixed order
+__global__ __launch_bounds__(256) void sum2_kernel(const double* __restrict__ a,
+                                                   const double* __restrict__ b, int64_t K,
+                                                   double* __restrict__ out) {
+  __shared__ double red[256];
+  for (int which = 0; which < 2; ++which) {
+    const double* p = which ? b : a;
+    double s = 0.0;
+    for (int64_t i = threadIdx.x; i < K; i += 256) s += p[i];
+    red[threadIdx.x] = s;
+    __syncthreads();
+    for (int st = 128; st > 0; st >>= 1) {
+      if (threadIdx.x < st) red[threadIdx.x] += red[threadIdx.x + st];
+      __syncthreads();
+    }
+    if (threadIdx.x == 0) out[which] = red[0];
+    __syncthreads();
+  }
+}
+
+__device__ __forceinline__ float e2m1_value(uint32_t idx) {
+  uint32_t e = idx >> 1, m = idx & 1u;
+  return e == 0 ? 0.5f * float(m) : as_f32(((e + 126u) << 23) | (m << 22));
+}
+
+// cands: [n_cand][K] int32, candidate c == -1 style identity is expressed by cands == nullptr
+// for c < first_perm.  row_err: [rows][n_cand] fp64.
+template <int FMT, int G>
+__global__ __launch_bounds__(256) void quant_error_kernel(const uint16_t* __restrict__ x, int K,
+                                                          const int32_t* __restrict__ cands,
+                                                          int n_cand, int identity_first, float T,
+                                                          double* __restrict__ row_err) {
+  extern __shared__ float row[];           // K floats
+  __shared__ double red[4];
+  const int64_t r = blockIdx.x;
+  const uint16_t* xr = x + r * (int64_t)K;
+  for (int c = threadIdx.x; c < K / 8; c += 256) {
+    uint4 p = *reinterpret_cast<const uint4*>(xr + (int64_t)c * 8);
+    float* d = row + c * 8;
+    d[0] = bf16_lo(p.x); d[1] = bf16_hi(p.x); d[2] = bf16_lo(p.y); d[3] = bf16_hi(p.y);
+    d[4] = bf16_lo(p.z); d[5] = bf16_hi(p.z); d[6] = bf16_lo(p.w); d[7] = bf16_hi(p.w);
+  }
+  __syncthreads();
+  const float encT = (FMT == kNvfp4) ? nv4_enc_scale(T) : 0.0f;
+  const int chunks = K / 8;
+  for (int cand = 0; cand < n_cand; ++cand) {
+    const int32_t* perm = nullptr;
+    if (!(identity_first && cand == 0)) perm = cands + (int64_t)(cand - identity_first) * K;
+    double err = 0.0;
+    for (int c0 = 0; c0 < chunks; c0 += 256) {
+      int c = c0 + threadIdx.x;
+      float v[8];
+      if (c < chunks) {
+        if (perm) {
+          const int4* pp = reinterpret_cast<const int4*>(perm + c * 8);
+          int4 i0 = pp[0], i1 = pp[1];
+          v[0] = row[i0.x]; v[1] = row[i0.y]; v[2] = row[i0.z]; v[3] = row[i0.w];
+          v[4] = row[i1.x]; v[5] = row[i1.y]; v[6] = row[i1.z]; v[7] = row[i1.w];
+        } else {
+#pragma unroll
+          for (int j = 0; j < 8; ++j) v[j] = row[c * 8 + j];
+        }
+      } else {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[j] = 0.0f;
+      }
+      float a = 0.0f;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) a = fmaxf(a, fabsf(v[j]));
+      a = group_max<G / 8>(a);
+      if constexpr (FMT == kNvfp4) {
+        Nv4Scale s = nv4_scale(a, T, encT);
+        double d = (double)e4m3_decode(s.byte) * (double)T;      // exact: 4 + 24 bits
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          uint32_t code = nv4_code(v[j], s.inv);
+          double mag = (double)e2m1_value(code & 7u) * d;         // exact
+          double xh = (code & 8u) ? -mag : mag;
+          double e = (double)v[j] - xh;
+          err += e * e;
+        }
+      } else {
+        const float Q = qmax_of(FMT);
+        IntScale s = int_scale(a, Q);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          float t = v[j] * s.inv;
+          t = rintf(fminf(fmaxf(t, -Q), Q));
+          double e = (double)v[j] - (double)s.s * (double)t;      // product exact in fp64
+          err += e * e;
+        }
+      }
+    }
+    // block reduction in a fixed order: lanes by xor-tree, then the four waves in order
+    err = wave_sum(err);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = err;
+    __syncthreads();
+    if (threadIdx.x == 0) row_err[r * n_cand + cand] = (red[0] + red[1]) + (red[2] + red[3]);
+    __syncthreads();
+  }
+}
+
+// out[c] = sum over rows of row_err[r][c], one workgroup per candidate, fixed order
+__global__ __launch_bounds__(256) void reduce_rows_kernel(const double* __restrict__ row_err,
+                                                          int64_t rows, int n_cand,
+                                                          double* __restrict__ out) {
+  __shared__ double red[256];
+  const int c = blockIdx.x;
+  double s = 0.0;
+  for (int64_t r = threadIdx.x; r < rows; r += 256) s += row_err[r * n_cand + c];
+  red[threadIdx.x] = s;
+  __syncthreads();
+  for (int st = 128; st > 0; st >>= 1) {
+    if (threadIdx.x < st) red[threadIdx.x] += red[threadIdx.x + st];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) out[c] = red[0];
+}
+
+template <int FMT, int G>
+static int launch_qe(const void* x, int64_t rows, int K, const int32_t* cands, int n_cand,
+                     int identity_first, float T, double* row_err, hipStream_t st) {
+  size_t shmem = (size_t)K * sizeof(float);
+  auto kern = quant_error_kernel<FMT, G>;
+  if (shmem > 48 * 1024) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
+    if (e != hipSuccess) return check_hip(e, "hipFuncSetAttribute(quant_error_kernel)");
+  }
+  hipLaunchKernelGGL(kern, dim3((unsigned)rows), dim3(256), shmem, st, (const uint16_t*)x, K, cands,
+                     n_cand, identity_first, T, row_err);
+  return check_hip(hipGetLastError(), "quant_error_kernel");
+}
+
+static int launch_quant_error(pq_format fmt, int group, const void* x, int64_t rows, int K,
+                              const int32_t* cands, int n_cand, int identity_first, float T,
+                              double* row_err, hipStream_t st) {
+  if ((size_t)K * 4 > 150 * 1024) return fail(PQ_ERR_SHAPE, "K=%d too large for the LDS-resident row", K);
+  if (fmt == PQ_FMT_NVFP4)
+    return launch_qe<kNvfp4, 16>(x, rows, K, cands, n_cand, identity_first, T, row_err, st);
+#define PQ_INT_CASE(F, FE)                                                                          \
+  if (fmt == F) {                                                                                   \
+    switch (group) {                                                                                \
+      case 32: return launch_qe<FE, 32>(x, rows, K, cands, n_cand, identity_first, T, row_err, st);  \
+      case 64: return launch_qe<FE, 64>(x, rows, K, cands, n_cand, identity_first, T, row_err, st);  \
+      case 128: return launch_qe<FE, 128>(x, rows, K, cands, n_cand, identity_first, T, row_err, st); \
+      case 256: return launch_qe<FE, 256>(x, rows, K, cands, n_cand, identity_first, T, row_err, st); \
+    }                                                                                               \
+  }
+  PQ_INT_CASE(PQ_FMT_INT4, kInt4)
+  PQ_INT_CASE(PQ_FMT_INT3, kInt3)
+#undef PQ_INT_CASE
+  return fail(PQ_ERR_FORMAT, "unsupported (format, group) = (%d, %d)", (int)fmt, group);
+}
+
+// ------------------------------------------------------------------------- workspace layout
+struct SelectWs {
+  double* keys;      // [K]
+  int32_t* cands;    // [PQ_MAX_ALPHAS][K]
+  double* row_err;   // [max(M, N)][kMaxCand]
+  double* sums;      // [(n_batches + 1) * kMaxCand + 2] : per-batch errors, weight errors, |X|^2, |W|^2
+  int* moved;        // [PQ_MAX_ALPHAS]
+};
+
+static size_t carve_select(void* base, int64_t M, int64_t N, int64_t K, int n_batches, SelectWs* w) {
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    size_t o = off;
+    off = align_up(off + bytes, 256);
+    return o;
+  };
+  size_t o_keys = take((size_t)K * 8);
+  size_t o_cands = take((size_t)PQ_MAX_ALPHAS * K * 4);
+  size_t o_rowerr = take((size_t)(M > N ? M : N) * kMaxCand * 8);
+  size_t o_sums = take(((size_t)(n_batches + 1) * kMaxCand + 2) * 8);
+  size_t o_moved = take((size_t)PQ_MAX_ALPHAS * 4);
+  if (w) {
+    char* b = (char*)base;
+    w->keys = (double*)(b + o_keys);
+    w->cands = (int32_t*)(b + o_cands);
+    w->row_err = (double*)(b + o_rowerr);
+    w->sums = (double*)(b + o_sums);
+    w->moved = (int*)(b + o_moved);
+  }
+  return off;
+}
+
+size_t select_workspace_bytes(int64_t M, int64_t N, int64_t K, int n_batches) {
+  return carve_select(nullptr, M, N, K, n_batches, nullptr);
+}
+
+size_t quant_error_workspace_bytes(int64_t rows) { return align_up((size_t)rows * 8, 256); }
+
+int run_quant_error(pq_format fmt, int group, const void* x, int64_t rows, int64_t K,
+                    const int32_t* perm, float ts, double* err_out, void* ws, hipStream_t st) {
+  double* row_err = (double*)ws;
+  int rc = launch_quant_error(fmt, group, x, rows, (int)K, perm, 1, perm ? 0 : 1, ts, row_err, st);
+  if (rc) return rc;
+  hipLaunchKernelGGL(reduce_rows_kernel, dim3(1), dim3(256), 0, st, row_err, rows, 1, err_out);
+  return check_hip(hipGetLastError(), "reduce_rows_kernel");
+}
+
+int run_select(pq_format fmt, int group, const double* act_sumsq, const double* w_sumsq, int64_t K,
+               const void* const* x_calib, int n_batches, int64_t M, const void* w, int64_t N,
+               float act_ts, float w_ts, const double* alphas, int n_alpha, double tau,
+               int32_t* perm_out, pq_select_report* report, void* ws, hipStream_t st) {
+  SelectWs W;
+  carve_select(ws, M, N, K, n_batches, &W);
+  const int n_cand = n_alpha + 1;            // candidate 0 is the original order
+  const unsigned kb = (unsigned)((K + 255) / 256);
+  int rc;
+  for (int j = 0; j < n_alpha; ++j) {
+    hipLaunchKernelGGL(key_kernel, dim3(kb), dim3(256), 0, st, act_sumsq, w_sumsq, K, alphas[j], W.keys);
+    hipLaunchKernelGGL(rank_kernel, dim3(kb), dim3(256), 0, st, W.keys, (int)K, W.cands + (int64_t)j * K);
+  }
+  if ((rc = check_hip(hipGetLastError(), "key/rank kernels"))) return rc;
+  hipLaunchKernelGGL(count_moved_kernel, dim3(n_alpha), dim3(256), 0, st, W.cands, (int)K, W.moved);
+  double* sums = W.sums;
+  for (int b = 0; b < n_batches; ++b) {
+    rc = launch_quant_error(fmt, group, x_calib[b], M, (int)K, W.cands, n_cand, 1, act_ts, W.row_err, st);
+    if (rc) return rc;
+    hipLaunchKernelGGL(reduce_rows_kernel, dim3(n_cand), dim3(256), 0, st, W.row_err, M, n_cand,
+                       sums + (size_t)b * kMaxCand);
+  }
+  rc = launch_quant_error(fmt, group, w, N, (int)K, W.cands, n_cand, 1, w_ts, W.row_err, st);
+  if (rc) return rc;
+  hipLaunchKernelGGL(reduce_rows_kernel, dim3(n_cand), dim3(256), 0, st, W.row_err, N, n_cand,
+                     sums + (size_t)n_batches * kMaxCand);
+  double* tot = sums + (size_t)(n_batches + 1) * kMaxCand;
+  hipLaunchKernelGGL(sum2_kernel, dim3(1), dim3(256), 0, st, act_sumsq, w_sumsq, K, tot);
+  if ((rc = check_hip(hipGetLastError(), "error reduction kernels"))) return rc;
+
+  const size_t n_sums = (size_t)(n_batches + 1) * kMaxCand + 2;
+  std::vector<double> h(n_sums);
+  int h_moved[PQ_MAX_ALPHAS];
+  if ((rc = check_hip(hipMemcpyAsync(h.data(), sums, n_sums * 8, hipMemcpyDeviceToHost, st), "copy sums")))
+    return rc;
+  if ((rc = check_hip(hipMemcpyAsync(h_moved, W.moved, n_alpha * 4, hipMemcpyDeviceToHost, st), "copy flags")))
+    return rc;
+  if ((rc = check_hip(hipStreamSynchronize(st), "hipStreamSynchronize"))) return rc;
+
+  const double sum_x2 = h[n_sums - 2], sum_w2 = h[n_sums - 1];
+  double E[kMaxCand];
+  for (int c = 0; c < n_cand; ++c) {
+    double ex = 0.0;
+    for (int b = 0; b < n_batches; ++b) ex += h[(size_t)b * kMaxCand + c];
+    double ew = h[(size_t)n_batches * kMaxCand + c];
+    E[c] = ex / sum_x2 + ew / sum_w2;
+  }
+  int best = 0;
+  for (int j = 1; j < n_alpha; ++j)
+    if (E[1 + j] < E[1 + best]) best = j;         // first minimum: smallest alpha on ties
+  const double e_orig = E[0], e_best = E[1 + best];
+  const bool accepted = h_moved[best] != 0 && e_orig > 0.0 && ((e_orig - e_best) / e_orig > tau);
+  memset(report, 0, sizeof(*report));
+  report->accepted = accepted ? 1 : 0;
+  report->alpha_index = best;
+  report->e_orig = e_orig;
+  report->e_best = e_best;
+  for (int j = 0; j < n_alpha; ++j) report->e_cand[j] = E[1 + j];
+  report->sum_x2 = sum_x2;
+  report->sum_w2 = sum_w2;
+  if (accepted) {
+    rc = check_hip(hipMemcpyAsync(perm_out, W.cands + (int64_t)best * K, (size_t)K * 4,
+                                  hipMemcpyDeviceToDevice, st), "copy permutation");
+  } else {
+    hipLaunchKernelGGL(iota_kernel, dim3(kb), dim3(256), 0, st, perm_out, (int)K);
+    rc = check_hip(hipGetLastError(), "iota_kernel");
+  }
+  return rc;
+}
+
+}  // namespace pq

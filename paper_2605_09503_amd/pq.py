@@ -1,0 +1,221 @@
+"""Thin Python binding of the C-ABI library (include/permuquant.h).
+
+Argument marshalling only: every step of the path runs inside the library's HIP kernels.
+torch tensors provide device memory and the current stream; nothing is computed here and
+there is no CPU fallback -- if the library cannot be loaded the first call raises.
+Functions carry the names of the C entry points.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import List, Optional, Sequence
+
+import torch
+
+FMT_NVFP4, FMT_INT4, FMT_INT3 = 0, 1, 2
+OP_CALIB_MOMENTS, OP_SELECT_PERM, OP_QUANTIZE_WEIGHTS, OP_QUANTIZE_ACT, OP_QGEMM, OP_QUANT_ERROR = range(6)
+MAX_ALPHAS = 15
+DEFAULT_ALPHAS = (0.0, 0.2, 0.4, 0.6, 0.8, 1.0)
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "lib", "libpermuquant.so")
+_lib = None
+
+
+class PQError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__("permuquant error %d: %s" % (code, msg))
+        self.code = code
+
+
+class _Report(C.Structure):
+    _fields_ = [("accepted", C.c_int), ("alpha_index", C.c_int), ("e_orig", C.c_double),
+                ("e_best", C.c_double), ("e_cand", C.c_double * MAX_ALPHAS),
+                ("sum_x2", C.c_double), ("sum_w2", C.c_double)]
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load():
+    """Load libpermuquant.so (built in-tree by paper_2605_09503_amd.build). Raises if missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise PQError(-100, "library not built: %s (run python -m paper_2605_09503_amd.build)" % _LIB_PATH)
+    lib = C.CDLL(_LIB_PATH)
+    vp, i64, i32, sz = C.c_void_p, C.c_int64, C.c_int, C.c_size_t
+    lib.pq_last_error.restype = C.c_char_p
+    lib.pq_last_error.argtypes = []
+    lib.pq_version.restype = i32
+    lib.pq_workspace_bytes.restype = sz
+    lib.pq_workspace_bytes.argtypes = [i32, i32, i32, i64, i64, i64, i32]
+    lib.pq_calib_moments.argtypes = [vp, i64, i64, i64, vp, vp, vp, sz, vp]
+    lib.pq_select_perm.argtypes = [i32, i32, vp, vp, i64, C.POINTER(vp), i32, i64, vp, i64,
+                                   C.c_float, C.c_float, C.POINTER(C.c_double), i32, C.c_double,
+                                   vp, C.POINTER(_Report), vp, sz, vp]
+    lib.pq_quant_error.argtypes = [i32, i32, vp, i64, i64, vp, C.c_float, vp, vp, sz, vp]
+    lib.pq_quantize_weights.argtypes = [i32, i32, vp, i64, i64, vp, vp, vp, vp, vp]
+    lib.pq_quantize_act.argtypes = [i32, i32, vp, i64, i64, i64, vp, vp, vp, vp, vp]
+    gemm_args = [i32, i32, vp, vp, vp, vp, vp, vp, i64, i64, i64, vp, i64, vp, sz, vp]
+    lib.pq_qgemm.argtypes = gemm_args
+    lib.pq_qgemm_f32.argtypes = gemm_args
+    for name in ("pq_calib_moments", "pq_select_perm", "pq_quant_error", "pq_quantize_weights",
+                 "pq_quantize_act", "pq_qgemm", "pq_qgemm_f32"):
+        getattr(lib, name).restype = i32
+    _lib = lib
+    return lib
+
+
+def _check(rc: int):
+    if rc != 0:
+        raise PQError(rc, load().pq_last_error().decode())
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def pq_last_error() -> str:
+    return load().pq_last_error().decode()
+
+
+def pq_version() -> int:
+    return load().pq_version()
+
+
+def pq_workspace_bytes(op: int, fmt: int, group: int, M: int, N: int, K: int, n_batches: int = 0) -> int:
+    return int(load().pq_workspace_bytes(op, fmt, group, M, N, K, n_batches))
+
+
+def _workspace(nbytes: int, device) -> Optional[torch.Tensor]:
+    if nbytes == 0:
+        return None
+    return torch.empty(nbytes, dtype=torch.uint8, device=device)
+
+
+def pq_calib_moments(x: torch.Tensor, sumsq: torch.Tensor, absmax: Optional[torch.Tensor] = None,
+                     workspace: Optional[torch.Tensor] = None, rows: Optional[int] = None,
+                     K: Optional[int] = None, ld: Optional[int] = None) -> None:
+    """sumsq[K] (float64, in/out) += column sums of squares of bf16 x[rows, ld]."""
+    rows = x.shape[0] if rows is None else rows
+    K = x.shape[1] if K is None else K
+    ld = x.stride(0) if ld is None else ld
+    if workspace is None:
+        workspace = _workspace(pq_workspace_bytes(OP_CALIB_MOMENTS, 0, 0, rows, 0, K), x.device)
+    _check(load().pq_calib_moments(_ptr(x), rows, K, ld, _ptr(sumsq), _ptr(absmax), _ptr(workspace),
+                                   0 if workspace is None else workspace.numel(), _stream()))
+
+
+@dataclass
+class SelectReport:
+    accepted: bool
+    alpha_index: int
+    e_orig: float
+    e_best: float
+    e_cand: List[float]
+    sum_x2: float
+    sum_w2: float
+
+
+def pq_select_perm(fmt: int, group: int, act_sumsq: torch.Tensor, w_sumsq: torch.Tensor,
+                   x_calib: Sequence[torch.Tensor], w: torch.Tensor, act_tensor_scale: float,
+                   w_tensor_scale: float, perm_out: torch.Tensor,
+                   alphas: Sequence[float] = DEFAULT_ALPHAS, tau: float = 0.0,
+                   workspace: Optional[torch.Tensor] = None) -> SelectReport:
+    M, K = x_calib[0].shape
+    N = w.shape[0]
+    nb = len(x_calib)
+    if workspace is None:
+        workspace = _workspace(pq_workspace_bytes(OP_SELECT_PERM, fmt, group, M, N, K, nb), w.device)
+    ptrs = (C.c_void_p * nb)(*[xb.data_ptr() for xb in x_calib])
+    al = (C.c_double * len(alphas))(*[float(a) for a in alphas])
+    rep = _Report()
+    _check(load().pq_select_perm(fmt, group, _ptr(act_sumsq), _ptr(w_sumsq), K, ptrs, nb, M, _ptr(w), N,
+                                 float(act_tensor_scale), float(w_tensor_scale), al, len(alphas),
+                                 float(tau), _ptr(perm_out), C.byref(rep), _ptr(workspace),
+                                 0 if workspace is None else workspace.numel(), _stream()))
+    return SelectReport(bool(rep.accepted), rep.alpha_index, rep.e_orig, rep.e_best,
+                        [rep.e_cand[j] for j in range(len(alphas))], rep.sum_x2, rep.sum_w2)
+
+
+def pq_quant_error(fmt: int, group: int, x: torch.Tensor, perm: Optional[torch.Tensor],
+                   tensor_scale: float, err_out: torch.Tensor,
+                   workspace: Optional[torch.Tensor] = None) -> None:
+    rows, K = x.shape
+    if workspace is None:
+        workspace = _workspace(pq_workspace_bytes(OP_QUANT_ERROR, fmt, group, rows, 0, K), x.device)
+    _check(load().pq_quant_error(fmt, group, _ptr(x), rows, K, _ptr(perm), float(tensor_scale),
+                                 _ptr(err_out), _ptr(workspace),
+                                 0 if workspace is None else workspace.numel(), _stream()))
+
+
+def pq_quantize_weights(fmt: int, group: int, w: torch.Tensor, perm: Optional[torch.Tensor],
+                        codes: torch.Tensor, scales: torch.Tensor, tensor_scale_out: torch.Tensor) -> None:
+    N, K = w.shape
+    _check(load().pq_quantize_weights(fmt, group, _ptr(w), N, K, _ptr(perm), _ptr(codes), _ptr(scales),
+                                      _ptr(tensor_scale_out), _stream()))
+
+
+def pq_quantize_act(fmt: int, group: int, x: torch.Tensor, perm: Optional[torch.Tensor],
+                    tensor_scale: Optional[torch.Tensor], codes: torch.Tensor, scales: torch.Tensor,
+                    M: Optional[int] = None, K: Optional[int] = None, ld: Optional[int] = None) -> None:
+    M = x.shape[0] if M is None else M
+    K = x.shape[1] if K is None else K
+    ld = x.stride(0) if ld is None else ld
+    _check(load().pq_quantize_act(fmt, group, _ptr(x), M, K, ld, _ptr(perm), _ptr(tensor_scale),
+                                  _ptr(codes), _ptr(scales), _stream()))
+
+
+def _gemm(fn, fmt, group, a_codes, a_scales, a_ts, w_codes, w_scales, w_ts, y, workspace, M, N, K, ldy):
+    M = a_codes.shape[0] if M is None else M
+    K = a_codes.shape[1] * 2 if K is None else K
+    N = w_codes.shape[0] if N is None else N
+    ldy = y.stride(0) if ldy is None else ldy
+    if workspace is None:
+        workspace = _workspace(pq_workspace_bytes(OP_QGEMM, fmt, group, M, N, K), a_codes.device)
+    _check(fn(fmt, group, _ptr(a_codes), _ptr(a_scales), _ptr(a_ts), _ptr(w_codes), _ptr(w_scales),
+              _ptr(w_ts), M, N, K, _ptr(y), ldy, _ptr(workspace),
+              0 if workspace is None else workspace.numel(), _stream()))
+
+
+def pq_qgemm(fmt: int, group: int, a_codes, a_scales, a_tensor_scale, w_codes, w_scales,
+             w_tensor_scale, y: torch.Tensor, workspace: Optional[torch.Tensor] = None,
+             M=None, N=None, K=None, ldy=None) -> None:
+    """y[M, N] (bf16) = dequant(A) @ dequant(W)^T."""
+    _gemm(load().pq_qgemm, fmt, group, a_codes, a_scales, a_tensor_scale, w_codes, w_scales,
+          w_tensor_scale, y, workspace, M, N, K, ldy)
+
+
+def pq_qgemm_f32(fmt: int, group: int, a_codes, a_scales, a_tensor_scale, w_codes, w_scales,
+                 w_tensor_scale, y: torch.Tensor, workspace: Optional[torch.Tensor] = None,
+                 M=None, N=None, K=None, ldy=None) -> None:
+    """Same product, fp32 output (accumulator before the bf16 rounding)."""
+    _gemm(load().pq_qgemm_f32, fmt, group, a_codes, a_scales, a_tensor_scale, w_codes, w_scales,
+          w_tensor_scale, y, workspace, M, N, K, ldy)
+
+
+# ------------------------------------------------------------------------ allocation helpers
+def scale_dtype(fmt: int):
+    return torch.uint8 if fmt == FMT_NVFP4 else torch.float32
+
+
+def alloc_quantized(fmt: int, group: int, rows: int, K: int, device="cuda"):
+    """(codes, scales) buffers in the stored layout."""
+    codes = torch.empty((rows, K // 2), dtype=torch.uint8, device=device)
+    scales = torch.empty((rows, K // group), dtype=scale_dtype(fmt), device=device)
+    return codes, scales
+
+
+def bf16_from_bits(bits_u16, device="cuda") -> torch.Tensor:
+    """numpy uint16 bit patterns -> bf16 tensor on the device (no value conversion)."""
+    import numpy as np
+    t = torch.from_numpy(np.ascontiguousarray(bits_u16).view(np.int16))
+    return t.to(device).view(torch.bfloat16)

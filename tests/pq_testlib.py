@@ -1,0 +1,58 @@
+"""Helpers shared by the parity tests: run the oracle and the GPU library on the same bits."""
+from __future__ import annotations
+
+import numpy as np
+
+from oracle import calib as OC
+from oracle import formats as OF
+from oracle import gemm as OG
+from oracle import quantize as OQ
+
+# tolerances of the parity bar
+GEMM_F32_RTOL = 1e-4        # fp32-accumulator output vs fp64 reference, on |y_ref| > GEMM_ABS_FLOOR
+GEMM_ABS_FLOOR = 1e-2
+MOMENTS_RTOL = 1e-12
+ERRSUM_RTOL = 1e-10
+
+
+def oracle_quantize_bits(fmt, g, bits_u16, perm=None, tensor_scale=None):
+    """bf16 bits [rows, K] -> (packed codes u8 [rows, K/2], scales, quant tuple)."""
+    x = OF.bf16_bits_to_f64(bits_u16)
+    if perm is not None:
+        x = x[:, np.asarray(perm)]
+    q = OQ.quantize(fmt, g, x, tensor_scale)
+    return OQ.packed_codes(fmt, q), q.scale, q
+
+
+def bf16_ulp_distance(bits_a, bits_b):
+    """Distance in bf16 units in the last place between two arrays of bf16 bit patterns."""
+    def key(b):
+        b = b.astype(np.int32)
+        return np.where(b & 0x8000, -(b & 0x7FFF), b & 0x7FFF)
+    return np.abs(key(np.asarray(bits_a)) - key(np.asarray(bits_b)))
+
+
+def gemm_f32_check(y_gpu, y_ref, label=""):
+    """max relative error over |y_ref| > floor, plus an absolute check below the floor."""
+    y_gpu = np.asarray(y_gpu, dtype=np.float64)
+    big = np.abs(y_ref) > GEMM_ABS_FLOOR
+    rel = np.abs(y_gpu[big] - y_ref[big]) / np.abs(y_ref[big])
+    max_rel = float(rel.max()) if rel.size else 0.0
+    small_abs = float(np.abs(y_gpu[~big] - y_ref[~big]).max()) if (~big).any() else 0.0
+    assert max_rel <= GEMM_F32_RTOL, "%s max rel err %.3e" % (label, max_rel)
+    assert small_abs <= GEMM_F32_RTOL * GEMM_ABS_FLOOR * 10, "%s abs err %.3e below floor" % (label, small_abs)
+    return max_rel
+
+
+def gemm_bf16_check(y_bits_gpu, y_ref, label=""):
+    """bf16 output equals bf16_rne(y_ref) or its neighbour."""
+    ref_bits = OG.bf16_round(y_ref)
+    d = bf16_ulp_distance(y_bits_gpu, ref_bits)
+    # tiny outputs: fp32 accumulation noise can exceed one bf16 ulp of a near-zero result
+    big = np.abs(y_ref) > GEMM_ABS_FLOOR
+    assert d[big].max(initial=0) <= 1, "%s bf16 output off by %d ulp" % (label, int(d[big].max()))
+    ref_f = OF.bf16_bits_to_f64(ref_bits)
+    got_f = OF.bf16_bits_to_f64(np.asarray(y_bits_gpu))
+    # below the floor: the fp32 path's absolute allowance plus one bf16 ulp at the floor (2^-14)
+    assert np.all(np.abs(got_f[~big] - ref_f[~big]) <= GEMM_F32_RTOL * GEMM_ABS_FLOOR * 10 + 2.0 ** -14), label
+    return float((d[big] == 0).mean()) if big.any() else 1.0

@@ -1,0 +1,142 @@
+"""The C-ABI library loads, exports what include/permuquant.h declares, and rejects bad
+arguments on the host before anything is launched (no GPU needed: no valid call is made)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2605_09503_amd import pq
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "permuquant.h")
+
+PQ_ERR_NULL, PQ_ERR_SHAPE, PQ_ERR_FORMAT, PQ_ERR_WORKSPACE = -1, -2, -3, -4
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(pq.lib_path()):
+        from paper_2605_09503_amd import build
+        build.build(verbose=False)
+    return pq.load()
+
+
+def _declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(pq_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_functions_are_exported(lib):
+    names = _declared_functions()
+    assert {"pq_calib_moments", "pq_select_perm", "pq_quantize_weights", "pq_quantize_act",
+            "pq_qgemm"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), "missing export " + n
+    assert lib.pq_version() >= 100
+    assert isinstance(pq.pq_last_error(), str)
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    monkeypatch.setattr(pq, "_lib", None)
+    monkeypatch.setattr(pq, "_LIB_PATH", "/nonexistent/libpermuquant.so")
+    with pytest.raises(pq.PQError):
+        pq.load()
+
+
+FAKE = C.c_void_p(0x1000)          # non-NULL, 16-byte aligned, never dereferenced on the host
+
+
+def test_calib_moments_validation(lib):
+    f = lib.pq_calib_moments
+    assert f(None, 8, 64, 64, FAKE, None, FAKE, 1 << 20, None) == PQ_ERR_NULL
+    assert f(FAKE, 8, 64, 64, None, None, FAKE, 1 << 20, None) == PQ_ERR_NULL
+    assert f(FAKE, 0, 64, 64, FAKE, None, FAKE, 1 << 20, None) == PQ_ERR_SHAPE
+    assert f(FAKE, 8, 60, 64, FAKE, None, FAKE, 1 << 20, None) == PQ_ERR_SHAPE      # K % 8
+    assert f(FAKE, 8, 64, 32, FAKE, None, FAKE, 1 << 20, None) == PQ_ERR_SHAPE      # ld < K
+    assert f(C.c_void_p(0x1004), 8, 64, 64, FAKE, None, FAKE, 1 << 20, None) == PQ_ERR_SHAPE
+    assert f(FAKE, 8, 64, 64, FAKE, None, None, 0, None) == PQ_ERR_WORKSPACE
+    assert f(FAKE, 8, 64, 64, FAKE, None, FAKE, 8, None) == PQ_ERR_WORKSPACE
+    assert "workspace" in pq.pq_last_error()
+
+
+def test_quantize_validation(lib):
+    qa = lib.pq_quantize_act
+    assert qa(pq.FMT_NVFP4, 16, None, 4, 64, 64, None, FAKE, FAKE, FAKE, None) == PQ_ERR_NULL
+    assert qa(pq.FMT_NVFP4, 16, FAKE, 4, 64, 64, None, None, FAKE, FAKE, None) == PQ_ERR_NULL   # no T
+    assert qa(7, 16, FAKE, 4, 64, 64, None, FAKE, FAKE, FAKE, None) == PQ_ERR_FORMAT
+    assert qa(pq.FMT_NVFP4, 32, FAKE, 4, 64, 64, None, FAKE, FAKE, FAKE, None) == PQ_ERR_FORMAT
+    assert qa(pq.FMT_INT4, 16, FAKE, 4, 64, 64, None, None, FAKE, FAKE, None) == PQ_ERR_FORMAT
+    assert qa(pq.FMT_INT3, 48, FAKE, 4, 96, 96, None, None, FAKE, FAKE, None) == PQ_ERR_FORMAT
+    assert qa(pq.FMT_INT4, 64, FAKE, 4, 96, 96, None, None, FAKE, FAKE, None) == PQ_ERR_SHAPE    # K % g
+    assert qa(pq.FMT_INT4, 64, FAKE, 0, 64, 64, None, None, FAKE, FAKE, None) == PQ_ERR_SHAPE
+    assert qa(pq.FMT_INT4, 64, FAKE, 4, 64, 32, None, None, FAKE, FAKE, None) == PQ_ERR_SHAPE    # ld < K
+    assert qa(pq.FMT_INT4, 64, FAKE, 4, -64, 64, None, None, FAKE, FAKE, None) == PQ_ERR_SHAPE
+    qw = lib.pq_quantize_weights
+    assert qw(pq.FMT_INT4, 64, FAKE, 4, 64, None, FAKE, FAKE, None, None) == PQ_ERR_NULL
+    assert qw(pq.FMT_INT4, 64, FAKE, 4, 65, None, FAKE, FAKE, FAKE, None) == PQ_ERR_SHAPE
+    assert qw(pq.FMT_INT4, 64, FAKE, -1, 64, None, FAKE, FAKE, FAKE, None) == PQ_ERR_SHAPE
+
+
+def test_select_and_error_validation(lib):
+    f = lib.pq_select_perm
+    ptrs = (C.c_void_p * 1)(0x2000)
+    al = (C.c_double * 2)(0.0, 1.0)
+    rep = pq._Report()
+    ok_args = dict(fmt=pq.FMT_INT4, group=64, sa=FAKE, sw=FAKE, K=128, xs=ptrs, nb=1, M=8, w=FAKE, N=8,
+                   ta=1.0, tw=1.0, al=al, na=2, tau=0.0, out=FAKE, rep=C.byref(rep), ws=FAKE,
+                   wsb=1 << 30, st=None)
+
+    def call(**kw):
+        a = dict(ok_args)
+        a.update(kw)
+        return f(a["fmt"], a["group"], a["sa"], a["sw"], a["K"], a["xs"], a["nb"], a["M"], a["w"], a["N"],
+                 a["ta"], a["tw"], a["al"], a["na"], a["tau"], a["out"], a["rep"], a["ws"], a["wsb"], a["st"])
+
+    assert call(sa=None) == PQ_ERR_NULL
+    assert call(out=None) == PQ_ERR_NULL
+    assert call(na=0) == PQ_ERR_SHAPE
+    assert call(na=16) == PQ_ERR_SHAPE
+    assert call(nb=0) == PQ_ERR_SHAPE
+    assert call(K=100) == PQ_ERR_SHAPE
+    assert call(group=48) == PQ_ERR_FORMAT
+    assert call(al=(C.c_double * 2)(0.0, 1.5)) == PQ_ERR_SHAPE
+    assert call(tau=float("nan")) == PQ_ERR_SHAPE
+    assert call(xs=(C.c_void_p * 1)(None)) == PQ_ERR_NULL
+    assert call(wsb=16) == PQ_ERR_WORKSPACE
+    assert call(ws=None) == PQ_ERR_WORKSPACE
+    e = lib.pq_quant_error
+    assert e(pq.FMT_INT3, 32, None, 4, 64, None, 1.0, FAKE, FAKE, 1 << 20, None) == PQ_ERR_NULL
+    assert e(pq.FMT_INT3, 32, FAKE, 4, 64, None, 1.0, FAKE, FAKE, 8, None) == PQ_ERR_WORKSPACE
+    assert e(pq.FMT_INT3, 32, FAKE, 4, 72, None, 1.0, FAKE, FAKE, 1 << 20, None) == PQ_ERR_SHAPE
+
+
+def test_qgemm_validation(lib):
+    for f in (lib.pq_qgemm, lib.pq_qgemm_f32):
+        def call(fmt=pq.FMT_INT4, group=64, a=FAKE, sa=FAKE, ta=None, w=FAKE, sw=FAKE, tw=None, M=8, N=8,
+                 K=128, y=FAKE, ldy=8, ws=FAKE, wsb=1 << 30):
+            return f(fmt, group, a, sa, ta, w, sw, tw, M, N, K, y, ldy, ws, wsb, None)
+        assert call(a=None) == PQ_ERR_NULL
+        assert call(y=None) == PQ_ERR_NULL
+        assert call(fmt=pq.FMT_NVFP4, group=16) == PQ_ERR_NULL            # tensor scales missing
+        assert call(fmt=pq.FMT_NVFP4, group=16, ta=FAKE, tw=FAKE, K=48) == PQ_ERR_SHAPE   # K % 32
+        assert call(M=0) == PQ_ERR_SHAPE
+        assert call(ldy=4) == PQ_ERR_SHAPE
+        assert call(ldy=9, N=8) == PQ_ERR_SHAPE
+        assert call(group=16) == PQ_ERR_FORMAT
+        assert call(wsb=0) == PQ_ERR_WORKSPACE
+        assert call(ws=None) == PQ_ERR_WORKSPACE
+        assert call(a=C.c_void_p(0x1008)) == PQ_ERR_SHAPE
+
+
+def test_workspace_sizes(lib):
+    w = pq.pq_workspace_bytes
+    assert w(pq.OP_QGEMM, pq.FMT_NVFP4, 16, 4608, 9216, 3072) == 0
+    need = w(pq.OP_QGEMM, pq.FMT_INT4, 64, 4608, 3072, 3072)
+    assert need >= (4608 + 3072) * (3072 // 64) * 2 + (4608 + 3072) * 4
+    assert w(pq.OP_CALIB_MOMENTS, 0, 0, 4608, 0, 3072) >= 3072 * 8
+    assert w(pq.OP_SELECT_PERM, pq.FMT_INT4, 64, 4608, 3072, 3072, 8) > 15 * 3072 * 4
+    assert w(pq.OP_QUANT_ERROR, pq.FMT_INT4, 64, 100, 0, 64) >= 800
+    assert w(pq.OP_QGEMM, pq.FMT_INT4, 64, 0, 0, 0) == 0
+    assert w(99, 0, 0, 1, 1, 1) == 0

@@ -1,0 +1,356 @@
+"""GPU parity: the HIP library against the CPU oracle on the same seeded bits, through the
+C ABI.  Sizes are small enough for the oracle to finish in seconds while still spanning
+several tiles and ragged tails.  Codes, scales, permutations: bit-exact.  Moments: 1e-12.
+Error sums: 1e-10.  GEMM: see pq_testlib."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import calib as OC
+from oracle import formats as OF
+from oracle import gemm as OG
+from oracle import quantize as OQ
+from paper_2605_09503_amd import pq, synth
+
+import pq_testlib as T
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda"
+
+FMTS = [(pq.FMT_NVFP4, 16), (pq.FMT_INT4, 64), (pq.FMT_INT4, 32), (pq.FMT_INT3, 32),
+        (pq.FMT_INT4, 128), (pq.FMT_INT3, 256)]
+
+
+def _say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def _rand_bits(rng, rows, K, spread=2.0, outliers=4):
+    chan = np.exp(spread * 0.5 * rng.standard_normal(K))
+    if outliers:
+        chan[rng.choice(K, outliers, replace=False)] *= 30.0
+    v = rng.standard_normal((rows, K)) * chan[None, :]
+    return synth.f64_to_bf16_bits(v)
+
+
+def _to_dev(bits):
+    return pq.bf16_from_bits(bits, DEV)
+
+
+# ------------------------------------------------------------------------------ moments
+
+@pytest.mark.parametrize("rows,K,ld", [(256, 512, 512), (1000, 264, 264), (37, 1032, 1040), (4608, 3072, 3072),
+                                        (1, 8, 8)])
+def test_calib_moments(rows, K, ld):
+    _say("moments rows=%d K=%d ld=%d" % (rows, K, ld))
+    rng = np.random.default_rng(100 + rows)
+    bits = _rand_bits(rng, rows, ld)
+    x = _to_dev(bits)
+    sumsq = torch.zeros(K, dtype=torch.float64, device=DEV)
+    absmax = torch.zeros(1, dtype=torch.float32, device=DEV)
+    pq.pq_calib_moments(x, sumsq, absmax, rows=rows, K=K, ld=ld)
+    pq.pq_calib_moments(x, sumsq, absmax, rows=rows, K=K, ld=ld)        # accumulates (in/out)
+    torch.cuda.synchronize()
+    xf = OF.bf16_bits_to_f64(bits)[:, :K]
+    ref = 2.0 * OC.column_sumsq(xf)
+    got = sumsq.cpu().numpy()
+    assert np.all(np.abs(got - ref) <= T.MOMENTS_RTOL * ref)
+    assert absmax.item() == np.float32(OC.absmax(xf))
+    # determinism: a second run gives the same bits
+    s2 = torch.zeros(K, dtype=torch.float64, device=DEV)
+    pq.pq_calib_moments(x, s2, None, rows=rows, K=K, ld=ld)
+    pq.pq_calib_moments(x, s2, None, rows=rows, K=K, ld=ld)
+    assert torch.equal(s2, sumsq)
+
+
+# ---------------------------------------------------------------------------- quantizers
+
+def _quantize_act_gpu(fmt, g, x, M, K, ld, perm, T_dev):
+    codes, scales = pq.alloc_quantized(fmt, g, M, K, DEV)
+    codes.fill_(0xAB)
+    pq.pq_quantize_act(fmt, g, x, perm, T_dev, codes, scales, M=M, K=K, ld=ld)
+    torch.cuda.synchronize()
+    return codes.cpu().numpy(), scales.cpu().numpy()
+
+
+@pytest.mark.parametrize("fmt,g", FMTS)
+@pytest.mark.parametrize("M,K", [(256, 512), (67, 768), (1, 256), (515, 2304)])
+def test_quantize_act_contiguous(fmt, g, M, K):
+    if K % g:
+        pytest.skip("K not a multiple of the group")
+    _say("quantize_act fmt=%d g=%d M=%d K=%d" % (fmt, g, M, K))
+    rng = np.random.default_rng(200 + M + K + g)
+    bits = _rand_bits(rng, M, K)
+    bits[0, :g] = 0                      # an all-zero group
+    bits[M - 1, -1] = 0x8000             # -0.0
+    x = _to_dev(bits)
+    ts = OQ.nvfp4_tensor_scale(OC.absmax(OF.bf16_bits_to_f64(bits))) if fmt == pq.FMT_NVFP4 else None
+    T_dev = torch.tensor([ts], dtype=torch.float32, device=DEV) if ts is not None else None
+    codes, scales = _quantize_act_gpu(fmt, g, x, M, K, K, None, T_dev)
+    ref_codes, ref_scales, _ = T.oracle_quantize_bits(fmt, g, bits, None, ts)
+    np.testing.assert_array_equal(scales.view(ref_scales.dtype), ref_scales)
+    np.testing.assert_array_equal(codes, ref_codes)
+
+
+@pytest.mark.parametrize("fmt,g", FMTS[:4])
+def test_quantize_act_strided_and_permuted(fmt, g):
+    M, K, ld = 131, 1024, 1040
+    _say("quantize_act strided/perm fmt=%d g=%d" % (fmt, g))
+    rng = np.random.default_rng(300 + g)
+    bits = _rand_bits(rng, M, ld)
+    x = _to_dev(bits)
+    xb = bits[:, :K]
+    ts = OQ.nvfp4_tensor_scale(OC.absmax(OF.bf16_bits_to_f64(xb))) if fmt == pq.FMT_NVFP4 else None
+    T_dev = torch.tensor([ts], dtype=torch.float32, device=DEV) if ts is not None else None
+    codes, scales = _quantize_act_gpu(fmt, g, x, M, K, ld, None, T_dev)
+    ref_codes, ref_scales, _ = T.oracle_quantize_bits(fmt, g, xb, None, ts)
+    np.testing.assert_array_equal(codes, ref_codes)
+    np.testing.assert_array_equal(scales.view(ref_scales.dtype), ref_scales)
+    perm = rng.permutation(K).astype(np.int32)
+    perm_dev = torch.from_numpy(perm).to(DEV)
+    codes, scales = _quantize_act_gpu(fmt, g, x, M, K, ld, perm_dev, T_dev)
+    ref_codes, ref_scales, _ = T.oracle_quantize_bits(fmt, g, xb, perm, ts)
+    np.testing.assert_array_equal(codes, ref_codes)
+    np.testing.assert_array_equal(scales.view(ref_scales.dtype), ref_scales)
+
+
+def test_quantize_act_nvfp4_live_values_above_calibration_max():
+    # static tensor scale from a smaller calibration maximum: block scales and codes saturate
+    M, K = 64, 256
+    rng = np.random.default_rng(310)
+    bits = _rand_bits(rng, M, K)
+    xf = OF.bf16_bits_to_f64(bits)
+    ts = OQ.nvfp4_tensor_scale(OC.absmax(xf) / 37.0)
+    T_dev = torch.tensor([ts], dtype=torch.float32, device=DEV)
+    codes, scales = _quantize_act_gpu(pq.FMT_NVFP4, 16, _to_dev(bits), M, K, K, None, T_dev)
+    ref_codes, ref_scales, _ = T.oracle_quantize_bits(pq.FMT_NVFP4, 16, bits, None, ts)
+    assert ref_scales.max() == 126
+    np.testing.assert_array_equal(codes, ref_codes)
+    np.testing.assert_array_equal(scales, ref_scales)
+    # zero tensor scale (all-zero calibration set): everything quantizes to signed zero
+    T0 = torch.zeros(1, dtype=torch.float32, device=DEV)
+    codes, scales = _quantize_act_gpu(pq.FMT_NVFP4, 16, _to_dev(bits), M, K, K, None, T0)
+    ref_codes, ref_scales, _ = T.oracle_quantize_bits(pq.FMT_NVFP4, 16, bits, None, np.float32(0))
+    np.testing.assert_array_equal(codes, ref_codes)
+    np.testing.assert_array_equal(scales, ref_scales)
+
+
+@pytest.mark.parametrize("fmt,g", FMTS[:4])
+@pytest.mark.parametrize("use_perm", [False, True])
+def test_quantize_weights(fmt, g, use_perm):
+    N, K = 203, 1280
+    _say("quantize_weights fmt=%d g=%d perm=%s" % (fmt, g, use_perm))
+    rng = np.random.default_rng(400 + g + use_perm)
+    bits = synth.f64_to_bf16_bits(0.02 * rng.standard_normal((N, K)) * np.exp(0.3 * rng.standard_normal(K)))
+    w = _to_dev(bits)
+    perm = rng.permutation(K).astype(np.int32) if use_perm else None
+    perm_dev = torch.from_numpy(perm).to(DEV) if use_perm else None
+    codes, scales = pq.alloc_quantized(fmt, g, N, K, DEV)
+    ts_out = torch.full((1,), -1.0, dtype=torch.float32, device=DEV)
+    pq.pq_quantize_weights(fmt, g, w, perm_dev, codes, scales, ts_out)
+    torch.cuda.synchronize()
+    if fmt == pq.FMT_NVFP4:
+        ts = OQ.nvfp4_tensor_scale(OC.absmax(OF.bf16_bits_to_f64(bits)))
+        assert np.float32(ts_out.item()) == ts
+    else:
+        ts = None
+        assert ts_out.item() == 1.0
+    ref_codes, ref_scales, _ = T.oracle_quantize_bits(fmt, g, bits, perm, ts)
+    np.testing.assert_array_equal(codes.cpu().numpy(), ref_codes)
+    np.testing.assert_array_equal(scales.cpu().numpy().view(ref_scales.dtype), ref_scales)
+
+
+# ------------------------------------------------------------------------------ selection
+
+def _layer_on_gpu(cfg):
+    st, calib, test = synth.make_layer(cfg)
+    xs = [_to_dev(b) for b in calib]
+    w = _to_dev(st.w_bits)
+    return st, calib, test, xs, w
+
+
+def _gpu_moments(xs, w, K):
+    sa = torch.zeros(K, dtype=torch.float64, device=DEV)
+    sw = torch.zeros(K, dtype=torch.float64, device=DEV)
+    amax_a = torch.zeros(1, dtype=torch.float32, device=DEV)
+    amax_w = torch.zeros(1, dtype=torch.float32, device=DEV)
+    for xb in xs:
+        pq.pq_calib_moments(xb, sa, amax_a)
+    pq.pq_calib_moments(w, sw, amax_w)
+    torch.cuda.synchronize()
+    return sa, sw, amax_a.item(), amax_w.item()
+
+
+@pytest.mark.parametrize("name,fmt,g,M,N,K,nb", [
+    ("c0", pq.FMT_NVFP4, 16, 256, 512, 512, 4),
+    ("c1", pq.FMT_INT4, 64, 160, 192, 768, 3),
+    ("c2", pq.FMT_NVFP4, 16, 96, 128, 1024, 2),
+    ("c3down", pq.FMT_NVFP4, 16, 64, 96, 2048, 2),
+    ("c4", pq.FMT_INT3, 32, 200, 160, 640, 3),
+])
+def test_select_perm_matches_oracle(name, fmt, g, M, N, K, nb):
+    _say("select_perm %s fmt=%d g=%d M=%d N=%d K=%d" % (name, fmt, g, M, N, K))
+    base = synth.CONFIGS[name]
+    cfg = synth.scaled(base, M=M, N=N, K=K, n_calib=nb, n_outlier=min(base.n_outlier, K // 64))
+    st, calib, test, xs, w = _layer_on_gpu(cfg)
+    sa, sw, amax_a, amax_w = _gpu_moments(xs, w, K)
+    xs64 = [OF.bf16_bits_to_f64(b) for b in calib]
+    w64 = OF.bf16_bits_to_f64(st.w_bits)
+    ts_a = ts_w = 1.0
+    if fmt == pq.FMT_NVFP4:
+        ts_a = float(OQ.nvfp4_tensor_scale(max(OC.absmax(x) for x in xs64)))
+        ts_w = float(OQ.nvfp4_tensor_scale(OC.absmax(w64)))
+        assert np.float32(amax_a) == np.float32(max(OC.absmax(x) for x in xs64))
+    ref = OC.select_permutation(fmt, g, xs64, w64, act_tensor_scale=np.float32(ts_a) if fmt == pq.FMT_NVFP4 else None)
+    assert ref.min_key_gap > 1e-11, "ill-posed case (sort keys closer than the moments are accurate): reseed"
+    perm_out = torch.empty(K, dtype=torch.int32, device=DEV)
+    rep = pq.pq_select_perm(fmt, g, sa, sw, xs, w, ts_a, ts_w, perm_out)
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(rep.e_orig, ref.e_orig, rtol=T.ERRSUM_RTOL)
+    np.testing.assert_allclose(rep.e_cand, ref.e_cand, rtol=T.ERRSUM_RTOL)
+    margin = abs((ref.e_orig - ref.e_best) / ref.e_orig)
+    assert margin > 1e-6, "acceptance margin too small for a bit-exact comparison: reseed"
+    assert rep.accepted == ref.accepted
+    assert rep.alpha_index == ref.alpha_index
+    np.testing.assert_array_equal(perm_out.cpu().numpy(), ref.perm)
+    # acceptance never raises the calibration error
+    assert rep.e_best <= rep.e_orig or not rep.accepted
+    # tau above the realised gain rejects and returns the identity
+    rep2 = pq.pq_select_perm(fmt, g, sa, sw, xs, w, ts_a, ts_w, perm_out, tau=0.999)
+    torch.cuda.synchronize()
+    assert not rep2.accepted
+    np.testing.assert_array_equal(perm_out.cpu().numpy(), np.arange(K))
+
+
+def test_select_perm_candidates_and_ties():
+    # equal second moments: the sort must keep ascending channel index (stable)
+    K, M, N = 256, 32, 32
+    xb = np.tile(synth.f64_to_bf16_bits(np.repeat(2.0 ** -np.arange(K // 16), 16))[None, :], (M, 1))
+    wb = np.tile(synth.f64_to_bf16_bits(np.repeat(2.0 ** -np.arange(K // 16), 16))[None, :], (N, 1))
+    xs = [_to_dev(xb)]
+    w = _to_dev(wb)
+    sa, sw, _, _ = _gpu_moments(xs, w, K)
+    perm_out = torch.empty(K, dtype=torch.int32, device=DEV)
+    rep = pq.pq_select_perm(pq.FMT_INT4, 32, sa, sw, xs, w, 1.0, 1.0, perm_out)
+    torch.cuda.synchronize()
+    assert not rep.accepted          # every candidate is the identity
+    np.testing.assert_array_equal(perm_out.cpu().numpy(), np.arange(K))
+    ref = OC.select_permutation(pq.FMT_INT4, 32, [OF.bf16_bits_to_f64(xb)], OF.bf16_bits_to_f64(wb))
+    assert not ref.accepted
+    np.testing.assert_allclose(rep.e_cand, ref.e_cand, rtol=1e-10, atol=1e-300)
+
+
+@pytest.mark.parametrize("fmt,g", FMTS[:4])
+def test_quant_error(fmt, g):
+    rows, K = 77, 1024
+    rng = np.random.default_rng(500 + g)
+    bits = _rand_bits(rng, rows, K)
+    x = _to_dev(bits)
+    x64 = OF.bf16_bits_to_f64(bits)
+    ts = float(OQ.nvfp4_tensor_scale(OC.absmax(x64))) if fmt == pq.FMT_NVFP4 else 1.0
+    perm = rng.permutation(K).astype(np.int32)
+    out = torch.zeros(1, dtype=torch.float64, device=DEV)
+    for p in (None, perm):
+        pq.pq_quant_error(fmt, g, x, None if p is None else torch.from_numpy(p).to(DEV), ts, out)
+        torch.cuda.synchronize()
+        ref = OC.squared_error(fmt, g, x64, p, np.float32(ts) if fmt == pq.FMT_NVFP4 else None)
+        np.testing.assert_allclose(out.item(), ref, rtol=T.ERRSUM_RTOL)
+
+
+# ----------------------------------------------------------------------------------- GEMM
+
+def _gemm_case(fmt, g, M, N, K, seed, ldy_pad=0):
+    rng = np.random.default_rng(seed)
+    xb = _rand_bits(rng, M, K)
+    wb = synth.f64_to_bf16_bits(0.02 * rng.standard_normal((N, K)) * np.exp(0.3 * rng.standard_normal(K)))
+    x64, w64 = OF.bf16_bits_to_f64(xb), OF.bf16_bits_to_f64(wb)
+    if fmt == pq.FMT_NVFP4:
+        ta, tw = OQ.nvfp4_tensor_scale(OC.absmax(x64)), OQ.nvfp4_tensor_scale(OC.absmax(w64))
+    else:
+        ta = tw = None
+    qa = OQ.quantize(fmt, g, x64, ta)
+    qw = OQ.quantize(fmt, g, w64, tw)
+    y_ref = OG.dequant_product(fmt, g, qa, qw)
+    # GPU operands come from the GPU quantizers (already checked bit-exact above)
+    a_codes, a_scales = pq.alloc_quantized(fmt, g, M, K, DEV)
+    w_codes, w_scales = pq.alloc_quantized(fmt, g, N, K, DEV)
+    Ta = torch.tensor([ta if ta is not None else 1.0], dtype=torch.float32, device=DEV)
+    Tw = torch.empty(1, dtype=torch.float32, device=DEV)
+    pq.pq_quantize_act(fmt, g, _to_dev(xb), None, Ta, a_codes, a_scales)
+    pq.pq_quantize_weights(fmt, g, _to_dev(wb), None, w_codes, w_scales, Tw)
+    np.testing.assert_array_equal(a_codes.cpu().numpy(), OQ.packed_codes(fmt, qa))
+    np.testing.assert_array_equal(w_codes.cpu().numpy(), OQ.packed_codes(fmt, qw))
+    ldy = (N + 7) // 8 * 8 + ldy_pad
+    y32 = torch.full((M, ldy), 777.0, dtype=torch.float32, device=DEV)
+    y16 = torch.full((M, ldy), 777.0, dtype=torch.bfloat16, device=DEV)
+    pq.pq_qgemm_f32(fmt, g, a_codes, a_scales, Ta, w_codes, w_scales, Tw, y32, M=M, N=N, K=K, ldy=ldy)
+    pq.pq_qgemm(fmt, g, a_codes, a_scales, Ta, w_codes, w_scales, Tw, y16, M=M, N=N, K=K, ldy=ldy)
+    torch.cuda.synchronize()
+    y32h = y32.cpu().numpy()
+    y16h = y16.view(torch.int16).cpu().numpy().view(np.uint16)
+    rel = T.gemm_f32_check(y32h[:, :N], y_ref, "fmt=%d g=%d" % (fmt, g))
+    same = T.gemm_bf16_check(y16h[:, :N], y_ref, "fmt=%d g=%d" % (fmt, g))
+    # nothing written beyond column N
+    assert np.all(y32h[:, N:] == 777.0)
+    _say("  gemm fmt=%d g=%d %dx%dx%d: max rel %.2e, bf16 identical %.4f" % (fmt, g, M, N, K, rel, same))
+
+
+@pytest.mark.parametrize("fmt,g", FMTS)
+def test_qgemm_small_ragged(fmt, g):
+    # 128x128 tiles, several of them, ragged in M and N
+    K = 512 if g <= 128 else 768
+    _gemm_case(fmt, g, 200, 328, K, 600 + g)
+
+
+@pytest.mark.parametrize("fmt,g", FMTS[:4])
+def test_qgemm_large_tile_path(fmt, g):
+    # enough 256x256 tiles to select the large-tile kernel; ragged edges; odd tile count
+    _gemm_case(fmt, g, 2304 + 40, 3584 + 72, 256, 700 + g, ldy_pad=8)
+
+
+@pytest.mark.parametrize("fmt,g", FMTS[:4])
+def test_qgemm_tiny(fmt, g):
+    _gemm_case(fmt, g, 1, 8, 2 * max(g, 32), 800 + g)
+    _gemm_case(fmt, g, 33, 17, 64 if g <= 64 else g, 810 + g)
+
+
+def test_qgemm_int_exact_small_integers():
+    # all scales 1 (h = Q), codes in {-1, 0, 1}: the accumulator holds Q^2 times an exact small
+    # integer; the epilogue's two fp32 factors 2^E/Q each round once (<= 3 roundings in all)
+    M, N, K, g = 70, 90, 256, 64
+    rng = np.random.default_rng(900)
+    za = rng.integers(-1, 2, size=(M, K))
+    zw = rng.integers(-1, 2, size=(N, K))
+    a_codes = torch.from_numpy(OF.pack_nibbles(OF.int_to_nibble(za))).to(DEV)
+    w_codes = torch.from_numpy(OF.pack_nibbles(OF.int_to_nibble(zw))).to(DEV)
+    sa = torch.ones((M, K // g), dtype=torch.float32, device=DEV)
+    sw = torch.ones((N, K // g), dtype=torch.float32, device=DEV)
+    y = torch.zeros((M, 96), dtype=torch.float32, device=DEV)
+    pq.pq_qgemm_f32(pq.FMT_INT4, g, a_codes, sa, None, w_codes, sw, None, y, M=M, N=N, K=K, ldy=96)
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(y.cpu().numpy()[:, :N], (za @ zw.T).astype(np.float32), rtol=3 * 2.0 ** -24, atol=0)
+
+
+def test_qgemm_int_wide_scale_range():
+    # groups spanning 2^20 in magnitude inside one row stay exact in the fp16 operands
+    M, N, K, g = 64, 64, 512, 64
+    rng = np.random.default_rng(910)
+    scale_a = 2.0 ** rng.integers(-10, 10, size=K // g)
+    xb = synth.f64_to_bf16_bits(rng.standard_normal((M, K)) * np.repeat(scale_a, g)[None, :])
+    wb = synth.f64_to_bf16_bits(rng.standard_normal((N, K)) * np.repeat(scale_a[::-1], g)[None, :])
+    x64, w64 = OF.bf16_bits_to_f64(xb), OF.bf16_bits_to_f64(wb)
+    qa, qw = OQ.quantize(pq.FMT_INT4, g, x64), OQ.quantize(pq.FMT_INT4, g, w64)
+    y_ref = OG.dequant_product(pq.FMT_INT4, g, qa, qw)
+    a_codes, a_scales = pq.alloc_quantized(pq.FMT_INT4, g, M, K, DEV)
+    w_codes, w_scales = pq.alloc_quantized(pq.FMT_INT4, g, N, K, DEV)
+    one = torch.ones(1, dtype=torch.float32, device=DEV)
+    pq.pq_quantize_act(pq.FMT_INT4, g, _to_dev(xb), None, None, a_codes, a_scales)
+    pq.pq_quantize_weights(pq.FMT_INT4, g, _to_dev(wb), None, w_codes, w_scales, one)
+    y = torch.zeros((M, N), dtype=torch.float32, device=DEV)
+    pq.pq_qgemm_f32(pq.FMT_INT4, g, a_codes, a_scales, None, w_codes, w_scales, None, y)
+    torch.cuda.synchronize()
+    T.gemm_f32_check(y.cpu().numpy(), y_ref, "wide scale range")
