@@ -101,6 +101,13 @@ int pq_calib_moments(const void* x_bf16, int64_t rows, int64_t K, int64_t ld, do
                      float* absmax, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * NVFP4 per-tensor scale from a running absmax (the two-level reading of NVFP4 W4A4, paper
+ * Sec. 4.4): tensor_scale_out[0] = fl32(absmax[0] / 2688), 2688 = 448 * 6, so that the largest
+ * block scale lands on the E4M3 maximum.  Both pointers: float [1] device; may alias.
+ */
+int pq_tensor_scale(const float* absmax, float* tensor_scale_out, void* stream);
+
+/*
  * Permutation selection (paper Sec. 3.3: joint score Eq. 9, alpha grid search, acceptance rule).
  *
  * For every alpha_j: key_i = alpha_j * ln(act_sumsq[i]) + (1 - alpha_j) * ln(w_sumsq[i]) (a

@@ -81,6 +81,11 @@ int pq_calib_moments(const void* x, int64_t rows, int64_t K, int64_t ld, double*
   return launch_moments(x, rows, K, ld, sumsq, absmax, workspace, as_stream(stream));
 }
 
+int pq_tensor_scale(const float* absmax, float* tensor_scale_out, void* stream) {
+  if (!absmax || !tensor_scale_out) return fail(PQ_ERR_NULL, "pq_tensor_scale: NULL pointer");
+  return launch_tensor_scale(absmax, tensor_scale_out, as_stream(stream));
+}
+
 int pq_select_perm(pq_format fmt, int group, const double* act_sumsq, const double* w_sumsq,
                    int64_t K, const void* const* x_calib, int n_batches, int64_t M,
                    const void* w_bf16, int64_t N, float act_tensor_scale, float w_tensor_scale,

@@ -22,6 +22,8 @@
 // a lane ends up with 4 consecutive n for one m and stores 8 bytes of bf16 at once.
 // LDS rows are 128 bytes (64 fp16) in 16-byte pieces, piece index XOR (row & 7): conflict-free
 // for the 16-byte fragment reads and for the unpack writes.
+#include <stdlib.h>
+
 #include "pq_device.h"
 #include "pq_host.h"
 
@@ -32,34 +34,14 @@ typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef float float16_t __attribute__((ext_vector_type(16)));
 
 constexpr int kBK = 64;                 // K elements per step
-constexpr int kRowBytes = kBK * 2;      // fp16 row in LDS
+constexpr int kRowBytes = kBK * 2 + 16; // fp16 row in LDS, padded by one 16-byte piece: with 144-byte
+                                        // rows both the 16-byte fragment reads (rows 0..31 of a
+                                        // piece) and the unpack writes spread over all banks
 
 __device__ __forceinline__ half2_t as_h2(uint32_t u) { return __builtin_bit_cast(half2_t, u); }
 __device__ __forceinline__ uint32_t h2_bits(half2_t h) { return __builtin_bit_cast(uint32_t, h); }
 
 // ------------------------------------------------------------------------ operand unpack
-// Eight 4-bit codes (one dword) -> eight fp16 values times the group scale (sc = {s, s}).
-// The position of an element inside the group of eight only has to be the same for A and W.
-template <int FMT>
-__device__ __forceinline__ uint4 unpack8_scaled(uint32_t d, half2_t sc) {
-  uint4 o;
-  if constexpr (FMT == kNvfp4) {
-    o.x = h2_bits(__builtin_amdgcn_cvt_scalef32_pk_f16_fp4(d, 1.0f, 0) * sc);
-    o.y = h2_bits(__builtin_amdgcn_cvt_scalef32_pk_f16_fp4(d, 1.0f, 1) * sc);
-    o.z = h2_bits(__builtin_amdgcn_cvt_scalef32_pk_f16_fp4(d, 1.0f, 2) * sc);
-    o.w = h2_bits(__builtin_amdgcn_cvt_scalef32_pk_f16_fp4(d, 1.0f, 3) * sc);
-  } else {
-    // two's complement nibble z -> offset binary u = z + 8 -> fp16 1024 + u -> subtract 1032
-    const uint32_t x = d ^ 0x88888888u;
-    const half2_t off = {(_Float16)1032.0f, (_Float16)1032.0f};
-    o.x = h2_bits((as_h2((x & 0x000F000Fu) | 0x64006400u) - off) * sc);
-    o.y = h2_bits((as_h2(((x >> 4) & 0x000F000Fu) | 0x64006400u) - off) * sc);
-    o.z = h2_bits((as_h2(((x >> 8) & 0x000F000Fu) | 0x64006400u) - off) * sc);
-    o.w = h2_bits((as_h2(((x >> 12) & 0x000F000Fu) | 0x64006400u) - off) * sc);
-  }
-  return o;
-}
-
 // Per-thread slice of a tile row: 32 consecutive k (16 bytes of codes) plus its scales.
 struct Slice {
   uint4 codes;
@@ -72,50 +54,87 @@ struct ScaleSrc {
   const uint16_t* f16;      // INT: normalised group maxima, [rows, K/G]
 };
 
+// Branch-free load of one slice.  `codes_row` / `sc_row` point at a valid row (the caller
+// clamps the row index) and k0 beyond K is redirected to the row start, so the address is
+// always valid.  The loaded registers are not touched here (a use would make the wave wait for
+// the load at once); a slice that is out of range is neutralised when it is unpacked, by
+// zeroing its scale (see slice_scales).
 template <int FMT, int G>
-__device__ __forceinline__ Slice load_slice(const uint8_t* __restrict__ codes, const ScaleSrc& sc,
-                                            int row, int rows, int K, int k0) {
+__device__ __forceinline__ Slice load_slice(const uint8_t* __restrict__ codes_row,
+                                            const void* __restrict__ sc_row, int K, int k0) {
+  const int kk = k0 < K ? k0 : 0;
   Slice s;
-  if (row < rows && k0 < K) {
-    s.codes = *reinterpret_cast<const uint4*>(codes + (int64_t)row * (K / 2) + k0 / 2);
-    if constexpr (FMT == kNvfp4) {
-      s.sc = *reinterpret_cast<const uint16_t*>(sc.e4m3 + (int64_t)row * (K / 16) + k0 / 16);
-    } else {
-      s.sc = sc.f16[(int64_t)row * (K / G) + k0 / G];
-    }
+  s.codes = *reinterpret_cast<const uint4*>(codes_row + kk / 2);
+  if constexpr (FMT == kNvfp4) {
+    s.sc = *reinterpret_cast<const uint16_t*>(reinterpret_cast<const uint8_t*>(sc_row) + kk / 16);
   } else {
-    s.codes = make_uint4(0, 0, 0, 0);     // zero codes: contribute nothing
-    s.sc = 0;
-    if constexpr (FMT != kNvfp4) s.codes = make_uint4(0, 0, 0, 0);
+    s.sc = reinterpret_cast<const uint16_t*>(sc_row)[kk / G];
   }
   return s;
 }
 
+// Scale pair(s) handed to unpack_pair.  INT carries {h, h} and {-24 h, -24 h} (see below).
+struct PairScale {
+  half2_t mul, add;
+};
+
+// {s, s} pairs of the two group scales a slice can touch; all zero when the slice is out of
+// range (row beyond the matrix or k beyond K), so that whatever codes were loaded contribute 0
 template <int FMT>
-__device__ __forceinline__ void unpack_slice(const Slice& s, uint4 (&out)[4]) {
-  half2_t s0, s1;
+__device__ __forceinline__ void slice_scales(const Slice& s, bool ok, PairScale& p0, PairScale& p1) {
   if constexpr (FMT == kNvfp4) {
     // E4M3 byte b -> fp16: bits (b << 7) read as fp16 are value * 2^-8, subnormals included
     uint32_t two = ((s.sc & 0xFFu) << 7) | ((s.sc & 0xFF00u) << 15);
+    two = ok ? two : 0u;
     half2_t v = as_h2(two) * (half2_t){(_Float16)256.0f, (_Float16)256.0f};
-    s0 = (half2_t){v.x, v.x};
-    s1 = (half2_t){v.y, v.y};
+    p0.mul = (half2_t){v.x, v.x};
+    p1.mul = (half2_t){v.y, v.y};
+    p0.add = p1.add = (half2_t){(_Float16)0.0f, (_Float16)0.0f};
   } else {
-    half2_t v = as_h2((s.sc & 0xFFFFu) | (s.sc << 16));
-    s0 = v;
-    s1 = v;
+    uint32_t b = (s.sc & 0xFFFFu) | (s.sc << 16);
+    half2_t v = as_h2(ok ? b : 0u);
+    p0.mul = p1.mul = v;
+    p0.add = p1.add = v * (half2_t){(_Float16)-24.0f, (_Float16)-24.0f};   // exact: 2 + 8 bits
   }
-  out[0] = unpack8_scaled<FMT>(s.codes.x, s0);
-  out[1] = unpack8_scaled<FMT>(s.codes.y, s0);
-  out[2] = unpack8_scaled<FMT>(s.codes.z, s1);
-  out[3] = unpack8_scaled<FMT>(s.codes.w, s1);
+}
+
+// two codes of dword d (pair j of four: nibbles j and j + 4 for INT, byte j for NVFP4) -> two
+// scaled fp16 values.  Which two elements form a pair only has to be the same for A and W.
+//
+// INT: the two's complement nibble z becomes offset binary u = z + 8 (flip bit 3), is placed
+// at mantissa bits 6..9 of an fp16 with exponent field 0x4C00, which reads 16 + u = 24 + z, and
+// one fused multiply-add forms (24 + z) * h - 24 * h = z * h.  The product has at most 13
+// significant bits, 24 * h has 10, the result 11: every step is exact in the fma.
+template <int FMT, int J>
+__device__ __forceinline__ uint32_t unpack_pair(uint32_t d, const PairScale& sc) {
+  if constexpr (FMT == kNvfp4) {
+    return h2_bits(__builtin_amdgcn_cvt_scalef32_pk_f16_fp4(d, 1.0f, J) * sc.mul);
+  } else {
+    constexpr int SH = 4 * J - 6;                       // nibble J from bit 4J to bit 6
+    const uint32_t x = SH < 0 ? (d << -SH) : (d >> SH);
+    const half2_t t = as_h2((x & 0x03C003C0u) ^ 0x4E004E00u);   // exponent 0x4C00, bit 9 flipped
+    return h2_bits(__builtin_elementwise_fma(t, sc.mul, sc.add));
+  }
 }
 
 // tile row `r`, 16-byte piece `piece` (0..7) -> byte offset inside one LDS operand tile
-__device__ __forceinline__ int lds_off(int r, int piece) {
-  return r * kRowBytes + ((piece ^ (r & 7)) << 4);
-}
+__device__ __forceinline__ int lds_off(int r, int piece) { return r * kRowBytes + (piece << 4); }
 
+template <int V>
+struct IntC {
+  static constexpr int value = V;
+};
+
+// Software pipeline of one K step s (P = s & 1 is the LDS stage being multiplied):
+//   - global loads for step s + 3 are issued first (two steps ahead of their use),
+//   - the MFMAs of step s run on stage P, fragment reads for the next 16-wide k slice are
+//     issued one slice ahead,
+//   - between MFMAs the wave unpacks its slice of step s + 1 (already in registers) pair by
+//     pair and writes it to stage P ^ 1,
+//   - one barrier ends the step.
+// Every MFMA is followed by its share of vector-ALU and LDS work in program order, pinned
+// with scheduling barriers, so that the matrix pipe and the vector ALU overlap inside a wave
+// instead of alternating in phases.
 template <int FMT, int G, int BM, int BN, int WGM, int WGN, bool OUT_F32>
 __global__ __launch_bounds__(WGM* WGN * 64) void qgemm_kernel(
     const uint8_t* __restrict__ a_codes, ScaleSrc a_sc, const uint8_t* __restrict__ w_codes,
@@ -125,11 +144,14 @@ __global__ __launch_bounds__(WGM* WGN * 64) void qgemm_kernel(
   constexpr int T = WGM * WGN * 64;
   constexpr int WTM = BM / WGM, WTN = BN / WGN;      // wave tile
   constexpr int TM = WTM / 32, TN = WTN / 32;        // MFMA tiles per wave
-  constexpr int A_SLOTS = BM * 2 / T, W_SLOTS = BN * 2 / T;
-  static_assert(BM * 2 % T == 0 && BN * 2 % T == 0, "loader mapping");
+  constexpr int SL = BM * 2 / T;                     // slices per operand per thread
+  static_assert(BM == BN && BM * 2 % T == 0, "square tile, whole slices per thread");
   static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile");
   constexpr int A_TILE_BYTES = BM * kRowBytes, W_TILE_BYTES = BN * kRowBytes;
   constexpr int STAGE_BYTES = A_TILE_BYTES + W_TILE_BYTES;
+  constexpr int NM = TN * TM;                        // MFMAs per 16-wide k slice
+  constexpr int NT = 8 * SL;                         // unpack pair tasks per k slice
+  static_assert(NT % NM == 0 || NM % NT == 0, "pair tasks divide over the MFMAs");
 
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
@@ -138,13 +160,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void qgemm_kernel(
   // 8 along M so that concurrently running workgroups share A and W strips.
   const int n_tiles = tiles_m * tiles_n;
   int pid = blockIdx.x;
-  {
-    const int per_xcd = (n_tiles + 7) / 8;
-    int xcd = pid & 7, local = pid >> 3;
-    int remapped = xcd * per_xcd + local;
-    // the last XCD ranges may be short when n_tiles % 8 != 0; fall back to the identity then
-    if (n_tiles % 8 == 0) pid = remapped;
-  }
+  if (n_tiles % 8 == 0) pid = (pid & 7) * (n_tiles >> 3) + (pid >> 3);
   constexpr int BAND = 8;
   const int band_sz = BAND * tiles_n;
   const int band = pid / band_sz;
@@ -159,8 +175,55 @@ __global__ __launch_bounds__(WGM* WGN * 64) void qgemm_kernel(
   const int lane = tid & 63, wave = tid >> 6;
   const int wave_m = wave % WGM, wave_n = wave / WGM;
 
-  // loader: slot s covers tile row (s*T + tid) / 2, half (tid & 1) -> k offset 32 * half
-  const int ld_half = tid & 1;
+  // loader: this thread owns tile rows tid / 2 + q * (T / 2), k offset 32 * (tid & 1), of both
+  // operands
+  const int ld_row = tid >> 1, ld_half = tid & 1;
+  bool a_ok[SL], w_ok[SL];
+  const uint8_t *a_crow[SL], *w_crow[SL];
+  const void *a_srow[SL], *w_srow[SL];
+#pragma unroll
+  for (int q = 0; q < SL; ++q) {
+    const int r = ld_row + q * (T / 2);
+    a_ok[q] = m0 + r < M;
+    w_ok[q] = n0 + r < N;
+    const int a_row = min(m0 + r, M - 1), w_row = min(n0 + r, N - 1);
+    a_crow[q] = a_codes + (int64_t)a_row * (K / 2);
+    w_crow[q] = w_codes + (int64_t)w_row * (K / 2);
+    if constexpr (FMT == kNvfp4) {
+      a_srow[q] = a_sc.e4m3 + (int64_t)a_row * (K / 16);
+      w_srow[q] = w_sc.e4m3 + (int64_t)w_row * (K / 16);
+    } else {
+      a_srow[q] = a_sc.f16 + (int64_t)a_row * (K / G);
+      w_srow[q] = w_sc.f16 + (int64_t)w_row * (K / G);
+    }
+  }
+  auto load_a = [&](int step, Slice (&ra)[SL]) {
+    const int k0 = step * kBK + ld_half * 32;
+#pragma unroll
+    for (int q = 0; q < SL; ++q) ra[q] = load_slice<FMT, G>(a_crow[q], a_srow[q], K, k0);
+  };
+  auto load_w = [&](int step, Slice (&rw)[SL]) {
+    const int k0 = step * kBK + ld_half * 32;
+#pragma unroll
+    for (int q = 0; q < SL; ++q) rw[q] = load_slice<FMT, G>(w_crow[q], w_srow[q], K, k0);
+  };
+  // byte offsets of this thread's 16-byte pieces inside an operand tile: [slot][piece]
+  int st_off[SL][4];
+#pragma unroll
+  for (int q = 0; q < SL; ++q)
+#pragma unroll
+    for (int c = 0; c < 4; ++c) st_off[q][c] = lds_off(ld_row + q * (T / 2), ld_half * 4 + c);
+
+  const int frag_row = lane & 31, frag_half = lane >> 5;
+  // fragment read offsets: row part + swizzled piece for each of the four k slices
+  int w_frag_base[TN], x_frag_base[TM];
+#pragma unroll
+  for (int i = 0; i < TN; ++i) w_frag_base[i] = (wave_n * WTN + i * 32 + frag_row) * kRowBytes;
+#pragma unroll
+  for (int j = 0; j < TM; ++j) x_frag_base[j] = (wave_m * WTM + j * 32 + frag_row) * kRowBytes;
+  int piece_off[4];
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) piece_off[kk] = (kk * 2 + frag_half) << 4;
 
   float16_t acc[TN][TM];
 #pragma unroll
@@ -170,117 +233,177 @@ __global__ __launch_bounds__(WGM* WGN * 64) void qgemm_kernel(
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-  Slice a_reg[A_SLOTS], w_reg[W_SLOTS];
-
-  auto load_global = [&](int kstep) {
-    const int k0 = kstep * kBK + ld_half * 32;
-#pragma unroll
-    for (int s = 0; s < A_SLOTS; ++s) {
-      int r = (s * T + tid) >> 1;
-      a_reg[s] = load_slice<FMT, G>(a_codes, a_sc, m0 + r, M, K, k0);
-    }
-#pragma unroll
-    for (int s = 0; s < W_SLOTS; ++s) {
-      int r = (s * T + tid) >> 1;
-      w_reg[s] = load_slice<FMT, G>(w_codes, w_sc, n0 + r, N, K, k0);
-    }
-  };
-  auto store_lds = [&](int stage) {
-    unsigned char* a_t = smem + stage * STAGE_BYTES;
-    unsigned char* w_t = a_t + A_TILE_BYTES;
-#pragma unroll
-    for (int s = 0; s < A_SLOTS; ++s) {
-      int r = (s * T + tid) >> 1;
-      uint4 v[4];
-      unpack_slice<FMT>(a_reg[s], v);
-#pragma unroll
-      for (int q = 0; q < 4; ++q)
-        *reinterpret_cast<uint4*>(a_t + lds_off(r, ld_half * 4 + q)) = v[q];
-    }
-#pragma unroll
-    for (int s = 0; s < W_SLOTS; ++s) {
-      int r = (s * T + tid) >> 1;
-      uint4 v[4];
-      unpack_slice<FMT>(w_reg[s], v);
-#pragma unroll
-      for (int q = 0; q < 4; ++q)
-        *reinterpret_cast<uint4*>(w_t + lds_off(r, ld_half * 4 + q)) = v[q];
-    }
-  };
-
+  Slice raw_a[2][SL], raw_w[2][SL];
   const int ksteps = (K + kBK - 1) / kBK;
-  load_global(0);
-  store_lds(0);
+
+  // one operand slice -> its four 16-byte pieces in LDS (used by the prologue only)
+  auto unpack_all = [&](const Slice& sl, bool ok, unsigned char* tile, int q) {
+    PairScale s0, s1;
+    slice_scales<FMT>(sl, ok, s0, s1);
+    const uint32_t d[4] = {sl.codes.x, sl.codes.y, sl.codes.z, sl.codes.w};
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const PairScale& sc = c < 2 ? s0 : s1;
+      uint4 v = make_uint4(unpack_pair<FMT, 0>(d[c], sc), unpack_pair<FMT, 1>(d[c], sc),
+                           unpack_pair<FMT, 2>(d[c], sc), unpack_pair<FMT, 3>(d[c], sc));
+      *reinterpret_cast<uint4*>(tile + st_off[q][c]) = v;
+    }
+  };
+
+  // ---- prologue: stage 0 <- step 0, raw[1] <- step 1, raw[0] <- step 2
+  load_a(0, raw_a[0]);
+  load_w(0, raw_w[0]);
+  load_a(1, raw_a[1]);
+  load_w(1, raw_w[1]);
+#pragma unroll
+  for (int q = 0; q < SL; ++q) {
+    unpack_all(raw_a[0][q], a_ok[q] && ld_half * 32 < K, smem, q);
+    unpack_all(raw_w[0][q], w_ok[q] && ld_half * 32 < K, smem + A_TILE_BYTES, q);
+  }
+  load_a(2, raw_a[0]);
+  load_w(2, raw_w[0]);
   __syncthreads();
 
-  const int frag_row = lane & 31, frag_half = lane >> 5;
-  for (int ks = 0; ks < ksteps; ++ks) {
-    const int stage = ks & 1;
-    if (ks + 1 < ksteps) load_global(ks + 1);
-    const unsigned char* a_t = smem + stage * STAGE_BYTES;
+  auto body = [&](auto Pc, int s) {
+    constexpr int P = decltype(Pc)::value;
+    const unsigned char* a_t = smem + P * STAGE_BYTES;
     const unsigned char* w_t = a_t + A_TILE_BYTES;
+    unsigned char* a_nx = smem + (P ^ 1) * STAGE_BYTES;
+    unsigned char* w_nx = a_nx + A_TILE_BYTES;
+
+    // step s + 1 sits in raw[P ^ 1]; it is unpacked during this step and the registers are
+    // refilled with step s + 3 as soon as they are free (A after half the step, W at the end)
+    Slice(&ca)[SL] = raw_a[P ^ 1];
+    Slice(&cw)[SL] = raw_w[P ^ 1];
+    PairScale sc_a[SL][2], sc_w[SL][2];
 #pragma unroll
-    for (int kk = 0; kk < kBK / 16; ++kk) {
-      half8_t wf[TN], xf[TM];
-      const int piece = kk * 2 + frag_half;
-#pragma unroll
-      for (int i = 0; i < TN; ++i) {
-        int r = wave_n * WTN + i * 32 + frag_row;
-        wf[i] = *reinterpret_cast<const half8_t*>(w_t + lds_off(r, piece));
-      }
-#pragma unroll
-      for (int j = 0; j < TM; ++j) {
-        int r = wave_m * WTM + j * 32 + frag_row;
-        xf[j] = *reinterpret_cast<const half8_t*>(a_t + lds_off(r, piece));
-      }
-#pragma unroll
-      for (int i = 0; i < TN; ++i)
-#pragma unroll
-        for (int j = 0; j < TM; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(wf[i], xf[j], acc[i][j], 0, 0, 0);
+    for (int q = 0; q < SL; ++q) {
+      const bool k_ok = (s + 1) * kBK + ld_half * 32 < K;
+      slice_scales<FMT>(ca[q], a_ok[q] && k_ok, sc_a[q][0], sc_a[q][1]);
+      slice_scales<FMT>(cw[q], w_ok[q] && k_ok, sc_w[q][0], sc_w[q][1]);
     }
-    if (ks + 1 < ksteps) store_lds(stage ^ 1);
+
+    // weight fragments: one set, each reloaded for the next k slice right after its last MFMA;
+    // activation fragments: two sets (they are used by every MFMA of a slice)
+    half8_t wf[TN], xf[2][TM];
+    auto read_w = [&](int kk, int i) {
+      wf[i] = *reinterpret_cast<const half8_t*>(w_t + w_frag_base[i] + piece_off[kk]);
+    };
+    auto read_x = [&](int set, int kk, int j) {
+      xf[set][j] = *reinterpret_cast<const half8_t*>(a_t + x_frag_base[j] + piece_off[kk]);
+    };
+#pragma unroll
+    for (int j = 0; j < TM; ++j) read_x(0, 0, j);
+#pragma unroll
+    for (int i = 0; i < TN; ++i) read_w(0, i);
+
+    uint32_t pk[4];        // the unit (one dword of codes -> one 16-byte piece) being assembled
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      const int cur = kk & 1;
+#pragma unroll
+      for (int mi = 0; mi < NM; ++mi) {
+        const int i = mi / TM, j = mi % TM;
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(wf[i], xf[cur][j], acc[i][j], 0, 0, 0);
+        if (kk < 3) {
+          if (j == TM - 1) read_w(kk + 1, i);                 // wf[i] is free now
+          if (mi < TM) read_x(cur ^ 1, kk + 1, mi);           // next slice's activations, early
+        }
+        // unpack tasks: NT pairs per k slice, spread evenly over the MFMAs.  Task order over
+        // the whole step: A slot 0 (4 pieces x 4 pairs), A slot 1, ..., then the W slots.
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+          if (t * NM / NT != mi) continue;
+          const int g = kk * NT + t;          // global pair task 0 .. 32 * SL - 1
+          const int u = g / 4;                // unit: one dword of codes -> one LDS piece
+          const int jp = g % 4;
+          const bool is_w = u >= 4 * SL;
+          const int q = (u / 4) % SL, c = u % 4;
+          const Slice& src = is_w ? cw[q] : ca[q];
+          const uint32_t d = c == 0 ? src.codes.x : c == 1 ? src.codes.y : c == 2 ? src.codes.z : src.codes.w;
+          const PairScale& sc = is_w ? sc_w[q][c / 2] : sc_a[q][c / 2];
+          if (jp == 0) pk[0] = unpack_pair<FMT, 0>(d, sc);
+          if (jp == 1) pk[1] = unpack_pair<FMT, 1>(d, sc);
+          if (jp == 2) pk[2] = unpack_pair<FMT, 2>(d, sc);
+          if (jp == 3) {
+            pk[3] = unpack_pair<FMT, 3>(d, sc);
+            unsigned char* dst = (is_w ? w_nx : a_nx) + st_off[q][c];
+            *reinterpret_cast<uint4*>(dst) = make_uint4(pk[0], pk[1], pk[2], pk[3]);
+          }
+        }
+        if (kk == 1 && mi == NM - 1) load_a(s + 3, ca);
+        if (kk == 3 && mi == NM - 1) load_w(s + 3, cw);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
     __syncthreads();
+  };
+
+  // two steps per trip so that the LDS stage and the register set are compile-time constants;
+  // an odd step count runs one extra step on all-zero operands (loads beyond K are zeroed),
+  // which keeps a single loop exit (two exits would double the live accumulators)
+  for (int s = 0; s < ksteps; s += 2) {
+    body(IntC<0>{}, s);
+    body(IntC<1>{}, s + 1);
   }
 
   // ---- epilogue: lane holds, per MFMA tile, column m = lane % 32 and rows
-  // n = 8 * (r / 4) + 4 * (lane / 32) + r % 4
+  // n = 8 * (r / 4) + 4 * (lane / 32) + r % 4.  The bf16 tile is staged through LDS (the
+  // operand stages are free after the last barrier) so that global stores are 16 bytes per
+  // lane and contiguous along n; the fp32 variant (a checking aid) stores directly.
+  constexpr int C_ROW_BYTES = BN * 2 + 16;
+  static_assert(BM * C_ROW_BYTES <= 2 * STAGE_BYTES, "output tile fits in the operand stages");
 #pragma unroll
   for (int j = 0; j < TM; ++j) {
-    const int m = m0 + wave_m * WTM + j * 32 + frag_row;
-    if (m >= M) continue;
-    const float am = a_mul[(int64_t)m * a_mul_stride];
+    const int ml = wave_m * WTM + j * 32 + frag_row;
+    const int m = m0 + ml;
+    const float am = a_mul[(int64_t)min(m, M - 1) * a_mul_stride];
 #pragma unroll
     for (int i = 0; i < TN; ++i) {
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        const int n = n0 + wave_n * WTN + i * 32 + q * 8 + frag_half * 4;
-        if (n >= N) continue;
+        const int nl = wave_n * WTN + i * 32 + q * 8 + frag_half * 4;
+        const int n = n0 + nl;
         float v[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          int nn = n + e;
-          float wm = (nn < N) ? w_mul[(int64_t)nn * w_mul_stride] : 0.0f;
+          const float wm = w_mul[(int64_t)min(n + e, N - 1) * w_mul_stride];
           v[e] = acc[i][j][q * 4 + e] * (am * wm);
         }
         if constexpr (OUT_F32) {
-          float* yo = reinterpret_cast<float*>(y) + (int64_t)m * ldy + n;
-          if (n + 3 < N) {
-            *reinterpret_cast<float4*>(yo) = make_float4(v[0], v[1], v[2], v[3]);
-          } else {
-            for (int e = 0; e < 4 && n + e < N; ++e) yo[e] = v[e];
+          if (m < M && n < N) {
+            float* yo = reinterpret_cast<float*>(y) + (int64_t)m * ldy + n;
+            if (n + 3 < N) {
+              *reinterpret_cast<float4*>(yo) = make_float4(v[0], v[1], v[2], v[3]);
+            } else {
+              for (int e = 0; e < 4 && n + e < N; ++e) yo[e] = v[e];
+            }
           }
         } else {
-          uint16_t* yo = reinterpret_cast<uint16_t*>(y) + (int64_t)m * ldy + n;
-          uint32_t b0 = f32_to_bf16_rne(v[0]), b1 = f32_to_bf16_rne(v[1]);
-          uint32_t b2 = f32_to_bf16_rne(v[2]), b3 = f32_to_bf16_rne(v[3]);
-          if (n + 3 < N) {
-            *reinterpret_cast<uint2*>(yo) = make_uint2(b0 | (b1 << 16), b2 | (b3 << 16));
-          } else {
-            uint32_t b[4] = {b0, b1, b2, b3};
-            for (int e = 0; e < 4 && n + e < N; ++e) yo[e] = (uint16_t)b[e];
-          }
+          const uint32_t b0 = f32_to_bf16_rne(v[0]), b1 = f32_to_bf16_rne(v[1]);
+          const uint32_t b2 = f32_to_bf16_rne(v[2]), b3 = f32_to_bf16_rne(v[3]);
+          *reinterpret_cast<uint2*>(smem + ml * C_ROW_BYTES + nl * 2) =
+              make_uint2(b0 | (b1 << 16), b2 | (b3 << 16));
         }
+      }
+    }
+  }
+  if constexpr (!OUT_F32) {
+    __syncthreads();
+    constexpr int CHUNKS_PER_ROW = BN / 8;               // 16-byte chunks of 8 bf16
+    uint16_t* yb = reinterpret_cast<uint16_t*>(y);
+#pragma unroll 4
+    for (int c = tid; c < BM * CHUNKS_PER_ROW; c += T) {
+      const int row = c / CHUNKS_PER_ROW, cc = c % CHUNKS_PER_ROW;
+      const int m = m0 + row, n = n0 + cc * 8;
+      if (m >= M || n >= N) continue;
+      const uint4 v = *reinterpret_cast<const uint4*>(smem + row * C_ROW_BYTES + cc * 16);
+      uint16_t* yo = yb + (int64_t)m * ldy + n;
+      if (n + 7 < N) {
+        *reinterpret_cast<uint4*>(yo) = v;
+      } else {
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+        for (int e = 0; e < 8 && n + e < N; ++e) yo[e] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
       }
     }
   }
@@ -289,7 +412,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void qgemm_kernel(
 // ------------------------------------------------------------------------ INT scale prepass
 // One wave per row of scales: recover each group's bf16 maximum h = bf16_rne(s * Q), find the
 // row's largest exponent, and emit fp16 h * 2^-E plus the fp32 epilogue factor 2^E / Q, with E
-// chosen so that the largest Q * h * 2^-E stays below 2^15.
+// chosen so that the largest h * 2^-E stays below 2^11.
 __global__ __launch_bounds__(256) void int_scale_prep_kernel(const float* __restrict__ s, int rows,
                                                              int groups, float Q,
                                                              uint16_t* __restrict__ h_out,
@@ -304,10 +427,11 @@ __global__ __launch_bounds__(256) void int_scale_prep_kernel(const float* __rest
     mx = fmaxf(mx, h);
   }
   mx = wave_max(mx);
-  // E = exponent(mx) - 11: the row maximum lands in [2^11, 2^12), times Q <= 7 stays < 2^15
+  // E = exponent(mx) - 10: the row maximum lands in [2^10, 2^11), so that the addend 24 * h of
+  // the unpack fma (and with it Q * h) stays below the fp16 maximum
   int e = (int)((as_u32(mx) >> 23) & 0xFF) - 127;
   if (mx == 0.0f) e = 0;
-  int E = e - 11;
+  int E = e - 10;
   // clamp so that both 2^-E and 2^E are normal fp32 numbers
   E = max(-120, min(120, E));
   const float down = as_f32((uint32_t)(127 - E) << 23);     // 2^-E
@@ -375,17 +499,30 @@ static int launch_gemm(const uint8_t* a_codes, ScaleSrc a_sc, const uint8_t* w_c
   return check_hip(hipGetLastError(), "qgemm_kernel");
 }
 
+// Tile choice: 256x256 with 8 waves when that still gives at least half a wave of workgroups
+// over the 256 compute units, else 128x128 with 4 waves.  PQ_QGEMM_TILE (0: 256x256 / 4 waves,
+// 1: 256x256 / 8 waves, 2: 128x128 / 4 waves) overrides the choice for tuning runs.
+static int tile_override() {
+  static int v = [] {
+    const char* e = getenv("PQ_QGEMM_TILE");
+    return e ? atoi(e) : -1;
+  }();
+  return v;
+}
+
 template <int FMT, int G, bool OUT_F32>
 static int pick_tile(const uint8_t* a_codes, ScaleSrc a_sc, const uint8_t* w_codes, ScaleSrc w_sc,
                      const float* a_mul, int a_stride, const float* w_mul, int w_stride, int M, int N,
                      int K, void* y, int64_t ldy, hipStream_t st) {
   // large tile when it still fills the 256 compute units, else the small one
   int64_t big_tiles = (int64_t)((M + 255) / 256) * ((N + 255) / 256);
-  if (big_tiles >= 128)
-    return launch_gemm<FMT, G, 256, 256, 2, 4, OUT_F32>(a_codes, a_sc, w_codes, w_sc, a_mul, a_stride,
-                                                        w_mul, w_stride, M, N, K, y, ldy, st);
-  return launch_gemm<FMT, G, 128, 128, 2, 2, OUT_F32>(a_codes, a_sc, w_codes, w_sc, a_mul, a_stride, w_mul,
-                                                      w_stride, M, N, K, y, ldy, st);
+  int choice = big_tiles >= 128 ? 1 : 2;
+  if (tile_override() >= 0) choice = tile_override();
+#define PQ_GEMM_ARGS a_codes, a_sc, w_codes, w_sc, a_mul, a_stride, w_mul, w_stride, M, N, K, y, ldy, st
+  if (choice == 0) return launch_gemm<FMT, G, 256, 256, 2, 2, OUT_F32>(PQ_GEMM_ARGS);
+  if (choice == 1) return launch_gemm<FMT, G, 256, 256, 2, 4, OUT_F32>(PQ_GEMM_ARGS);
+  return launch_gemm<FMT, G, 128, 128, 2, 2, OUT_F32>(PQ_GEMM_ARGS);
+#undef PQ_GEMM_ARGS
 }
 
 template <int FMT, int G>

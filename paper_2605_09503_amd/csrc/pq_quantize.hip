@@ -188,7 +188,14 @@ __global__ void zero_word_kernel(uint32_t* p) { *p = 0u; }
 // in place: absmax -> T = absmax / (448 * 6)
 __global__ void tensor_scale_kernel(float* p) { *p = *p / 2688.0f; }
 
+__global__ void tensor_scale_from_kernel(const float* a, float* t) { *t = *a / 2688.0f; }
+
 __global__ void fill_float_kernel(float* p, float v) { *p = v; }
+
+int launch_tensor_scale(const float* absmax, float* out, hipStream_t st) {
+  hipLaunchKernelGGL(tensor_scale_from_kernel, dim3(1), dim3(1), 0, st, absmax, out);
+  return check_hip(hipGetLastError(), "tensor_scale_from_kernel");
+}
 
 int launch_fill_float(float* p, float v, hipStream_t st) {
   hipLaunchKernelGGL(fill_float_kernel, dim3(1), dim3(1), 0, st, p, v);

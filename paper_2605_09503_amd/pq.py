@@ -54,6 +54,8 @@ def load():
     lib.pq_workspace_bytes.restype = sz
     lib.pq_workspace_bytes.argtypes = [i32, i32, i32, i64, i64, i64, i32]
     lib.pq_calib_moments.argtypes = [vp, i64, i64, i64, vp, vp, vp, sz, vp]
+    lib.pq_tensor_scale.argtypes = [vp, vp, vp]
+    lib.pq_tensor_scale.restype = i32
     lib.pq_select_perm.argtypes = [i32, i32, vp, vp, i64, C.POINTER(vp), i32, i64, vp, i64,
                                    C.c_float, C.c_float, C.POINTER(C.c_double), i32, C.c_double,
                                    vp, C.POINTER(_Report), vp, sz, vp]
@@ -112,6 +114,11 @@ def pq_calib_moments(x: torch.Tensor, sumsq: torch.Tensor, absmax: Optional[torc
         workspace = _workspace(pq_workspace_bytes(OP_CALIB_MOMENTS, 0, 0, rows, 0, K), x.device)
     _check(load().pq_calib_moments(_ptr(x), rows, K, ld, _ptr(sumsq), _ptr(absmax), _ptr(workspace),
                                    0 if workspace is None else workspace.numel(), _stream()))
+
+
+def pq_tensor_scale(absmax: torch.Tensor, tensor_scale_out: torch.Tensor) -> None:
+    """NVFP4 per-tensor scale T = fl32(absmax / 2688), computed on the device."""
+    _check(load().pq_tensor_scale(_ptr(absmax), _ptr(tensor_scale_out), _stream()))
 
 
 @dataclass
