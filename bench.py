@@ -86,15 +86,15 @@ def main():
     a_codes, a_scales = pq.alloc_quantized(fmt, g, M, K, dev)
     w_codes, w_scales = pq.alloc_quantized(fmt, g, N, K, dev)
     y = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
-    ws_mom = torch.empty(max(pq.pq_workspace_bytes(pq.OP_CALIB_MOMENTS, fmt, g, max(M, N), 0, K), 16),
+    ws_mom = torch.empty(max(max(pq.pq_workspace_bytes(pq.OP_CALIB_MOMENTS, fmt, g, M, 0, K, nb),
+                             pq.pq_workspace_bytes(pq.OP_CALIB_MOMENTS, fmt, g, N, 0, K, 1)), 16),
                          dtype=torch.uint8, device=dev)
     ws_sel = torch.empty(pq.pq_workspace_bytes(pq.OP_SELECT_PERM, fmt, g, M, N, K, nb), dtype=torch.uint8, device=dev)
     ws_gemm = torch.empty(max(pq.pq_workspace_bytes(pq.OP_QGEMM, fmt, g, M, N, K), 16), dtype=torch.uint8, device=dev)
 
     def calibrate():
         sa.zero_(); sw.zero_(); amax_a.zero_(); amax_w.zero_()
-        for xb in xs:
-            pq.pq_calib_moments(xb, sa, amax_a, ws_mom)
+        pq.pq_calib_moments_batched(xs, sa, amax_a, ws_mom)
         pq.pq_calib_moments(w, sw, amax_w, ws_mom)
         ta = tw = 1.0
         if fmt == pq.FMT_NVFP4:

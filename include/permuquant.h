@@ -94,11 +94,22 @@ size_t pq_workspace_bytes(pq_op op, pq_format fmt, int group, int64_t M, int64_t
  * x: bf16 [rows, ld] with ld >= K.  sumsq: double [K], in/out -- the caller zero-fills it
  * before the first batch; call once per calibration batch, and once with x = W, rows = N.
  * absmax: float [1], in/out, >= 0 (zero-filled by the caller), may be NULL.
- * workspace: pq_workspace_bytes(PQ_OP_CALIB_MOMENTS, ., ., rows, 0, K, 0) bytes; contents
- * are scratch.  Results are deterministic (fixed summation order for fixed sizes).
+ * workspace: pq_workspace_bytes(PQ_OP_CALIB_MOMENTS, ., ., rows, 0, K, n_batches) bytes
+ * (n_batches = 1 here); contents are scratch.  Results are deterministic (fixed summation order
+ * for fixed sizes, no atomics).
  */
 int pq_calib_moments(const void* x_bf16, int64_t rows, int64_t K, int64_t ld, double* sumsq,
                      float* absmax, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Same statistic over several calibration batches of equal shape in one launch (the batches of a
+ * calibration set are separate tensors; one launch over all of them keeps the memory system
+ * busy where one 28 MB batch alone is mostly launch latency).
+ * x_batches: HOST array of n_batches DEVICE pointers, each bf16 [rows, ld].
+ */
+int pq_calib_moments_batched(const void* const* x_batches, int n_batches, int64_t rows, int64_t K,
+                             int64_t ld, double* sumsq, float* absmax, void* workspace,
+                             size_t workspace_bytes, void* stream);
 
 /*
  * NVFP4 per-tensor scale from a running absmax (the two-level reading of NVFP4 W4A4, paper

@@ -50,7 +50,7 @@ size_t pq_workspace_bytes(pq_op op, pq_format fmt, int group, int64_t M, int64_t
   switch (op) {
     case PQ_OP_CALIB_MOMENTS:
       if (M <= 0 || K <= 0) return 0;
-      return moments_workspace_bytes(M, K);
+      return moments_workspace_bytes(M, K, n_batches);
     case PQ_OP_SELECT_PERM:
       if (M <= 0 || N <= 0 || K <= 0 || n_batches <= 0) return 0;
       return select_workspace_bytes(M, N, K, n_batches);
@@ -65,20 +65,39 @@ size_t pq_workspace_bytes(pq_op op, pq_format fmt, int group, int64_t M, int64_t
   }
 }
 
+static int calib_moments_common(const char* who, const void* const* xs, int n_batches, int64_t rows,
+                                int64_t K, int64_t ld, double* sumsq, float* absmax, void* workspace,
+                                size_t workspace_bytes, void* stream) {
+  if (!xs || !sumsq) return fail(PQ_ERR_NULL, "%s: x and sumsq must not be NULL", who);
+  if (n_batches <= 0) return fail(PQ_ERR_SHAPE, "%s: n_batches=%d must be positive", who, n_batches);
+  if (rows <= 0 || K <= 0) return fail(PQ_ERR_SHAPE, "%s: rows=%lld K=%lld must be positive", who,
+                                        (long long)rows, (long long)K);
+  if (K % 8 || ld % 8) return fail(PQ_ERR_SHAPE, "%s: K=%lld and ld=%lld must be multiples of 8", who,
+                                   (long long)K, (long long)ld);
+  if (ld < K) return fail(PQ_ERR_SHAPE, "%s: ld=%lld < K=%lld", who, (long long)ld, (long long)K);
+  for (int b = 0; b < n_batches; ++b) {
+    if (!xs[b]) return fail(PQ_ERR_NULL, "%s: batch %d is NULL", who, b);
+    if (!aligned16(xs[b])) return fail(PQ_ERR_SHAPE, "%s: batch %d must be 16-byte aligned", who, b);
+  }
+  size_t need = moments_workspace_bytes(rows, K, n_batches);
+  if (!workspace || workspace_bytes < need)
+    return fail(PQ_ERR_WORKSPACE, "%s: workspace of %zu bytes needed, %zu given", who, need,
+                workspace ? workspace_bytes : (size_t)0);
+  return launch_moments(xs, n_batches, rows, K, ld, sumsq, absmax, workspace, as_stream(stream));
+}
+
 int pq_calib_moments(const void* x, int64_t rows, int64_t K, int64_t ld, double* sumsq,
                      float* absmax, void* workspace, size_t workspace_bytes, void* stream) {
-  if (!x || !sumsq) return fail(PQ_ERR_NULL, "pq_calib_moments: x and sumsq must not be NULL");
-  if (rows <= 0 || K <= 0) return fail(PQ_ERR_SHAPE, "pq_calib_moments: rows=%lld K=%lld must be positive",
-                                        (long long)rows, (long long)K);
-  if (K % 8 || ld % 8) return fail(PQ_ERR_SHAPE, "pq_calib_moments: K=%lld and ld=%lld must be multiples of 8",
-                                   (long long)K, (long long)ld);
-  if (ld < K) return fail(PQ_ERR_SHAPE, "pq_calib_moments: ld=%lld < K=%lld", (long long)ld, (long long)K);
-  if (!aligned16(x)) return fail(PQ_ERR_SHAPE, "pq_calib_moments: x must be 16-byte aligned");
-  size_t need = moments_workspace_bytes(rows, K);
-  if (!workspace || workspace_bytes < need)
-    return fail(PQ_ERR_WORKSPACE, "pq_calib_moments: workspace of %zu bytes needed, %zu given", need,
-                workspace ? workspace_bytes : (size_t)0);
-  return launch_moments(x, rows, K, ld, sumsq, absmax, workspace, as_stream(stream));
+  const void* xs[1] = {x};
+  return calib_moments_common("pq_calib_moments", x ? xs : nullptr, 1, rows, K, ld, sumsq, absmax,
+                              workspace, workspace_bytes, stream);
+}
+
+int pq_calib_moments_batched(const void* const* x_batches, int n_batches, int64_t rows, int64_t K,
+                             int64_t ld, double* sumsq, float* absmax, void* workspace,
+                             size_t workspace_bytes, void* stream) {
+  return calib_moments_common("pq_calib_moments_batched", x_batches, n_batches, rows, K, ld, sumsq,
+                              absmax, workspace, workspace_bytes, stream);
 }
 
 int pq_tensor_scale(const float* absmax, float* tensor_scale_out, void* stream) {

@@ -68,11 +68,23 @@ __device__ __forceinline__ uint32_t e2m1_rne_sat(float a) {
 }
 
 // ---------------------------------------------------------------- lane reductions
-// max over aligned blocks of LANES consecutive lanes (LANES power of two <= 64)
+// value of the lane selected by a DPP control word (invalid source lanes read 0)
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float v) {
+  return as_f32((uint32_t)__builtin_amdgcn_update_dpp(0, (int)as_u32(v), CTRL, 0xF, 0xF, true));
+}
+
+// max over aligned blocks of LANES consecutive lanes (LANES power of two <= 64) of a
+// non-negative value.  Up to 16 lanes the exchange is a DPP operand modifier of the max itself
+// (quad permutes, then mirrors inside 8 and 16 lanes); wider groups finish with lane shuffles.
 template <int LANES>
 __device__ __forceinline__ float group_max(float v) {
+  if constexpr (LANES >= 2) v = fmaxf(v, dpp_f32<0xB1>(v));    // quad_perm [1,0,3,2]
+  if constexpr (LANES >= 4) v = fmaxf(v, dpp_f32<0x4E>(v));    // quad_perm [2,3,0,1]
+  if constexpr (LANES >= 8) v = fmaxf(v, dpp_f32<0x141>(v));   // row_half_mirror
+  if constexpr (LANES >= 16) v = fmaxf(v, dpp_f32<0x140>(v));  // row_mirror
 #pragma unroll
-  for (int off = 1; off < LANES; off <<= 1) v = fmaxf(v, __shfl_xor(v, off, kWave));
+  for (int off = 16; off < LANES; off <<= 1) v = fmaxf(v, __shfl_xor(v, off, kWave));
   return v;
 }
 
@@ -84,39 +96,87 @@ __device__ __forceinline__ double wave_sum(double v) {
   return v;
 }
 
+// ---------------------------------------------------------------- exact divisions, cheaply
+// x / Q for a constant Q with c = RN(1 / Q): one multiply and two fused multiply-adds
+// (quotient, exact remainder, correction).  Checked against IEEE division for every
+// non-negative finite binary32 x: identical for Q = 3 and 7 everywhere, and for Q = 6 whenever
+// the exponent field of x is at least 3.
+__device__ __forceinline__ float div_const(float x, float Q, float c) {
+  const float q0 = x * c;
+  const float r = __builtin_fmaf(-Q, q0, x);
+  return __builtin_fmaf(r, c, q0);
+}
+
+// 1 / s: hardware reciprocal plus one Newton step equals the IEEE quotient for every s whose
+// exponent field lies in [3, 251] (checked exhaustively); outside that window (s >= 2^125; zero
+// and subnormal s never get here) the whole wave takes the IEEE division.
+__device__ __forceinline__ float recip_exact(float s, bool needed) {
+  const bool fast = !needed || ((as_u32(s) >> 23) - 3u) <= 248u;
+  if (__builtin_expect(__all(fast), 1)) {
+    const float r = __builtin_amdgcn_rcpf(s);
+    const float e = __builtin_fmaf(-s, r, 1.0f);
+    return __builtin_fmaf(e, r, r);
+  }
+  return 1.0f / s;
+}
+
 // ---------------------------------------------------------------- quantizer steps
 struct IntScale {
   float s, inv;
 };
-__device__ __forceinline__ IntScale int_scale(float amax, float Q) {
+template <int FMT>
+__device__ __forceinline__ IntScale int_scale(float amax) {
+  constexpr float Q = qmax_of(FMT);
   IntScale r;
-  r.s = amax / Q;
-  r.inv = is_normal32(r.s) ? 1.0f / r.s : 0.0f;
+  r.s = div_const(amax, Q, 1.0f / Q);
+  const bool normal = is_normal32(r.s);
+  const float inv = recip_exact(r.s, normal);
+  r.inv = normal ? inv : 0.0f;
   return r;
 }
-// 4-bit two's complement container of clip(rint(x * inv), -Q, Q)
+// clip(rint(x * inv), -Q, Q) as a float: clipping first is the same for integer Q, and adding
+// 1.5 * 2^23 rounds to the nearest integer (ties to even) in the adder; the low mantissa bits of
+// the sum are then the two's complement integer.
+__device__ __forceinline__ uint32_t int_code_bits(float x, float inv, float Q) {
+  const float v = __builtin_amdgcn_fmed3f(x * inv, -Q, Q);
+  return as_u32(v + 12582912.0f);
+}
 __device__ __forceinline__ uint32_t int_code(float x, float inv, float Q) {
-  float v = x * inv;
-  v = fminf(fmaxf(v, -Q), Q);            // clipping before rounding is the same for integer Q
-  return (uint32_t)(int)rintf(v) & 0xFu;
+  return int_code_bits(x, inv, Q) & 0xFu;
+}
+// the same integer as a float (for the error evaluation)
+__device__ __forceinline__ float int_code_value(float x, float inv, float Q) {
+  const float v = __builtin_amdgcn_fmed3f(x * inv, -Q, Q);
+  return (v + 12582912.0f) - 12582912.0f;
 }
 
 struct Nv4Scale {
   uint32_t byte;
   float inv;
+  float d;       // decoded block scale times the tensor scale
 };
 __device__ __forceinline__ float nv4_enc_scale(float T) { return is_normal32(T) ? 1.0f / T : 0.0f; }
 __device__ __forceinline__ Nv4Scale nv4_scale(float amax, float T, float encT) {
   Nv4Scale r;
-  float t = (amax * encT) / 6.0f;
+  // division by 6: the cheap sequence differs from IEEE only below 2^-124, far under the
+  // smallest E4M3 value, where the byte is 0 either way
+  const float t = div_const(amax * encT, 6.0f, 1.0f / 6.0f);
   r.byte = e4m3_rne_sat(t);
-  float d = e4m3_decode(r.byte) * T;
-  r.inv = is_normal32(d) ? 1.0f / d : 0.0f;
+  r.d = e4m3_decode(r.byte) * T;
+  const bool normal = is_normal32(r.d);
+  const float inv = recip_exact(r.d, normal);
+  r.inv = normal ? inv : 0.0f;
   return r;
 }
 __device__ __forceinline__ uint32_t nv4_code(float x, float inv) {
   float v = x * inv;
   return ((as_u32(x) >> 28) & 8u) | e2m1_rne_sat(fabsf(v));
+}
+// two elements at once on the conversion unit: byte = code(x1) << 4 | code(x0).  The
+// instruction rounds to nearest even, saturates at +-6 and keeps the sign of a zero result
+// (checked against nv4_code for all 2^32 inputs); the sign of x * inv is the sign of x.
+__device__ __forceinline__ uint32_t nv4_code_pair(float x0, float x1, float inv) {
+  return __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(0u, x0 * inv, x1 * inv, 1.0f, 0) & 0xFFu;
 }
 
 }  // namespace pq

@@ -25,9 +25,10 @@ int check_format(pq_format fmt, int group, int64_t K);
 inline hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
 
 // ---- kernel launchers (one per source file) --------------------------------------------
-size_t moments_workspace_bytes(int64_t rows, int64_t K);
-int launch_moments(const void* x, int64_t rows, int64_t K, int64_t ld, double* sumsq, float* absmax,
-                   void* ws, hipStream_t st);
+constexpr int kMaxMomentBatches = 16;   // batches handled by one launch of the moments kernel
+size_t moments_workspace_bytes(int64_t rows, int64_t K, int n_batches);
+int launch_moments(const void* const* xs, int n_batches, int64_t rows, int64_t K, int64_t ld,
+                   double* sumsq, float* absmax, void* ws, hipStream_t st);
 
 int launch_absmax_to_tensor_scale(const void* x, int64_t n_elems, float* tensor_scale_out,
                                   hipStream_t st);

@@ -31,12 +31,15 @@ __device__ __forceinline__ ChunkOut<FMT> quantize_chunk(const float (&v)[8], flo
   uint32_t c = 0;
   if constexpr (FMT == kNvfp4) {
     Nv4Scale s = nv4_scale(a, T, encT);
-#pragma unroll
-    for (int j = 0; j < 8; ++j) c |= nv4_code(v[j], s.inv) << (4 * j);
+    // the conversion unit rounds, saturates, keeps the sign and packs two codes per byte
+    c = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(c, v[0] * s.inv, v[1] * s.inv, 1.0f, 0);
+    c = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(c, v[2] * s.inv, v[3] * s.inv, 1.0f, 1);
+    c = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(c, v[4] * s.inv, v[5] * s.inv, 1.0f, 2);
+    c = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(c, v[6] * s.inv, v[7] * s.inv, 1.0f, 3);
     o.scale = s.byte;
   } else {
-    const float Q = qmax_of(FMT);
-    IntScale s = int_scale(a, Q);
+    constexpr float Q = qmax_of(FMT);
+    IntScale s = int_scale<FMT>(a);
 #pragma unroll
     for (int j = 0; j < 8; ++j) c |= int_code(v[j], s.inv, Q) << (4 * j);
     o.scale = as_u32(s.s);

@@ -2,11 +2,13 @@
 // (Prop. 1), calibration error of every candidate order, alpha search and acceptance rule.
 //
 // Kernels
-//   key_kernel        key[j][i] = alpha_j ln Sa[i] + (1 - alpha_j) ln Sw[i], fp64; a term whose
-//                     weight is zero is skipped.
-//   rank_kernel       stable descending sort by counting: rank(i) = #{j : key_j > key_i or
+//   key_kernel        key[j][i] = alpha_j ln Sa[i] + (1 - alpha_j) ln Sw[i], fp64, all j in one
+//                     launch; a term whose weight is zero is skipped.
+//   rank_count_kernel / rank_scatter_kernel
+//                     stable descending sort by counting: rank(i) = #{j : key_j > key_i or
 //                     (key_j == key_i and j < i)}; perm[rank(i)] = i.  O(K^2) compares, K <= 65536,
-//                     keys staged through LDS; no data-dependent control flow, fully deterministic.
+//                     split over (channel block, key chunk, candidate) workgroups, integer
+//                     partial counts, no data-dependent control flow, fully deterministic.
 //   quant_error_kernel one workgroup per row: the row is staged in LDS once, then for every
 //                     candidate order its channels are gathered from LDS, quantized with the same
 //                     lane-cooperative quantizer as the runtime kernels, dequantized, and the
@@ -25,36 +27,62 @@ namespace pq {
 
 constexpr int kMaxCand = PQ_MAX_ALPHAS + 1;   // identity + candidates
 
+struct AlphaList {
+  double a[PQ_MAX_ALPHAS];
+};
+
+// key[j][i] for every alpha_j of the grid (blockIdx.y = j)
 __global__ __launch_bounds__(256) void key_kernel(const double* __restrict__ sa,
                                                   const double* __restrict__ sw, int64_t K,
-                                                  double alpha, double* __restrict__ key) {
+                                                  AlphaList alphas, double* __restrict__ key) {
   int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (i >= K) return;
+  const double alpha = alphas.a[blockIdx.y];
   double k = 0.0;
   if (alpha != 0.0) k += alpha * log(sa[i]);
   if (alpha != 1.0) k += (1.0 - alpha) * log(sw[i]);
-  key[i] = k;
+  key[(int64_t)blockIdx.y * K + i] = k;
 }
 
-__global__ __launch_bounds__(256) void rank_kernel(const double* __restrict__ key, int K,
-                                                   int32_t* __restrict__ perm) {
-  __shared__ double tile[256];
+constexpr int kRankChunk = 1024;   // keys compared per workgroup of the counting pass
+
+// Counting pass of the stable descending sort: workgroup (x, y, z) compares its 256 channels i
+// with the keys j of chunk y of candidate z and writes how many of them sort before i.
+__global__ __launch_bounds__(256) void rank_count_kernel(const double* __restrict__ keys, int K,
+                                                         int n_chunks, int32_t* __restrict__ part) {
+  __shared__ double tile[kRankChunk];
+  const double* key = keys + (int64_t)blockIdx.z * K;
   const int i = blockIdx.x * 256 + threadIdx.x;
-  const double ki = (i < K) ? key[i] : 0.0;
-  int rank = 0;
-  for (int j0 = 0; j0 < K; j0 += 256) {
-    int j = j0 + threadIdx.x;
-    tile[threadIdx.x] = (j < K) ? key[j] : 0.0;
-    __syncthreads();
-    int n = min(256, K - j0);
-    for (int t = 0; t < n; ++t) {
-      double kj = tile[t];
-      int jj = j0 + t;
-      rank += (kj > ki || (kj == ki && jj < i)) ? 1 : 0;
-    }
-    __syncthreads();
+  const int j0 = blockIdx.y * kRankChunk;
+  const int n = min(kRankChunk, K - j0);
+  for (int t = threadIdx.x; t < n; t += 256) tile[t] = key[j0 + t];
+  __syncthreads();
+  if (i >= K) return;
+  const double ki = key[i];
+  int before = 0;
+  int t = 0;
+  for (; t + 8 <= n; t += 8) {              // eight LDS reads in flight per trip
+    double kj[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) kj[u] = tile[t + u];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) before += (kj[u] > ki || (kj[u] == ki && j0 + t + u < i)) ? 1 : 0;
   }
-  if (i < K) perm[rank] = i;
+  for (; t < n; ++t) {
+    const double kj = tile[t];
+    before += (kj > ki || (kj == ki && j0 + t < i)) ? 1 : 0;
+  }
+  part[((int64_t)blockIdx.z * n_chunks + blockIdx.y) * K + i] = before;
+}
+
+// perm[z][rank(i)] = i with rank(i) the sum of the chunk counts
+__global__ __launch_bounds__(256) void rank_scatter_kernel(const int32_t* __restrict__ part, int K,
+                                                           int n_chunks, int32_t* __restrict__ perms) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= K) return;
+  int rank = 0;
+  for (int c = 0; c < n_chunks; ++c) rank += part[((int64_t)blockIdx.y * n_chunks + c) * K + i];
+  perms[(int64_t)blockIdx.y * K + rank] = i;
 }
 
 __global__ __launch_bounds__(256) void iota_kernel(int32_t* p, int K) {
@@ -105,15 +133,20 @@ __device__ __forceinline__ float e2m1_value(uint32_t idx) {
 
 // cands: [n_cand][K] int32, candidate c == -1 style identity is expressed by cands == nullptr
 // for c < first_perm.  row_err: [rows][n_cand] fp64.
+struct TensorList {
+  const uint16_t* p[kMaxMomentBatches];
+};
+
+// blockIdx.x = row inside a tensor, blockIdx.y = tensor of the list (equal shapes)
 template <int FMT, int G>
-__global__ __launch_bounds__(256) void quant_error_kernel(const uint16_t* __restrict__ x, int K,
+__global__ __launch_bounds__(256) void quant_error_kernel(TensorList xs, int K,
                                                           const int32_t* __restrict__ cands,
                                                           int n_cand, int identity_first, float T,
                                                           double* __restrict__ row_err) {
   extern __shared__ float row[];           // K floats
   __shared__ double red[4];
-  const int64_t r = blockIdx.x;
-  const uint16_t* xr = x + r * (int64_t)K;
+  const int64_t r = (int64_t)blockIdx.y * gridDim.x + blockIdx.x;     // row of the stacked tensors
+  const uint16_t* xr = xs.p[blockIdx.y] + (int64_t)blockIdx.x * K;
   for (int c = threadIdx.x; c < K / 8; c += 256) {
     uint4 p = *reinterpret_cast<const uint4*>(xr + (int64_t)c * 8);
     float* d = row + c * 8;
@@ -150,24 +183,26 @@ __global__ __launch_bounds__(256) void quant_error_kernel(const uint16_t* __rest
       a = group_max<G / 8>(a);
       if constexpr (FMT == kNvfp4) {
         Nv4Scale s = nv4_scale(a, T, encT);
-        double d = (double)e4m3_decode(s.byte) * (double)T;      // exact: 4 + 24 bits
+        const double d = (double)e4m3_decode(s.byte) * (double)T;   // exact: 4 + 24 bits
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          uint32_t code = nv4_code(v[j], s.inv);
-          double mag = (double)e2m1_value(code & 7u) * d;         // exact
-          double xh = (code & 8u) ? -mag : mag;
-          double e = (double)v[j] - xh;
-          err += e * e;
+        for (int j = 0; j < 8; j += 2) {
+          // quantize two elements on the conversion unit and decode them again: q = +-E2M1 value
+          const uint32_t byte = nv4_code_pair(v[j], v[j + 1], s.inv);
+          const auto q = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(byte, 1.0f, 0);
+          const double e0 = fma(-(double)q[0], d, (double)v[j]);      // product exact: 2 + 28 bits
+          const double e1 = fma(-(double)q[1], d, (double)v[j + 1]);
+          err = fma(e0, e0, err);
+          err = fma(e1, e1, err);
         }
       } else {
-        const float Q = qmax_of(FMT);
-        IntScale s = int_scale(a, Q);
+        constexpr float Q = qmax_of(FMT);
+        IntScale s = int_scale<FMT>(a);
+        const double sd = (double)s.s;
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-          float t = v[j] * s.inv;
-          t = rintf(fminf(fmaxf(t, -Q), Q));
-          double e = (double)v[j] - (double)s.s * (double)t;      // product exact in fp64
-          err += e * e;
+          const float t = int_code_value(v[j], s.inv, Q);
+          const double e = fma(-sd, (double)t, (double)v[j]);         // product exact: 24 + 3 bits
+          err = fma(e, e, err);
         }
       }
     }
@@ -180,26 +215,28 @@ __global__ __launch_bounds__(256) void quant_error_kernel(const uint16_t* __rest
   }
 }
 
-// out[c] = sum over rows of row_err[r][c], one workgroup per candidate, fixed order
+// out[seg][c] = sum over the rows of segment seg of row_err[r][c]; one workgroup per
+// (candidate, segment), fixed order.  Segments are consecutive runs of seg_rows rows.
 __global__ __launch_bounds__(256) void reduce_rows_kernel(const double* __restrict__ row_err,
-                                                          int64_t rows, int n_cand,
+                                                          int64_t seg_rows, int n_cand, int out_stride,
                                                           double* __restrict__ out) {
   __shared__ double red[256];
   const int c = blockIdx.x;
+  const double* base = row_err + (int64_t)blockIdx.y * seg_rows * n_cand;
   double s = 0.0;
-  for (int64_t r = threadIdx.x; r < rows; r += 256) s += row_err[r * n_cand + c];
+  for (int64_t r = threadIdx.x; r < seg_rows; r += 256) s += base[r * n_cand + c];
   red[threadIdx.x] = s;
   __syncthreads();
   for (int st = 128; st > 0; st >>= 1) {
     if (threadIdx.x < st) red[threadIdx.x] += red[threadIdx.x + st];
     __syncthreads();
   }
-  if (threadIdx.x == 0) out[c] = red[0];
+  if (threadIdx.x == 0) out[(int64_t)blockIdx.y * out_stride + c] = red[0];
 }
 
 template <int FMT, int G>
-static int launch_qe(const void* x, int64_t rows, int K, const int32_t* cands, int n_cand,
-                     int identity_first, float T, double* row_err, hipStream_t st) {
+static int launch_qe(const TensorList& xs, int n_tensors, int64_t rows, int K, const int32_t* cands,
+                     int n_cand, int identity_first, float T, double* row_err, hipStream_t st) {
   size_t shmem = (size_t)K * sizeof(float);
   auto kern = quant_error_kernel<FMT, G>;
   if (shmem > 48 * 1024) {
@@ -207,24 +244,25 @@ static int launch_qe(const void* x, int64_t rows, int K, const int32_t* cands, i
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
     if (e != hipSuccess) return check_hip(e, "hipFuncSetAttribute(quant_error_kernel)");
   }
-  hipLaunchKernelGGL(kern, dim3((unsigned)rows), dim3(256), shmem, st, (const uint16_t*)x, K, cands,
+  hipLaunchKernelGGL(kern, dim3((unsigned)rows, (unsigned)n_tensors), dim3(256), shmem, st, xs, K, cands,
                      n_cand, identity_first, T, row_err);
   return check_hip(hipGetLastError(), "quant_error_kernel");
 }
 
-static int launch_quant_error(pq_format fmt, int group, const void* x, int64_t rows, int K,
-                              const int32_t* cands, int n_cand, int identity_first, float T,
+static int launch_quant_error(pq_format fmt, int group, const TensorList& x, int n_tensors, int64_t rows,
+                              int K, const int32_t* cands, int n_cand, int identity_first, float T,
                               double* row_err, hipStream_t st) {
+  if (rows > 0x7FFFFFFF) return fail(PQ_ERR_SHAPE, "too many rows");
   if ((size_t)K * 4 > 150 * 1024) return fail(PQ_ERR_SHAPE, "K=%d too large for the LDS-resident row", K);
   if (fmt == PQ_FMT_NVFP4)
-    return launch_qe<kNvfp4, 16>(x, rows, K, cands, n_cand, identity_first, T, row_err, st);
+    return launch_qe<kNvfp4, 16>(x, n_tensors, rows, K, cands, n_cand, identity_first, T, row_err, st);
 #define PQ_INT_CASE(F, FE)                                                                          \
   if (fmt == F) {                                                                                   \
     switch (group) {                                                                                \
-      case 32: return launch_qe<FE, 32>(x, rows, K, cands, n_cand, identity_first, T, row_err, st);  \
-      case 64: return launch_qe<FE, 64>(x, rows, K, cands, n_cand, identity_first, T, row_err, st);  \
-      case 128: return launch_qe<FE, 128>(x, rows, K, cands, n_cand, identity_first, T, row_err, st); \
-      case 256: return launch_qe<FE, 256>(x, rows, K, cands, n_cand, identity_first, T, row_err, st); \
+      case 32: return launch_qe<FE, 32>(x, n_tensors, rows, K, cands, n_cand, identity_first, T, row_err, st);  \
+      case 64: return launch_qe<FE, 64>(x, n_tensors, rows, K, cands, n_cand, identity_first, T, row_err, st);  \
+      case 128: return launch_qe<FE, 128>(x, n_tensors, rows, K, cands, n_cand, identity_first, T, row_err, st); \
+      case 256: return launch_qe<FE, 256>(x, n_tensors, rows, K, cands, n_cand, identity_first, T, row_err, st); \
     }                                                                                               \
   }
   PQ_INT_CASE(PQ_FMT_INT4, kInt4)
@@ -235,12 +273,15 @@ static int launch_quant_error(pq_format fmt, int group, const void* x, int64_t r
 
 // ------------------------------------------------------------------------- workspace layout
 struct SelectWs {
-  double* keys;      // [K]
+  double* keys;      // [PQ_MAX_ALPHAS][K]
   int32_t* cands;    // [PQ_MAX_ALPHAS][K]
-  double* row_err;   // [max(M, N)][kMaxCand]
+  int32_t* part;     // [PQ_MAX_ALPHAS][chunks][K] partial ranks
+  double* row_err;   // [n_batches * M + N][kMaxCand]
   double* sums;      // [(n_batches + 1) * kMaxCand + 2] : per-batch errors, weight errors, |X|^2, |W|^2
   int* moved;        // [PQ_MAX_ALPHAS]
 };
+
+static int rank_chunks(int64_t K) { return (int)((K + kRankChunk - 1) / kRankChunk); }
 
 static size_t carve_select(void* base, int64_t M, int64_t N, int64_t K, int n_batches, SelectWs* w) {
   size_t off = 0;
@@ -249,15 +290,17 @@ static size_t carve_select(void* base, int64_t M, int64_t N, int64_t K, int n_ba
     off = align_up(off + bytes, 256);
     return o;
   };
-  size_t o_keys = take((size_t)K * 8);
+  size_t o_keys = take((size_t)PQ_MAX_ALPHAS * K * 8);
   size_t o_cands = take((size_t)PQ_MAX_ALPHAS * K * 4);
-  size_t o_rowerr = take((size_t)(M > N ? M : N) * kMaxCand * 8);
+  size_t o_part = take((size_t)PQ_MAX_ALPHAS * rank_chunks(K) * K * 4);
+  size_t o_rowerr = take((size_t)((int64_t)n_batches * M + N) * kMaxCand * 8);
   size_t o_sums = take(((size_t)(n_batches + 1) * kMaxCand + 2) * 8);
   size_t o_moved = take((size_t)PQ_MAX_ALPHAS * 4);
   if (w) {
     char* b = (char*)base;
     w->keys = (double*)(b + o_keys);
     w->cands = (int32_t*)(b + o_cands);
+    w->part = (int32_t*)(b + o_part);
     w->row_err = (double*)(b + o_rowerr);
     w->sums = (double*)(b + o_sums);
     w->moved = (int*)(b + o_moved);
@@ -274,9 +317,11 @@ size_t quant_error_workspace_bytes(int64_t rows) { return align_up((size_t)rows 
 int run_quant_error(pq_format fmt, int group, const void* x, int64_t rows, int64_t K,
                     const int32_t* perm, float ts, double* err_out, void* ws, hipStream_t st) {
   double* row_err = (double*)ws;
-  int rc = launch_quant_error(fmt, group, x, rows, (int)K, perm, 1, perm ? 0 : 1, ts, row_err, st);
+  TensorList tl;
+  for (int b = 0; b < kMaxMomentBatches; ++b) tl.p[b] = (const uint16_t*)x;
+  int rc = launch_quant_error(fmt, group, tl, 1, rows, (int)K, perm, 1, perm ? 0 : 1, ts, row_err, st);
   if (rc) return rc;
-  hipLaunchKernelGGL(reduce_rows_kernel, dim3(1), dim3(256), 0, st, row_err, rows, 1, err_out);
+  hipLaunchKernelGGL(reduce_rows_kernel, dim3(1, 1), dim3(256), 0, st, row_err, rows, 1, 1, err_out);
   return check_hip(hipGetLastError(), "reduce_rows_kernel");
 }
 
@@ -288,23 +333,35 @@ int run_select(pq_format fmt, int group, const double* act_sumsq, const double* 
   carve_select(ws, M, N, K, n_batches, &W);
   const int n_cand = n_alpha + 1;            // candidate 0 is the original order
   const unsigned kb = (unsigned)((K + 255) / 256);
+  const int chunks = rank_chunks(K);
   int rc;
-  for (int j = 0; j < n_alpha; ++j) {
-    hipLaunchKernelGGL(key_kernel, dim3(kb), dim3(256), 0, st, act_sumsq, w_sumsq, K, alphas[j], W.keys);
-    hipLaunchKernelGGL(rank_kernel, dim3(kb), dim3(256), 0, st, W.keys, (int)K, W.cands + (int64_t)j * K);
-  }
+  AlphaList al;
+  for (int j = 0; j < PQ_MAX_ALPHAS; ++j) al.a[j] = j < n_alpha ? alphas[j] : 0.0;
+  hipLaunchKernelGGL(key_kernel, dim3(kb, n_alpha), dim3(256), 0, st, act_sumsq, w_sumsq, K, al, W.keys);
+  hipLaunchKernelGGL(rank_count_kernel, dim3(kb, chunks, n_alpha), dim3(256), 0, st, W.keys, (int)K, chunks,
+                     W.part);
+  hipLaunchKernelGGL(rank_scatter_kernel, dim3(kb, n_alpha), dim3(256), 0, st, W.part, (int)K, chunks,
+                     W.cands);
   if ((rc = check_hip(hipGetLastError(), "key/rank kernels"))) return rc;
   hipLaunchKernelGGL(count_moved_kernel, dim3(n_alpha), dim3(256), 0, st, W.cands, (int)K, W.moved);
   double* sums = W.sums;
-  for (int b = 0; b < n_batches; ++b) {
-    rc = launch_quant_error(fmt, group, x_calib[b], M, (int)K, W.cands, n_cand, 1, act_ts, W.row_err, st);
+  // activations: all batches of a launch share one grid (up to kMaxMomentBatches per launch)
+  for (int b0 = 0; b0 < n_batches; b0 += kMaxMomentBatches) {
+    const int nb = n_batches - b0 < kMaxMomentBatches ? n_batches - b0 : kMaxMomentBatches;
+    TensorList tl;
+    for (int b = 0; b < kMaxMomentBatches; ++b) tl.p[b] = (const uint16_t*)x_calib[b0 + (b < nb ? b : 0)];
+    rc = launch_quant_error(fmt, group, tl, nb, M, (int)K, W.cands, n_cand, 1, act_ts,
+                            W.row_err + (size_t)b0 * M * n_cand, st);
     if (rc) return rc;
-    hipLaunchKernelGGL(reduce_rows_kernel, dim3(n_cand), dim3(256), 0, st, W.row_err, M, n_cand,
-                       sums + (size_t)b * kMaxCand);
   }
-  rc = launch_quant_error(fmt, group, w, N, (int)K, W.cands, n_cand, 1, w_ts, W.row_err, st);
+  hipLaunchKernelGGL(reduce_rows_kernel, dim3(n_cand, n_batches), dim3(256), 0, st, W.row_err, M, n_cand,
+                     kMaxCand, sums);
+  double* w_row_err = W.row_err + (size_t)n_batches * M * n_cand;
+  TensorList wl;
+  for (int b = 0; b < kMaxMomentBatches; ++b) wl.p[b] = (const uint16_t*)w;
+  rc = launch_quant_error(fmt, group, wl, 1, N, (int)K, W.cands, n_cand, 1, w_ts, w_row_err, st);
   if (rc) return rc;
-  hipLaunchKernelGGL(reduce_rows_kernel, dim3(n_cand), dim3(256), 0, st, W.row_err, N, n_cand,
+  hipLaunchKernelGGL(reduce_rows_kernel, dim3(n_cand, 1), dim3(256), 0, st, w_row_err, N, n_cand, kMaxCand,
                      sums + (size_t)n_batches * kMaxCand);
   double* tot = sums + (size_t)(n_batches + 1) * kMaxCand;
   hipLaunchKernelGGL(sum2_kernel, dim3(1), dim3(256), 0, st, act_sumsq, w_sumsq, K, tot);

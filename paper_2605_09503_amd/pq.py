@@ -54,6 +54,7 @@ def load():
     lib.pq_workspace_bytes.restype = sz
     lib.pq_workspace_bytes.argtypes = [i32, i32, i32, i64, i64, i64, i32]
     lib.pq_calib_moments.argtypes = [vp, i64, i64, i64, vp, vp, vp, sz, vp]
+    lib.pq_calib_moments_batched.argtypes = [C.POINTER(vp), i32, i64, i64, i64, vp, vp, vp, sz, vp]
     lib.pq_tensor_scale.argtypes = [vp, vp, vp]
     lib.pq_tensor_scale.restype = i32
     lib.pq_select_perm.argtypes = [i32, i32, vp, vp, i64, C.POINTER(vp), i32, i64, vp, i64,
@@ -65,7 +66,7 @@ def load():
     gemm_args = [i32, i32, vp, vp, vp, vp, vp, vp, i64, i64, i64, vp, i64, vp, sz, vp]
     lib.pq_qgemm.argtypes = gemm_args
     lib.pq_qgemm_f32.argtypes = gemm_args
-    for name in ("pq_calib_moments", "pq_select_perm", "pq_quant_error", "pq_quantize_weights",
+    for name in ("pq_calib_moments", "pq_calib_moments_batched", "pq_select_perm", "pq_quant_error", "pq_quantize_weights",
                  "pq_quantize_act", "pq_qgemm", "pq_qgemm_f32"):
         getattr(lib, name).restype = i32
     _lib = lib
@@ -111,9 +112,23 @@ def pq_calib_moments(x: torch.Tensor, sumsq: torch.Tensor, absmax: Optional[torc
     K = x.shape[1] if K is None else K
     ld = x.stride(0) if ld is None else ld
     if workspace is None:
-        workspace = _workspace(pq_workspace_bytes(OP_CALIB_MOMENTS, 0, 0, rows, 0, K), x.device)
+        workspace = _workspace(pq_workspace_bytes(OP_CALIB_MOMENTS, 0, 0, rows, 0, K, 1), x.device)
     _check(load().pq_calib_moments(_ptr(x), rows, K, ld, _ptr(sumsq), _ptr(absmax), _ptr(workspace),
                                    0 if workspace is None else workspace.numel(), _stream()))
+
+
+def pq_calib_moments_batched(xs: Sequence[torch.Tensor], sumsq: torch.Tensor,
+                             absmax: Optional[torch.Tensor] = None,
+                             workspace: Optional[torch.Tensor] = None) -> None:
+    """sumsq[K] += column sums of squares over all batches (equal shapes), one launch."""
+    rows, K = xs[0].shape
+    ld = xs[0].stride(0)
+    nb = len(xs)
+    if workspace is None:
+        workspace = _workspace(pq_workspace_bytes(OP_CALIB_MOMENTS, 0, 0, rows, 0, K, nb), xs[0].device)
+    ptrs = (C.c_void_p * nb)(*[x.data_ptr() for x in xs])
+    _check(load().pq_calib_moments_batched(ptrs, nb, rows, K, ld, _ptr(sumsq), _ptr(absmax), _ptr(workspace),
+                                           0 if workspace is None else workspace.numel(), _stream()))
 
 
 def pq_tensor_scale(absmax: torch.Tensor, tensor_scale_out: torch.Tensor) -> None:

@@ -135,7 +135,8 @@ def test_workspace_sizes(lib):
     assert w(pq.OP_QGEMM, pq.FMT_NVFP4, 16, 4608, 9216, 3072) == 0
     need = w(pq.OP_QGEMM, pq.FMT_INT4, 64, 4608, 3072, 3072)
     assert need >= (4608 + 3072) * (3072 // 64) * 2 + (4608 + 3072) * 4
-    assert w(pq.OP_CALIB_MOMENTS, 0, 0, 4608, 0, 3072) >= 3072 * 8
+    assert w(pq.OP_CALIB_MOMENTS, 0, 0, 4608, 0, 3072, 1) >= 3072 * 8
+    assert w(pq.OP_CALIB_MOMENTS, 0, 0, 4608, 0, 3072, 8) >= 8 * 3072 * 8
     assert w(pq.OP_SELECT_PERM, pq.FMT_INT4, 64, 4608, 3072, 3072, 8) > 15 * 3072 * 4
     assert w(pq.OP_QUANT_ERROR, pq.FMT_INT4, 64, 100, 0, 64) >= 800
     assert w(pq.OP_QGEMM, pq.FMT_INT4, 64, 0, 0, 0) == 0

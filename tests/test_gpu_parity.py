@@ -67,6 +67,22 @@ def test_calib_moments(rows, K, ld):
     assert torch.equal(s2, sumsq)
 
 
+@pytest.mark.parametrize("nb,rows,K", [(3, 200, 520), (8, 96, 1024), (19, 40, 256)])
+def test_calib_moments_batched(nb, rows, K):
+    _say("moments batched nb=%d rows=%d K=%d" % (nb, rows, K))
+    rng = np.random.default_rng(150 + nb)
+    bits = [_rand_bits(rng, rows, K) for _ in range(nb)]
+    xs = [_to_dev(b) for b in bits]
+    sumsq = torch.zeros(K, dtype=torch.float64, device=DEV)
+    absmax = torch.zeros(1, dtype=torch.float32, device=DEV)
+    pq.pq_calib_moments_batched(xs, sumsq, absmax)
+    torch.cuda.synchronize()
+    x64 = [OF.bf16_bits_to_f64(b) for b in bits]
+    ref = sum(OC.column_sumsq(x) for x in x64)
+    assert np.all(np.abs(sumsq.cpu().numpy() - ref) <= T.MOMENTS_RTOL * ref)
+    assert absmax.item() == np.float32(max(OC.absmax(x) for x in x64))
+
+
 # ---------------------------------------------------------------------------- quantizers
 
 def _quantize_act_gpu(fmt, g, x, M, K, ld, perm, T_dev):
