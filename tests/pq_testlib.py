@@ -9,8 +9,9 @@ from oracle import gemm as OG
 from oracle import quantize as OQ
 
 # tolerances of the parity bar
-GEMM_F32_RTOL = 1e-4        # fp32-accumulator output vs fp64 reference, on |y_ref| > GEMM_ABS_FLOOR
+GEMM_F32_RTOL = 1e-3        # fp32-accumulator output vs fp64 reference, on |y_ref| > GEMM_ABS_FLOOR
 GEMM_ABS_FLOOR = 1e-2
+GEMM_ACC_UNITS = 32         # allowed accumulation error in units of 2^-24 of sum_k |terms|
 MOMENTS_RTOL = 1e-12
 ERRSUM_RTOL = 1e-10
 
@@ -32,15 +33,28 @@ def bf16_ulp_distance(bits_a, bits_b):
     return np.abs(key(np.asarray(bits_a)) - key(np.asarray(bits_b)))
 
 
-def gemm_f32_check(y_gpu, y_ref, label=""):
-    """max relative error over |y_ref| > floor, plus an absolute check below the floor."""
+def abs_product(fmt, g, qa, qw):
+    """sum_k |xhat[m, k] * what[n, k]|: the scale against which fp32 accumulation error is judged."""
+    return np.abs(OQ.dequantize(fmt, g, qa)) @ np.abs(OQ.dequantize(fmt, g, qw)).T
+
+
+def gemm_f32_check(y_gpu, y_ref, mag, label=""):
+    """fp32-accumulator output against the fp64 reference.
+
+    (a) |err| <= 32 * 2^-24 * sum_k |terms| for every output: products are exact in the kernel,
+        so the only error is the fp32 accumulation over K terms (worst case K * 2^-24 of the
+        absolute sum, a few units of 2^-24 in practice) plus two roundings in the epilogue;
+    (b) the task's form: max relative error <= 1e-3 on outputs with |y_ref| > 1e-2.
+    Returns the largest relative error of (b)."""
     y_gpu = np.asarray(y_gpu, dtype=np.float64)
+    err = np.abs(y_gpu - y_ref)
+    worst = float((err / np.maximum(mag, 1e-300)).max())
+    assert worst <= GEMM_ACC_UNITS * 2.0 ** -24, "%s accumulation error %.2f units of 2^-24 of sum|terms|" % (
+        label, worst * 2.0 ** 24)
     big = np.abs(y_ref) > GEMM_ABS_FLOOR
-    rel = np.abs(y_gpu[big] - y_ref[big]) / np.abs(y_ref[big])
+    rel = err[big] / np.abs(y_ref[big])
     max_rel = float(rel.max()) if rel.size else 0.0
-    small_abs = float(np.abs(y_gpu[~big] - y_ref[~big]).max()) if (~big).any() else 0.0
     assert max_rel <= GEMM_F32_RTOL, "%s max rel err %.3e" % (label, max_rel)
-    assert small_abs <= GEMM_F32_RTOL * GEMM_ABS_FLOOR * 10, "%s abs err %.3e below floor" % (label, small_abs)
     return max_rel
 
 
@@ -54,5 +68,5 @@ def gemm_bf16_check(y_bits_gpu, y_ref, label=""):
     ref_f = OF.bf16_bits_to_f64(ref_bits)
     got_f = OF.bf16_bits_to_f64(np.asarray(y_bits_gpu))
     # below the floor: the fp32 path's absolute allowance plus one bf16 ulp at the floor (2^-14)
-    assert np.all(np.abs(got_f[~big] - ref_f[~big]) <= GEMM_F32_RTOL * GEMM_ABS_FLOOR * 10 + 2.0 ** -14), label
+    assert np.all(np.abs(got_f[~big] - ref_f[~big]) <= GEMM_F32_RTOL * GEMM_ABS_FLOOR + 2.0 ** -14), label
     return float((d[big] == 0).mean()) if big.any() else 1.0
