@@ -143,8 +143,12 @@ def main():
         return e0.elapsed_time(e1) * 1e-3 / iters            # seconds per call
 
     it = args.kernel_iters
-    t_gemm = time_calls(lambda i: pq.pq_qgemm(fmt, g, a_codes, a_scales, ts_a, w_codes, w_scales, ts_w, y,
-                                              workspace=ws_gemm), it)
+    # the product kernel alone (scale preparation done once before), and the whole call
+    pq.pq_qgemm_prep(fmt, g, a_scales, w_scales, M, N, K, ws_gemm)
+    t_gemm = time_calls(lambda i: pq.pq_qgemm_run(fmt, g, a_codes, a_scales, ts_a, w_codes, w_scales, ts_w, y,
+                                                  workspace=ws_gemm), it)
+    t_gemm_call = time_calls(lambda i: pq.pq_qgemm(fmt, g, a_codes, a_scales, ts_a, w_codes, w_scales, ts_w, y,
+                                                   workspace=ws_gemm), it)
     t_qa_warm = time_calls(lambda i: pq.pq_quantize_act(fmt, g, x_run, None, ts_a, a_codes, a_scales), it)
     # cold: rotate through > 1 GB of distinct inputs so that no input is cache-resident
     n_rot = max(2, int(1.2e9 // (M * K * 2)) + 1)
@@ -154,6 +158,7 @@ def main():
     t_mom_cold = time_calls(lambda i: pq.pq_calib_moments(pool[i % n_rot], sa, None, ws_mom), max(it, n_rot))
     t_mom_warm = time_calls(lambda i: pq.pq_calib_moments(x_run, sa, None, ws_mom), it)
     del pool
+    t_mom_all = time_calls(lambda i: pq.pq_calib_moments_batched(xs, sa, amax_a, ws_mom), 10)
     t_fwd = time_calls(lambda i: forward(), it)
     t_qw = time_calls(lambda i: pq.pq_quantize_weights(fmt, g, w, perm, w_codes, w_scales, ts_w), 5)
     t_cal = time_calls(lambda i: calibrate(), 3)
@@ -162,7 +167,8 @@ def main():
     mbytes = 2.0 * M * K
     gemm_tflops = flops / t_gemm / 1e12
     kernels = {
-        "qgemm": {"us": t_gemm * 1e6, "tflops": gemm_tflops, "frac_mfma_f16_peak": gemm_tflops / MFMA_F16_PEAK_TFLOPS},
+        "qgemm_kernel": {"us": t_gemm * 1e6, "tflops": gemm_tflops, "frac_mfma_f16_peak": gemm_tflops / MFMA_F16_PEAK_TFLOPS},
+        "qgemm_call_with_scale_prep": {"us": t_gemm_call * 1e6, "tflops": flops / t_gemm_call / 1e12},
         "quantize_act_warm": {"us": t_qa_warm * 1e6, "gbs": qbytes / t_qa_warm / 1e9,
                               "frac_hbm_peak": qbytes / t_qa_warm / 1e9 / HBM_PEAK_GBS},
         "quantize_act_cold": {"us": t_qa_cold * 1e6, "gbs": qbytes / t_qa_cold / 1e9,
@@ -171,6 +177,8 @@ def main():
                                "frac_hbm_peak": mbytes / t_mom_warm / 1e9 / HBM_PEAK_GBS},
         "calib_moments_cold": {"us": t_mom_cold * 1e6, "gbs": mbytes / t_mom_cold / 1e9,
                                "frac_hbm_peak": mbytes / t_mom_cold / 1e9 / HBM_PEAK_GBS},
+        "calib_moments_all_batches": {"us": t_mom_all * 1e6, "gbs": nb * mbytes / t_mom_all / 1e9,
+                                      "frac_hbm_peak": nb * mbytes / t_mom_all / 1e9 / HBM_PEAK_GBS},
         "forward_quantize_act_plus_qgemm": {"us": t_fwd * 1e6, "tflops": flops / t_fwd / 1e12},
         "quantize_weights": {"us": t_qw * 1e6},
         "calibrate_moments_plus_select": {"us": t_cal * 1e6},
@@ -178,31 +186,78 @@ def main():
     for k, v in kernels.items():
         log("  %-34s %s" % (k, json.dumps({a: round(b, 4) for a, b in v.items()})))
 
+    # a plain copy of known size, outside every timing: gives the byte counters of a counter
+    # run (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE) a reference to be scaled by
+    probe_src = torch.empty(64 << 20, dtype=torch.float32, device=dev).fill_(1.0)
+    probe_dst = torch.empty_like(probe_src)
+    probe_dst.copy_(probe_src)
+    torch.cuda.synchronize()
+    del probe_src, probe_dst
+
     # ---- CPU baseline: the oracle as it stands, on a bounded sample -------------------------
     cpu = None
     if not args.no_cpu_baseline:
-        from oracle import formats as OF, quantize as OQ, gemm as OG, calib as OC
-        rows = min(M, 512)
-        cols = min(N, 1024)
-        xb = OF.bf16_bits_to_f64(x_run[:rows].view(torch.int16).cpu().numpy().view(np.uint16))
-        wb = OF.bf16_bits_to_f64(st.w_bits[:cols])[:, perm.cpu().numpy()]
-        ta = np.float32(ts_a.item())
-        tw = np.float32(ts_w.item())
-        qw = OQ.quantize(fmt, g, wb, tw if fmt == 0 else None)        # offline, not timed
+        from oracle import formats as OF, quantize as OQ, gemm as OG
+        perm_h = perm.cpu().numpy()
+        ta = np.float32(ts_a.item()) if fmt == 0 else None
+        tw = np.float32(ts_w.item()) if fmt == 0 else None
+        x_bits_run = x_run.view(torch.int16).cpu().numpy().view(np.uint16)
+        cols = min(N, 3072)
+        qw = OQ.quantize(fmt, g, OF.bf16_bits_to_f64(st.w_bits[:cols])[:, perm_h], tw)   # offline, not timed
+
+        def cpu_forward(rows):
+            t0 = time.perf_counter()
+            qa = OQ.quantize(fmt, g, OF.bf16_bits_to_f64(x_bits_run[:rows]), ta)
+            yr = OG.dequant_product(fmt, g, qa, qw)
+            return time.perf_counter() - t0, yr
+
+        t_probe, _ = cpu_forward(128)
+        rows = int(min(M, max(128, 128 * 5.0 / max(t_probe, 1e-3))))       # a few seconds at most
+        t_fwd_cpu, y_ref = cpu_forward(rows)
+        t_fwd_full = t_fwd_cpu * (M / rows) * (N / cols)
+        # calibration half of the step: moments, the alpha grid's sorts, and the error of the
+        # original and the six candidate orders -- on as many calibration batches as fit ~10 s
+        from oracle import calib as OC
+        w64 = OF.bf16_bits_to_f64(st.w_bits)
         t0 = time.perf_counter()
-        qa = OQ.quantize(fmt, g, xb, ta if fmt == 0 else None)
-        y_ref = OG.dequant_product(fmt, g, qa, qw)
-        t_cpu = time.perf_counter() - t0
-        cpu = {"value": 2.0 * rows * cols * K / t_cpu / 1e12, "unit": "TFLOP/s",
+        sw_ref = OC.column_sumsq(w64)
+        sa_ref = OC.column_sumsq(OF.bf16_bits_to_f64(calib_bits[0])) * nb     # stand-in for the sort keys
+        orders = [None] + [OC.sort_descending(OC.joint_key(sa_ref, sw_ref, a)) for a in OC.DEFAULT_ALPHAS]
+        for p_ in orders:
+            OC.squared_error(fmt, g, w64, p_, tw)
+        t_w_cpu = time.perf_counter() - t0
+        used, t_act_cpu = 0, 0.0
+        while used < nb and t_act_cpu < 10.0:
+            t0 = time.perf_counter()
+            xb = OF.bf16_bits_to_f64(calib_bits[used])
+            OC.column_sumsq(xb)
+            for p_ in orders:
+                OC.squared_error(fmt, g, xb, p_, ta)
+            t_act_cpu += time.perf_counter() - t0
+            used += 1
+        t_step_cpu = t_w_cpu + t_act_cpu * nb / used + t_fwd_full
+        cpu = {"value": flops / t_step_cpu / 1e12, "unit": "TFLOP/s",
                "cores": os.cpu_count(), "kind": "oracle",
-               "sample": "forward path (oracle quantize_act + fp64 dequantized product) on %d token rows x %d "
-                         "output channels of the same workload, %.2f s; numpy elementwise steps use one "
-                         "thread, the matmul uses the BLAS threads" % (rows, cols, t_cpu)}
-        # spot check of the timed GPU result against the oracle on the same rows
+               "sample": "the oracle (numpy fp64) on the same workload: calibration half (moments, sorts, error of "
+                         "the original and six candidate orders) measured on W and on %d of %d calibration batches "
+                         "(%.1f s + %.1f s, scaled to all batches), forward half (quantize_act + dequantized "
+                         "product) on %d of %d token rows (%.1f s, scaled); value = 2*M*N*K / extrapolated step "
+                         "time %.1f s; elementwise steps run on one thread, the matmul on the BLAS threads"
+                         % (used, nb, t_w_cpu, t_act_cpu, rows, M, t_fwd_cpu, t_step_cpu)}
+        # spot check of the timed GPU result against the oracle on the same outputs
         got = y[:rows, :cols].float().cpu().numpy().astype(np.float64)
         big = np.abs(y_ref) > 1e-2
         rel = np.abs(got[big] - y_ref[big]) / np.abs(y_ref[big])
         log("  spot check vs oracle on %dx%d outputs: max rel err %.3e (bf16 output)" % (rows, cols, rel.max()))
+        assert rel.max() <= 2.0 ** -8 + 1e-3
+
+    # HBM bytes per qgemm launch from the committed counter summary, if there is one for this workload
+    traffic = None
+    prof = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "qgemm_%s_hbm_traffic.md" % args.config)
+    if os.path.exists(prof):
+        for line in open(prof):
+            if line.startswith("TRAFFIC_BYTES_PER_LAUNCH="):
+                traffic = float(line.split("=")[1])
 
     out = {
         "metric": "qgemm TFLOP/s + % of MFMA-dtype peak on FLUX-shaped W4A4 linears; quantizer GB/s",
@@ -219,7 +274,8 @@ def main():
                    "calib_batches": nb, "accepted": bool(rep.accepted)},
         "roofline": {"bound": "mfma", "kernel": "qgemm_kernel", "achieved": gemm_tflops,
                      "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": gemm_tflops / MFMA_F16_PEAK_TFLOPS, "traffic": None},
+                     "frac": gemm_tflops / MFMA_F16_PEAK_TFLOPS, "traffic": traffic,
+                     "algorithmic_flops_per_launch": flops},
         "cpu_baseline": cpu,
         "kernels": kernels,
     }

@@ -214,6 +214,21 @@ int pq_qgemm(pq_format fmt, int group, const uint8_t* a_codes, const void* a_sca
              const float* w_tensor_scale, int64_t M, int64_t N, int64_t K, void* y_bf16,
              int64_t ldy, void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * pq_qgemm in two steps, for callers that want the scale preparation out of the per-token path
+ * (and for timing the product kernel alone).  pq_qgemm_prep turns the stored INT scales of both
+ * operands into the kernel's working form inside `workspace` (per-row power-of-two
+ * normalisation; nothing to do for NVFP4); pq_qgemm_run then computes the product from codes
+ * and that workspace.  pq_qgemm(...) == pq_qgemm_prep(...) followed by pq_qgemm_run(...) with
+ * the same workspace.  Arguments as for pq_qgemm.
+ */
+int pq_qgemm_prep(pq_format fmt, int group, const void* a_scales, const void* w_scales, int64_t M,
+                  int64_t N, int64_t K, void* workspace, size_t workspace_bytes, void* stream);
+int pq_qgemm_run(pq_format fmt, int group, const uint8_t* a_codes, const void* a_scales,
+                 const float* a_tensor_scale, const uint8_t* w_codes, const void* w_scales,
+                 const float* w_tensor_scale, int64_t M, int64_t N, int64_t K, void* y_bf16,
+                 int64_t ldy, void* workspace, size_t workspace_bytes, void* stream);
+
 /* Same product with the fp32 accumulator stored unrounded: y_f32 is float [M, ldy].  For
  * checking the accumulation against an fp64 reference before the bf16 rounding.           */
 int pq_qgemm_f32(pq_format fmt, int group, const uint8_t* a_codes, const void* a_scales,

@@ -197,19 +197,21 @@ int pq_quantize_act(pq_format fmt, int group, const void* x, int64_t M, int64_t 
 static int qgemm_common(pq_format fmt, int group, const uint8_t* a_codes, const void* a_scales,
                         const float* a_ts, const uint8_t* w_codes, const void* w_scales,
                         const float* w_ts, int64_t M, int64_t N, int64_t K, void* y, int64_t ldy,
-                        bool out_f32, void* workspace, size_t workspace_bytes, void* stream) {
-  if (!a_codes || !a_scales || !w_codes || !w_scales || !y)
+                        bool out_f32, int phases, void* workspace, size_t workspace_bytes,
+                        void* stream) {
+  const bool need_codes = (phases & 2) != 0;
+  if (!a_scales || !w_scales || (need_codes && (!a_codes || !w_codes || !y)))
     return fail(PQ_ERR_NULL, "pq_qgemm: a required pointer is NULL");
   int rc = check_format(fmt, group, K);
   if (rc) return rc;
-  if (fmt == PQ_FMT_NVFP4 && (!a_ts || !w_ts))
+  if (fmt == PQ_FMT_NVFP4 && need_codes && (!a_ts || !w_ts))
     return fail(PQ_ERR_NULL, "pq_qgemm: NVFP4 needs both per-tensor scales");
   if (M <= 0 || N <= 0) return fail(PQ_ERR_SHAPE, "pq_qgemm: M=%lld N=%lld must be positive",
                                     (long long)M, (long long)N);
   if (K % 32) return fail(PQ_ERR_SHAPE, "pq_qgemm: K=%lld must be a multiple of 32", (long long)K);
   if (M > (1 << 24) || N > (1 << 24) || K > (1 << 24))
     return fail(PQ_ERR_SHAPE, "pq_qgemm: a dimension exceeds 2^24");
-  if (ldy < N || ldy % 8)
+  if (need_codes && (ldy < N || ldy % 8))
     return fail(PQ_ERR_SHAPE, "pq_qgemm: ldy=%lld must be >= N=%lld and a multiple of 8",
                 (long long)ldy, (long long)N);
   if (!aligned16(a_codes) || !aligned16(w_codes) || !aligned16(a_scales) || !aligned16(w_scales) ||
@@ -221,7 +223,7 @@ static int qgemm_common(pq_format fmt, int group, const uint8_t* a_codes, const 
                 workspace ? workspace_bytes : (size_t)0);
   if (need && !aligned16(workspace)) return fail(PQ_ERR_SHAPE, "pq_qgemm: workspace must be 16-byte aligned");
   return run_qgemm(fmt, group, a_codes, a_scales, a_ts, w_codes, w_scales, w_ts, M, N, K, y, ldy,
-                   out_f32, workspace, as_stream(stream));
+                   out_f32, phases, workspace, as_stream(stream));
 }
 
 int pq_qgemm(pq_format fmt, int group, const uint8_t* a_codes, const void* a_scales,
@@ -229,7 +231,21 @@ int pq_qgemm(pq_format fmt, int group, const uint8_t* a_codes, const void* a_sca
              const float* w_tensor_scale, int64_t M, int64_t N, int64_t K, void* y_bf16, int64_t ldy,
              void* workspace, size_t workspace_bytes, void* stream) {
   return qgemm_common(fmt, group, a_codes, a_scales, a_tensor_scale, w_codes, w_scales,
-                      w_tensor_scale, M, N, K, y_bf16, ldy, false, workspace, workspace_bytes, stream);
+                      w_tensor_scale, M, N, K, y_bf16, ldy, false, 3, workspace, workspace_bytes, stream);
+}
+
+int pq_qgemm_prep(pq_format fmt, int group, const void* a_scales, const void* w_scales, int64_t M,
+                  int64_t N, int64_t K, void* workspace, size_t workspace_bytes, void* stream) {
+  return qgemm_common(fmt, group, nullptr, a_scales, nullptr, nullptr, w_scales, nullptr, M, N, K, nullptr,
+                      0, false, 1, workspace, workspace_bytes, stream);
+}
+
+int pq_qgemm_run(pq_format fmt, int group, const uint8_t* a_codes, const void* a_scales,
+                 const float* a_tensor_scale, const uint8_t* w_codes, const void* w_scales,
+                 const float* w_tensor_scale, int64_t M, int64_t N, int64_t K, void* y_bf16, int64_t ldy,
+                 void* workspace, size_t workspace_bytes, void* stream) {
+  return qgemm_common(fmt, group, a_codes, a_scales, a_tensor_scale, w_codes, w_scales,
+                      w_tensor_scale, M, N, K, y_bf16, ldy, false, 2, workspace, workspace_bytes, stream);
 }
 
 int pq_qgemm_f32(pq_format fmt, int group, const uint8_t* a_codes, const void* a_scales,
@@ -237,7 +253,7 @@ int pq_qgemm_f32(pq_format fmt, int group, const uint8_t* a_codes, const void* a
                  const float* w_tensor_scale, int64_t M, int64_t N, int64_t K, float* y_f32,
                  int64_t ldy, void* workspace, size_t workspace_bytes, void* stream) {
   return qgemm_common(fmt, group, a_codes, a_scales, a_tensor_scale, w_codes, w_scales,
-                      w_tensor_scale, M, N, K, y_f32, ldy, true, workspace, workspace_bytes, stream);
+                      w_tensor_scale, M, N, K, y_f32, ldy, true, 3, workspace, workspace_bytes, stream);
 }
 
 }  // extern "C"

@@ -50,7 +50,7 @@ int run_quant_error(pq_format fmt, int group, const void* x, int64_t rows, int64
 size_t qgemm_workspace_bytes(pq_format fmt, int group, int64_t M, int64_t N, int64_t K);
 int run_qgemm(pq_format fmt, int group, const uint8_t* a_codes, const void* a_scales,
               const float* a_ts, const uint8_t* w_codes, const void* w_scales, const float* w_ts,
-              int64_t M, int64_t N, int64_t K, void* y, int64_t ldy, bool out_f32, void* ws,
-              hipStream_t st);
+              int64_t M, int64_t N, int64_t K, void* y, int64_t ldy, bool out_f32, int phases,
+              void* ws, hipStream_t st);   // phases: 1 = scale preparation, 2 = product
 
 }  // namespace pq

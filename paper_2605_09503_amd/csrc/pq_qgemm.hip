@@ -528,7 +528,7 @@ static int pick_tile(const uint8_t* a_codes, ScaleSrc a_sc, const uint8_t* w_cod
 template <int FMT, int G>
 static int run_fmt(const uint8_t* a_codes, const void* a_scales, const float* a_ts,
                    const uint8_t* w_codes, const void* w_scales, const float* w_ts, int M, int N, int K,
-                   void* y, int64_t ldy, bool out_f32, void* ws, hipStream_t st) {
+                   void* y, int64_t ldy, bool out_f32, int phases, void* ws, hipStream_t st) {
   ScaleSrc a_sc{nullptr, nullptr}, w_sc{nullptr, nullptr};
   const float *a_mul, *w_mul;
   int a_stride, w_stride;
@@ -542,18 +542,21 @@ static int run_fmt(const uint8_t* a_codes, const void* a_scales, const float* a_
     GemmWs W;
     carve_gemm(ws, (pq_format)FMT, G, M, N, K, &W);
     const float Q = qmax_of(FMT);
-    hipLaunchKernelGGL(int_scale_prep_kernel, dim3((unsigned)((M + 3) / 4)), dim3(256), 0, st,
-                       (const float*)a_scales, M, K / G, Q, W.a_h, W.a_mul);
-    hipLaunchKernelGGL(int_scale_prep_kernel, dim3((unsigned)((N + 3) / 4)), dim3(256), 0, st,
-                       (const float*)w_scales, N, K / G, Q, W.w_h, W.w_mul);
-    int rc = check_hip(hipGetLastError(), "int_scale_prep_kernel");
-    if (rc) return rc;
+    if (phases & 1) {
+      hipLaunchKernelGGL(int_scale_prep_kernel, dim3((unsigned)((M + 3) / 4)), dim3(256), 0, st,
+                         (const float*)a_scales, M, K / G, Q, W.a_h, W.a_mul);
+      hipLaunchKernelGGL(int_scale_prep_kernel, dim3((unsigned)((N + 3) / 4)), dim3(256), 0, st,
+                         (const float*)w_scales, N, K / G, Q, W.w_h, W.w_mul);
+      int rc = check_hip(hipGetLastError(), "int_scale_prep_kernel");
+      if (rc) return rc;
+    }
     a_sc.f16 = W.a_h;
     w_sc.f16 = W.w_h;
     a_mul = W.a_mul;
     w_mul = W.w_mul;
     a_stride = w_stride = 1;
   }
+  if (!(phases & 2)) return PQ_OK;
   if (out_f32)
     return pick_tile<FMT, G, true>(a_codes, a_sc, w_codes, w_sc, a_mul, a_stride, w_mul, w_stride, M, N, K,
                                    y, ldy, st);
@@ -563,9 +566,9 @@ static int run_fmt(const uint8_t* a_codes, const void* a_scales, const float* a_
 
 int run_qgemm(pq_format fmt, int group, const uint8_t* a_codes, const void* a_scales,
               const float* a_ts, const uint8_t* w_codes, const void* w_scales, const float* w_ts,
-              int64_t M, int64_t N, int64_t K, void* y, int64_t ldy, bool out_f32, void* ws,
-              hipStream_t st) {
-#define PQ_ARGS a_codes, a_scales, a_ts, w_codes, w_scales, w_ts, (int)M, (int)N, (int)K, y, ldy, out_f32, ws, st
+              int64_t M, int64_t N, int64_t K, void* y, int64_t ldy, bool out_f32, int phases,
+              void* ws, hipStream_t st) {
+#define PQ_ARGS a_codes, a_scales, a_ts, w_codes, w_scales, w_ts, (int)M, (int)N, (int)K, y, ldy, out_f32, phases, ws, st
   if (fmt == PQ_FMT_NVFP4) return run_fmt<kNvfp4, 16>(PQ_ARGS);
   if (fmt == PQ_FMT_INT4) {
     switch (group) {

@@ -66,8 +66,10 @@ def load():
     gemm_args = [i32, i32, vp, vp, vp, vp, vp, vp, i64, i64, i64, vp, i64, vp, sz, vp]
     lib.pq_qgemm.argtypes = gemm_args
     lib.pq_qgemm_f32.argtypes = gemm_args
+    lib.pq_qgemm_run.argtypes = gemm_args
+    lib.pq_qgemm_prep.argtypes = [i32, i32, vp, vp, i64, i64, i64, vp, sz, vp]
     for name in ("pq_calib_moments", "pq_calib_moments_batched", "pq_select_perm", "pq_quant_error", "pq_quantize_weights",
-                 "pq_quantize_act", "pq_qgemm", "pq_qgemm_f32"):
+                 "pq_quantize_act", "pq_qgemm", "pq_qgemm_f32", "pq_qgemm_run", "pq_qgemm_prep"):
         getattr(lib, name).restype = i32
     _lib = lib
     return lib
@@ -213,6 +215,21 @@ def pq_qgemm(fmt: int, group: int, a_codes, a_scales, a_tensor_scale, w_codes, w
              M=None, N=None, K=None, ldy=None) -> None:
     """y[M, N] (bf16) = dequant(A) @ dequant(W)^T."""
     _gemm(load().pq_qgemm, fmt, group, a_codes, a_scales, a_tensor_scale, w_codes, w_scales,
+          w_tensor_scale, y, workspace, M, N, K, ldy)
+
+
+def pq_qgemm_prep(fmt: int, group: int, a_scales, w_scales, M: int, N: int, K: int,
+                  workspace: Optional[torch.Tensor]) -> None:
+    """Scale preparation half of pq_qgemm (INT formats; no-op for NVFP4)."""
+    _check(load().pq_qgemm_prep(fmt, group, _ptr(a_scales), _ptr(w_scales), M, N, K, _ptr(workspace),
+                                0 if workspace is None else workspace.numel(), _stream()))
+
+
+def pq_qgemm_run(fmt: int, group: int, a_codes, a_scales, a_tensor_scale, w_codes, w_scales,
+                 w_tensor_scale, y: torch.Tensor, workspace: Optional[torch.Tensor] = None,
+                 M=None, N=None, K=None, ldy=None) -> None:
+    """Product half of pq_qgemm: the workspace must have been filled by pq_qgemm_prep."""
+    _gemm(load().pq_qgemm_run, fmt, group, a_codes, a_scales, a_tensor_scale, w_codes, w_scales,
           w_tensor_scale, y, workspace, M, N, K, ldy)
 
 

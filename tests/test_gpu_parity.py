@@ -334,6 +334,29 @@ def test_qgemm_tiny(fmt, g):
     _gemm_case(fmt, g, 33, 17, 64 if g <= 64 else g, 810 + g)
 
 
+@pytest.mark.parametrize("fmt,g", FMTS[:4])
+def test_qgemm_prep_then_run_equals_one_call(fmt, g):
+    M, N, K = 300, 264, 512
+    rng = np.random.default_rng(850 + g)
+    xb = _rand_bits(rng, M, K)
+    wb = synth.f64_to_bf16_bits(0.02 * rng.standard_normal((N, K)))
+    a_codes, a_scales = pq.alloc_quantized(fmt, g, M, K, DEV)
+    w_codes, w_scales = pq.alloc_quantized(fmt, g, N, K, DEV)
+    Ta = torch.tensor([0.01], dtype=torch.float32, device=DEV)
+    Tw = torch.empty(1, dtype=torch.float32, device=DEV)
+    pq.pq_quantize_act(fmt, g, _to_dev(xb), None, Ta, a_codes, a_scales)
+    pq.pq_quantize_weights(fmt, g, _to_dev(wb), None, w_codes, w_scales, Tw)
+    ws = torch.empty(max(16, pq.pq_workspace_bytes(pq.OP_QGEMM, fmt, g, M, N, K)), dtype=torch.uint8, device=DEV)
+    y1 = torch.zeros((M, N), dtype=torch.bfloat16, device=DEV)
+    y2 = torch.zeros((M, N), dtype=torch.bfloat16, device=DEV)
+    pq.pq_qgemm(fmt, g, a_codes, a_scales, Ta, w_codes, w_scales, Tw, y1, workspace=ws)
+    ws.zero_()
+    pq.pq_qgemm_prep(fmt, g, a_scales, w_scales, M, N, K, ws)
+    pq.pq_qgemm_run(fmt, g, a_codes, a_scales, Ta, w_codes, w_scales, Tw, y2, workspace=ws)
+    torch.cuda.synchronize()
+    assert torch.equal(y1.view(torch.int16), y2.view(torch.int16))
+
+
 def test_qgemm_int_exact_small_integers():
     # all scales 1 (h = Q), codes in {-1, 0, 1}: the accumulator holds Q^2 times an exact small
     # integer; the epilogue's two fp32 factors 2^E/Q each round once (<= 3 roundings in all)
