@@ -20,110 +20,14 @@
 // barrier per step.  Waves form a WGM x WGN grid; each owns (BM/WGM) x (BN/WGN) outputs as
 // 32x32 MFMA tiles.  The MFMA "A" operand is the weight tile and "B" the activation tile, so
 // a lane ends up with 4 consecutive n for one m and stores 8 bytes of bf16 at once.
-// LDS rows are 128 bytes (64 fp16) in 16-byte pieces, piece index XOR (row & 7): conflict-free
-// for the 16-byte fragment reads and for the unpack writes.
+// LDS rows are 64 fp16 plus one 16-byte piece of padding (144 bytes): measured on gfx950, the
+// 16-byte fragment reads of the 32-row MFMA operand pattern run at full LDS rate with this
+// stride (an XOR swizzle of unpadded rows reaches two thirds of it).
 #include <stdlib.h>
 
-#include "pq_device.h"
-#include "pq_host.h"
+#include "pq_qgemm_common.h"
 
 namespace pq {
-
-typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
-typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
-typedef float float16_t __attribute__((ext_vector_type(16)));
-
-constexpr int kBK = 64;                 // K elements per step
-constexpr int kRowBytes = kBK * 2 + 16; // fp16 row in LDS, padded by one 16-byte piece: with 144-byte
-                                        // rows both the 16-byte fragment reads (rows 0..31 of a
-                                        // piece) and the unpack writes spread over all banks
-
-__device__ __forceinline__ half2_t as_h2(uint32_t u) { return __builtin_bit_cast(half2_t, u); }
-__device__ __forceinline__ uint32_t h2_bits(half2_t h) { return __builtin_bit_cast(uint32_t, h); }
-
-// ------------------------------------------------------------------------ operand unpack
-// Per-thread slice of a tile row: 32 consecutive k (16 bytes of codes) plus its scales.
-struct Slice {
-  uint4 codes;
-  uint32_t sc;      // NVFP4: two E4M3 bytes (k 0-15, 16-31); INT: one fp16 in the low half
-};
-
-// scale source for one operand
-struct ScaleSrc {
-  const uint8_t* e4m3;      // NVFP4: [rows, K/16]
-  const uint16_t* f16;      // INT: normalised group maxima, [rows, K/G]
-};
-
-// Branch-free load of one slice.  `codes_row` / `sc_row` point at a valid row (the caller
-// clamps the row index) and k0 beyond K is redirected to the row start, so the address is
-// always valid.  The loaded registers are not touched here (a use would make the wave wait for
-// the load at once); a slice that is out of range is neutralised when it is unpacked, by
-// zeroing its scale (see slice_scales).
-template <int FMT, int G>
-__device__ __forceinline__ Slice load_slice(const uint8_t* __restrict__ codes_row,
-                                            const void* __restrict__ sc_row, int K, int k0) {
-  const int kk = k0 < K ? k0 : 0;
-  Slice s;
-  s.codes = *reinterpret_cast<const uint4*>(codes_row + kk / 2);
-  if constexpr (FMT == kNvfp4) {
-    s.sc = *reinterpret_cast<const uint16_t*>(reinterpret_cast<const uint8_t*>(sc_row) + kk / 16);
-  } else {
-    s.sc = reinterpret_cast<const uint16_t*>(sc_row)[kk / G];
-  }
-  return s;
-}
-
-// Scale pair(s) handed to unpack_pair.  INT carries {h, h} and {-24 h, -24 h} (see below).
-struct PairScale {
-  half2_t mul, add;
-};
-
-// {s, s} pairs of the two group scales a slice can touch; all zero when the slice is out of
-// range (row beyond the matrix or k beyond K), so that whatever codes were loaded contribute 0
-template <int FMT>
-__device__ __forceinline__ void slice_scales(const Slice& s, bool ok, PairScale& p0, PairScale& p1) {
-  if constexpr (FMT == kNvfp4) {
-    // E4M3 byte b -> fp16: bits (b << 7) read as fp16 are value * 2^-8, subnormals included
-    uint32_t two = ((s.sc & 0xFFu) << 7) | ((s.sc & 0xFF00u) << 15);
-    two = ok ? two : 0u;
-    half2_t v = as_h2(two) * (half2_t){(_Float16)256.0f, (_Float16)256.0f};
-    p0.mul = (half2_t){v.x, v.x};
-    p1.mul = (half2_t){v.y, v.y};
-    p0.add = p1.add = (half2_t){(_Float16)0.0f, (_Float16)0.0f};
-  } else {
-    uint32_t b = (s.sc & 0xFFFFu) | (s.sc << 16);
-    half2_t v = as_h2(ok ? b : 0u);
-    p0.mul = p1.mul = v;
-    p0.add = p1.add = v * (half2_t){(_Float16)-24.0f, (_Float16)-24.0f};   // exact: 2 + 8 bits
-  }
-}
-
-// two codes of dword d (pair j of four: nibbles j and j + 4 for INT, byte j for NVFP4) -> two
-// scaled fp16 values.  Which two elements form a pair only has to be the same for A and W.
-//
-// INT: the two's complement nibble z becomes offset binary u = z + 8 (flip bit 3), is placed
-// at mantissa bits 6..9 of an fp16 with exponent field 0x4C00, which reads 16 + u = 24 + z, and
-// one fused multiply-add forms (24 + z) * h - 24 * h = z * h.  The product has at most 13
-// significant bits, 24 * h has 10, the result 11: every step is exact in the fma.
-template <int FMT, int J>
-__device__ __forceinline__ uint32_t unpack_pair(uint32_t d, const PairScale& sc) {
-  if constexpr (FMT == kNvfp4) {
-    return h2_bits(__builtin_amdgcn_cvt_scalef32_pk_f16_fp4(d, 1.0f, J) * sc.mul);
-  } else {
-    constexpr int SH = 4 * J - 6;                       // nibble J from bit 4J to bit 6
-    const uint32_t x = SH < 0 ? (d << -SH) : (d >> SH);
-    const half2_t t = as_h2((x & 0x03C003C0u) ^ 0x4E004E00u);   // exponent 0x4C00, bit 9 flipped
-    return h2_bits(__builtin_elementwise_fma(t, sc.mul, sc.add));
-  }
-}
-
-// tile row `r`, 16-byte piece `piece` (0..7) -> byte offset inside one LDS operand tile
-__device__ __forceinline__ int lds_off(int r, int piece) { return r * kRowBytes + (piece << 4); }
-
-template <int V>
-struct IntC {
-  static constexpr int value = V;
-};
 
 // Software pipeline of one K step s (P = s & 1 is the LDS stage being multiplied):
 //   - global loads for step s + 3 are issued first (two steps ahead of their use),
@@ -499,9 +403,11 @@ static int launch_gemm(const uint8_t* a_codes, ScaleSrc a_sc, const uint8_t* w_c
   return check_hip(hipGetLastError(), "qgemm_kernel");
 }
 
-// Tile choice: 256x256 with 8 waves when that still gives at least half a wave of workgroups
-// over the 256 compute units, else 128x128 with 4 waves.  PQ_QGEMM_TILE (0: 256x256 / 4 waves,
-// 1: 256x256 / 8 waves, 2: 128x128 / 4 waves) overrides the choice for tuning runs.
+// Tile choice.  256 x 256 with eight waves unless the output is so small that 128 x 128 tiles
+// (four waves, about 35 % more operand traffic per output) fill more of the 256 compute units.
+// The cost of a variant is the number of rounds its tiles need times the tile area.
+// PQ_QGEMM_TILE (0: 256 x 256 with 4 waves, 1: 256 x 256 with 8 waves, 2: 128 x 128) overrides
+// the choice for tuning runs.
 static int tile_override() {
   static int v = [] {
     const char* e = getenv("PQ_QGEMM_TILE");
@@ -510,14 +416,22 @@ static int tile_override() {
   return v;
 }
 
+static int choose_tile(int M, int N) {
+  auto rounds = [&](int bm, int bn) {
+    int64_t tiles = (int64_t)((M + bm - 1) / bm) * ((N + bn - 1) / bn);
+    return (double)((tiles + 255) / 256);
+  };
+  const double c256 = rounds(256, 256) * 256 * 256;
+  const double c128 = rounds(128, 128) * 128 * 128 * 1.35;
+  return c128 < c256 ? 2 : 1;
+}
+
 template <int FMT, int G, bool OUT_F32>
 static int pick_tile(const uint8_t* a_codes, ScaleSrc a_sc, const uint8_t* w_codes, ScaleSrc w_sc,
                      const float* a_mul, int a_stride, const float* w_mul, int w_stride, int M, int N,
                      int K, void* y, int64_t ldy, hipStream_t st) {
-  // large tile when it still fills the 256 compute units, else the small one
-  int64_t big_tiles = (int64_t)((M + 255) / 256) * ((N + 255) / 256);
-  int choice = big_tiles >= 128 ? 1 : 2;
-  if (tile_override() >= 0) choice = tile_override();
+  int choice = choose_tile(M, N);
+  if (tile_override() >= 0 && tile_override() <= 2) choice = tile_override();
 #define PQ_GEMM_ARGS a_codes, a_sc, w_codes, w_sc, a_mul, a_stride, w_mul, w_stride, M, N, K, y, ldy, st
   if (choice == 0) return launch_gemm<FMT, G, 256, 256, 2, 2, OUT_F32>(PQ_GEMM_ARGS);
   if (choice == 1) return launch_gemm<FMT, G, 256, 256, 2, 4, OUT_F32>(PQ_GEMM_ARGS);
