@@ -70,22 +70,29 @@ __device__ __forceinline__ uint32_t e2m1_rne_sat(float a) {
 // ---------------------------------------------------------------- lane reductions
 // value of the lane selected by a DPP control word (invalid source lanes read 0)
 template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_u32(uint32_t v) {
+  return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xF, 0xF, true);
+}
+template <int CTRL>
 __device__ __forceinline__ float dpp_f32(float v) {
-  return as_f32((uint32_t)__builtin_amdgcn_update_dpp(0, (int)as_u32(v), CTRL, 0xF, 0xF, true));
+  return as_f32(dpp_u32<CTRL>(as_u32(v)));
 }
 
 // max over aligned blocks of LANES consecutive lanes (LANES power of two <= 64) of a
-// non-negative value.  Up to 16 lanes the exchange is a DPP operand modifier of the max itself
-// (quad permutes, then mirrors inside 8 and 16 lanes); wider groups finish with lane shuffles.
+// non-negative, non-NaN value.  Such floats order like their bit patterns, so the maximum is an
+// unsigned integer max, which takes the DPP lane exchange as an operand modifier (quad permutes,
+// then mirrors inside 8 and 16 lanes: one instruction per step); wider groups finish with lane
+// shuffles.
 template <int LANES>
 __device__ __forceinline__ float group_max(float v) {
-  if constexpr (LANES >= 2) v = fmaxf(v, dpp_f32<0xB1>(v));    // quad_perm [1,0,3,2]
-  if constexpr (LANES >= 4) v = fmaxf(v, dpp_f32<0x4E>(v));    // quad_perm [2,3,0,1]
-  if constexpr (LANES >= 8) v = fmaxf(v, dpp_f32<0x141>(v));   // row_half_mirror
-  if constexpr (LANES >= 16) v = fmaxf(v, dpp_f32<0x140>(v));  // row_mirror
+  uint32_t u = as_u32(v);
+  if constexpr (LANES >= 2) u = max(u, dpp_u32<0xB1>(u));    // quad_perm [1,0,3,2]
+  if constexpr (LANES >= 4) u = max(u, dpp_u32<0x4E>(u));    // quad_perm [2,3,0,1]
+  if constexpr (LANES >= 8) u = max(u, dpp_u32<0x141>(u));   // row_half_mirror
+  if constexpr (LANES >= 16) u = max(u, dpp_u32<0x140>(u));  // row_mirror
 #pragma unroll
-  for (int off = 16; off < LANES; off <<= 1) v = fmaxf(v, __shfl_xor(v, off, kWave));
-  return v;
+  for (int off = 16; off < LANES; off <<= 1) u = max(u, (uint32_t)__shfl_xor((int)u, off, kWave));
+  return as_f32(u);
 }
 
 __device__ __forceinline__ float wave_max(float v) { return group_max<64>(v); }
@@ -134,6 +141,30 @@ __device__ __forceinline__ IntScale int_scale(float amax) {
   r.inv = normal ? inv : 0.0f;
   return r;
 }
+// the same for R independent maxima at once: one wave-wide window test for all of them
+template <int FMT, int R>
+__device__ __forceinline__ void int_scales(const float (&amax)[R], IntScale (&out)[R]) {
+  constexpr float Q = qmax_of(FMT);
+  bool normal[R];
+  bool fast = true;
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    out[r].s = div_const(amax[r], Q, 1.0f / Q);
+    normal[r] = is_normal32(out[r].s);
+    fast = fast && (!normal[r] || ((as_u32(out[r].s) >> 23) - 3u) <= 248u);
+  }
+  if (__builtin_expect(__all(fast), 1)) {
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      const float q = __builtin_amdgcn_rcpf(out[r].s);
+      const float e = __builtin_fmaf(-out[r].s, q, 1.0f);
+      out[r].inv = normal[r] ? __builtin_fmaf(e, q, q) : 0.0f;
+    }
+  } else {
+#pragma unroll
+    for (int r = 0; r < R; ++r) out[r].inv = normal[r] ? 1.0f / out[r].s : 0.0f;
+  }
+}
 // clip(rint(x * inv), -Q, Q) as a float: clipping first is the same for integer Q, and adding
 // 1.5 * 2^23 rounds to the nearest integer (ties to even) in the adder; the low mantissa bits of
 // the sum are then the two's complement integer.
@@ -167,6 +198,30 @@ __device__ __forceinline__ Nv4Scale nv4_scale(float amax, float T, float encT) {
   const float inv = recip_exact(r.d, normal);
   r.inv = normal ? inv : 0.0f;
   return r;
+}
+template <int R>
+__device__ __forceinline__ void nv4_scales(const float (&amax)[R], float T, float encT, Nv4Scale (&out)[R]) {
+  bool normal[R];
+  bool fast = true;
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    const float t = div_const(amax[r] * encT, 6.0f, 1.0f / 6.0f);
+    out[r].byte = e4m3_rne_sat(t);
+    out[r].d = e4m3_decode(out[r].byte) * T;
+    normal[r] = is_normal32(out[r].d);
+    fast = fast && (!normal[r] || ((as_u32(out[r].d) >> 23) - 3u) <= 248u);
+  }
+  if (__builtin_expect(__all(fast), 1)) {
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      const float q = __builtin_amdgcn_rcpf(out[r].d);
+      const float e = __builtin_fmaf(-out[r].d, q, 1.0f);
+      out[r].inv = normal[r] ? __builtin_fmaf(e, q, q) : 0.0f;
+    }
+  } else {
+#pragma unroll
+    for (int r = 0; r < R; ++r) out[r].inv = normal[r] ? 1.0f / out[r].d : 0.0f;
+  }
 }
 __device__ __forceinline__ uint32_t nv4_code(float x, float inv) {
   float v = x * inv;

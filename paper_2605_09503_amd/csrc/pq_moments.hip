@@ -22,10 +22,19 @@ struct BatchPtrs {
   const uint16_t* p[kMaxMomentBatches];
 };
 
+// Row slabs per (column block, batch): the smallest count that gives every one of the 256
+// compute units the same number of workgroups (two or three of them), so that no unit idles
+// while others finish, capped so that a wave keeps at least four rows.
 static int moments_slabs(int64_t rows, int64_t K, int n_batches) {
-  int64_t col_blocks = (K + kColsPerBlock - 1) / kColsPerBlock;
-  int64_t want = (512 + col_blocks * n_batches - 1) / (col_blocks * n_batches);  // ~512 workgroups
-  int64_t max_slabs = (rows + 4 * kTy - 1) / (4 * kTy);                          // >= 4 rows per wave
+  const int64_t col_blocks = (K + kColsPerBlock - 1) / kColsPerBlock;
+  const int64_t per_slab = col_blocks * n_batches;
+  int64_t want = (512 + per_slab - 1) / per_slab;                                // >= 512 workgroups
+  for (int64_t s = want; s <= want + 8; ++s)
+    if (s * per_slab % 256 == 0) {
+      want = s;
+      break;
+    }
+  const int64_t max_slabs = (rows + 4 * kTy - 1) / (4 * kTy);                    // >= 4 rows per wave
   if (want > max_slabs) want = max_slabs;
   if (want < 1) want = 1;
   if (want > 64) want = 64;
@@ -66,15 +75,18 @@ __global__ __launch_bounds__(64 * kTy) void moments_partial_kernel(BatchPtrs xs,
   double acc[kColsPerLane];
 #pragma unroll
   for (int c = 0; c < kColsPerLane; ++c) acc[c] = 0.0;
-  uint32_t amax = 0;
+  // |bf16| bit patterns of finite values order like the magnitudes: the running maximum is kept
+  // as two 16-bit lanes of one register (even and odd columns), one packed max per two elements
+  typedef uint16_t u16x2 __attribute__((ext_vector_type(2)));
+  u16x2 amax2 = {0, 0};
   auto accumulate = [&](const uint4& v) {
     const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      float f0 = bf16_lo(w[j]), f1 = bf16_hi(w[j]);
-      acc[2 * j] += (double)(f0 * f0);
-      acc[2 * j + 1] += (double)(f1 * f1);
-      amax = max(amax, max(w[j] & 0x7FFFu, (w[j] >> 16) & 0x7FFFu));
+      const double d0 = (double)bf16_lo(w[j]), d1 = (double)bf16_hi(w[j]);
+      acc[2 * j] = fma(d0, d0, acc[2 * j]);          // the square is exact, one rounding per element
+      acc[2 * j + 1] = fma(d1, d1, acc[2 * j + 1]);
+      amax2 = __builtin_elementwise_max(amax2, __builtin_bit_cast(u16x2, w[j] & 0x7FFF7FFFu));
     }
   };
   if (col < K) {
@@ -92,7 +104,8 @@ __global__ __launch_bounds__(64 * kTy) void moments_partial_kernel(BatchPtrs xs,
   }
 #pragma unroll
   for (int c = 0; c < kColsPerLane; ++c) red[ty][lane][c] = acc[c];
-  // |bf16| bit patterns of finite values order like the magnitudes; widen to fp32 bits
+  // widen the larger of the two 16-bit maxima to fp32 bits
+  const uint32_t amax = max((uint32_t)amax2.x, (uint32_t)amax2.y);
   float fm = wave_max(as_f32(amax << 16));
   if (lane == 0) red_max[ty] = fm;
   __syncthreads();
@@ -112,25 +125,34 @@ __global__ __launch_bounds__(64 * kTy) void moments_partial_kernel(BatchPtrs xs,
   }
 }
 
+// sumsq[i] += sum of the partials of column i.  A workgroup covers 64 columns; its four waves
+// each add a contiguous quarter of the partials in order, and the four sums are combined in
+// wave order: the result does not depend on scheduling.
 __global__ __launch_bounds__(256) void moments_finish_kernel(const double* __restrict__ partial,
                                                             int n_partials, int64_t K,
                                                             double* __restrict__ sumsq,
                                                             const float* __restrict__ blockmax,
                                                             int n_blockmax, float* __restrict__ absmax) {
-  int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  __shared__ double quarter[4][64];
+  const int lane = threadIdx.x & 63, part = threadIdx.x >> 6;
+  const int64_t i = (int64_t)blockIdx.x * 64 + lane;
+  const int per = (n_partials + 3) / 4;
+  const int r0 = part * per, r1 = min(n_partials, r0 + per);
+  double s = 0.0;
   if (i < K) {
-    double s = 0.0;
-    int r = 0;
-    for (; r + 8 <= n_partials; r += 8) {          // independent loads, fixed order of additions
+    int r = r0;
+    for (; r + 8 <= r1; r += 8) {                  // independent loads, fixed order of additions
       double v[8];
 #pragma unroll
       for (int u = 0; u < 8; ++u) v[u] = partial[(int64_t)(r + u) * K + i];
 #pragma unroll
       for (int u = 0; u < 8; ++u) s += v[u];
     }
-    for (; r < n_partials; ++r) s += partial[(int64_t)r * K + i];
-    sumsq[i] += s;
+    for (; r < r1; ++r) s += partial[(int64_t)r * K + i];
   }
+  quarter[part][lane] = s;
+  __syncthreads();
+  if (part == 0 && i < K) sumsq[i] += ((quarter[0][lane] + quarter[1][lane]) + quarter[2][lane]) + quarter[3][lane];
   if (absmax && blockIdx.x == 0) {
     float m = 0.0f;
     for (int b = threadIdx.x; b < n_blockmax; b += 256) m = fmaxf(m, blockmax[b]);
@@ -161,7 +183,7 @@ int launch_moments(const void* const* xs, int n_batches, int64_t rows, int64_t K
                        blockmax);
     int rc = check_hip(hipGetLastError(), "moments_partial_kernel");
     if (rc) return rc;
-    hipLaunchKernelGGL(moments_finish_kernel, dim3((unsigned)((K + 255) / 256)), dim3(256), 0, st,
+    hipLaunchKernelGGL(moments_finish_kernel, dim3((unsigned)((K + 63) / 64)), dim3(256), 0, st,
                        (const double*)partial, nb * slabs, K, sumsq, (const float*)blockmax,
                        (int)blockmax_count(K, slabs, nb), absmax);
     rc = check_hip(hipGetLastError(), "moments_finish_kernel");

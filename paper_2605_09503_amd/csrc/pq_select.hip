@@ -9,12 +9,12 @@
 //                     (key_j == key_i and j < i)}; perm[rank(i)] = i.  O(K^2) compares, K <= 65536,
 //                     split over (channel block, key chunk, candidate) workgroups, integer
 //                     partial counts, no data-dependent control flow, fully deterministic.
-//   quant_error_kernel one workgroup per row: the row is staged in LDS once, then for every
-//                     candidate order its channels are gathered from LDS, quantized with the same
-//                     lane-cooperative quantizer as the runtime kernels, dequantized, and the
-//                     squared error accumulated in fp64.  HBM traffic is one read of the tensor
-//                     for all candidates.
-//   reduce_rows_kernel fixed-order sum of the per-row errors (deterministic).
+//   quant_error_kernel a workgroup stages a few rows in LDS at a time; for every candidate order
+//                     their channels are gathered from LDS (one read serves all resident rows),
+//                     quantized with the same lane-cooperative quantizer as the runtime kernels,
+//                     dequantized, and the squared error accumulated in fp64.  HBM traffic is one
+//                     read of the tensor for all candidates.
+//   reduce_rows_kernel fixed-order sum of the per-wave partial errors (deterministic).
 // The final argmin / acceptance decision is a handful of scalar operations and runs on the host.
 #include <string.h>
 
@@ -126,93 +126,159 @@ __global__ __launch_bounds__(256) void sum2_kernel(const double* __restrict__ a,
   }
 }
 
-__device__ __forceinline__ float e2m1_value(uint32_t idx) {
-  uint32_t e = idx >> 1, m = idx & 1u;
-  return e == 0 ? 0.5f * float(m) : as_f32(((e + 126u) << 23) | (m << 22));
-}
-
-// cands: [n_cand][K] int32, candidate c == -1 style identity is expressed by cands == nullptr
-// for c < first_perm.  row_err: [rows][n_cand] fp64.
+// up to kMaxMomentBatches tensors of equal shape handled by one launch
 struct TensorList {
   const uint16_t* p[kMaxMomentBatches];
 };
 
-// blockIdx.x = row inside a tensor, blockIdx.y = tensor of the list (equal shapes)
-template <int FMT, int G>
-__global__ __launch_bounds__(256) void quant_error_kernel(TensorList xs, int K,
+// fewest rows a workgroup of the error evaluation covers (bounds the number of partial sums)
+constexpr int kQeMinRowsPerBlock = 8;
+
+template <int R>
+struct FloatVec;
+template <>
+struct FloatVec<1> { typedef float type; };
+template <>
+struct FloatVec<2> { typedef float type __attribute__((ext_vector_type(2))); };
+template <>
+struct FloatVec<4> { typedef float type __attribute__((ext_vector_type(4))); };
+
+// Workgroup (x, y) evaluates rows [x * rows_per_block, (x + 1) * rows_per_block) of tensor y of
+// the list (equal shapes) for every candidate order.  R rows at a time are staged in LDS as
+// fp32, channel-major with the R rows of a channel adjacent (slot of channel e: e + e / 8, the
+// extra slot per 8 channels spreads the staging writes over the banks).  For a candidate, a
+// lane reads the eight channel indices of its chunk once and gathers the R rows of each channel
+// with one LDS read; the quantizer is the lane-cooperative one of the runtime kernels; squared
+// errors are accumulated in fp64 (every product below is exact in fp64).  Lane c of every wave
+// ends up with the wave's total for candidate c: part[((y * gridDim.x + x) * waves + wave) *
+// n_cand + c].
+template <int FMT, int G, int R>
+__global__ __launch_bounds__(512) void quant_error_kernel(TensorList xs, int rows, int K,
                                                           const int32_t* __restrict__ cands,
                                                           int n_cand, int identity_first, float T,
-                                                          double* __restrict__ row_err) {
-  extern __shared__ float row[];           // K floats
-  __shared__ double red[4];
-  const int64_t r = (int64_t)blockIdx.y * gridDim.x + blockIdx.x;     // row of the stacked tensors
-  const uint16_t* xr = xs.p[blockIdx.y] + (int64_t)blockIdx.x * K;
-  for (int c = threadIdx.x; c < K / 8; c += 256) {
-    uint4 p = *reinterpret_cast<const uint4*>(xr + (int64_t)c * 8);
-    float* d = row + c * 8;
-    d[0] = bf16_lo(p.x); d[1] = bf16_hi(p.x); d[2] = bf16_lo(p.y); d[3] = bf16_hi(p.y);
-    d[4] = bf16_lo(p.z); d[5] = bf16_hi(p.z); d[6] = bf16_lo(p.w); d[7] = bf16_hi(p.w);
-  }
-  __syncthreads();
-  const float encT = (FMT == kNvfp4) ? nv4_enc_scale(T) : 0.0f;
+                                                          int rows_per_block,
+                                                          double* __restrict__ part) {
+  typedef typename FloatVec<R>::type vec_t;
+  extern __shared__ __attribute__((aligned(16))) float slots[];     // (K + K / 8) * R floats
+  const int tid = threadIdx.x, nthr = blockDim.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const uint16_t* x = xs.p[blockIdx.y];
+  const int row0 = blockIdx.x * rows_per_block;
+  const int row_end = min(rows, row0 + rows_per_block);
   const int chunks = K / 8;
-  for (int cand = 0; cand < n_cand; ++cand) {
-    const int32_t* perm = nullptr;
-    if (!(identity_first && cand == 0)) perm = cands + (int64_t)(cand - identity_first) * K;
-    double err = 0.0;
-    for (int c0 = 0; c0 < chunks; c0 += 256) {
-      int c = c0 + threadIdx.x;
-      float v[8];
-      if (c < chunks) {
-        if (perm) {
-          const int4* pp = reinterpret_cast<const int4*>(perm + c * 8);
-          int4 i0 = pp[0], i1 = pp[1];
-          v[0] = row[i0.x]; v[1] = row[i0.y]; v[2] = row[i0.z]; v[3] = row[i0.w];
-          v[4] = row[i1.x]; v[5] = row[i1.y]; v[6] = row[i1.z]; v[7] = row[i1.w];
-        } else {
+  const float encT = (FMT == kNvfp4) ? nv4_enc_scale(T) : 0.0f;
+  double acc = 0.0;
+  for (int rg = row0; rg < row_end; rg += R) {
+    __syncthreads();                       // the previous rows have been read by every wave
+    for (int c = tid; c < chunks; c += nthr) {
+      float v[R][8];
 #pragma unroll
-          for (int j = 0; j < 8; ++j) v[j] = row[c * 8 + j];
-        }
-      } else {
-#pragma unroll
-        for (int j = 0; j < 8; ++j) v[j] = 0.0f;
+      for (int rr = 0; rr < R; ++rr) {
+        uint4 p = make_uint4(0u, 0u, 0u, 0u);       // rows past the end count as zero rows: error 0
+        if (rg + rr < row_end) p = *reinterpret_cast<const uint4*>(x + (int64_t)(rg + rr) * K + (int64_t)c * 8);
+        v[rr][0] = bf16_lo(p.x); v[rr][1] = bf16_hi(p.x); v[rr][2] = bf16_lo(p.y); v[rr][3] = bf16_hi(p.y);
+        v[rr][4] = bf16_lo(p.z); v[rr][5] = bf16_hi(p.z); v[rr][6] = bf16_lo(p.w); v[rr][7] = bf16_hi(p.w);
       }
-      float a = 0.0f;
 #pragma unroll
-      for (int j = 0; j < 8; ++j) a = fmaxf(a, fabsf(v[j]));
-      a = group_max<G / 8>(a);
-      if constexpr (FMT == kNvfp4) {
-        Nv4Scale s = nv4_scale(a, T, encT);
-        const double d = (double)e4m3_decode(s.byte) * (double)T;   // exact: 4 + 24 bits
+      for (int j = 0; j < 8; ++j) {
+        vec_t o;
+        if constexpr (R == 1) o = v[0][j];
+        else {
 #pragma unroll
-        for (int j = 0; j < 8; j += 2) {
-          // quantize two elements on the conversion unit and decode them again: q = +-E2M1 value
-          const uint32_t byte = nv4_code_pair(v[j], v[j + 1], s.inv);
-          const auto q = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(byte, 1.0f, 0);
-          const double e0 = fma(-(double)q[0], d, (double)v[j]);      // product exact: 2 + 28 bits
-          const double e1 = fma(-(double)q[1], d, (double)v[j + 1]);
-          err = fma(e0, e0, err);
-          err = fma(e1, e1, err);
+          for (int rr = 0; rr < R; ++rr) o[rr] = v[rr][j];
         }
-      } else {
-        constexpr float Q = qmax_of(FMT);
-        IntScale s = int_scale<FMT>(a);
-        const double sd = (double)s.s;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          const float t = int_code_value(v[j], s.inv, Q);
-          const double e = fma(-sd, (double)t, (double)v[j]);         // product exact: 24 + 3 bits
-          err = fma(e, e, err);
-        }
+        *reinterpret_cast<vec_t*>(slots + (size_t)(9 * c + j) * R) = o;
       }
     }
-    // block reduction in a fixed order: lanes by xor-tree, then the four waves in order
-    err = wave_sum(err);
-    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = err;
     __syncthreads();
-    if (threadIdx.x == 0) row_err[r * n_cand + cand] = (red[0] + red[1]) + (red[2] + red[3]);
-    __syncthreads();
+    for (int cand = 0; cand < n_cand; ++cand) {
+      const int32_t* perm = nullptr;
+      if (!(identity_first && cand == 0)) perm = cands + (int64_t)(cand - identity_first) * K;
+      double errs[R];                               // one chain per resident row
+#pragma unroll
+      for (int rr = 0; rr < R; ++rr) errs[rr] = 0.0;
+      for (int c0 = 0; c0 < chunks; c0 += nthr) {
+        const int c = c0 + tid;                     // every lane runs the group reduction
+        float v[R][8];
+        if (c < chunks) {
+          int slot[8];
+          if (perm) {
+            const int4* pp = reinterpret_cast<const int4*>(perm + c * 8);
+            const int4 i0 = pp[0], i1 = pp[1];
+            const int idx[8] = {i0.x, i0.y, i0.z, i0.w, i1.x, i1.y, i1.z, i1.w};
+#pragma unroll
+            for (int j = 0; j < 8; ++j) slot[j] = idx[j] + (idx[j] >> 3);
+          } else {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) slot[j] = 9 * c + j;
+          }
+#pragma unroll
+          for (int j = 0; j < 8; ++j) {
+            const vec_t g = *reinterpret_cast<const vec_t*>(slots + (size_t)slot[j] * R);
+            if constexpr (R == 1) v[0][j] = g;
+            else {
+#pragma unroll
+              for (int rr = 0; rr < R; ++rr) v[rr][j] = g[rr];
+            }
+          }
+        } else {
+#pragma unroll
+          for (int rr = 0; rr < R; ++rr)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v[rr][j] = 0.0f;
+        }
+        float amax[R];
+#pragma unroll
+        for (int rr = 0; rr < R; ++rr) {
+          float a = 0.0f;
+#pragma unroll
+          for (int j = 0; j < 8; ++j) a = fmaxf(a, fabsf(v[rr][j]));
+          amax[rr] = group_max<G / 8>(a);
+        }
+        if constexpr (FMT == kNvfp4) {
+          Nv4Scale s[R];
+          nv4_scales<R>(amax, T, encT, s);
+#pragma unroll
+          for (int rr = 0; rr < R; ++rr) {
+            const double d = (double)e4m3_decode(s[rr].byte) * (double)T;   // exact: 4 + 24 bits
+#pragma unroll
+            for (int j = 0; j < 8; j += 2) {
+              // quantize two elements on the conversion unit and decode them again: q = +-E2M1 value
+              const uint32_t byte = nv4_code_pair(v[rr][j], v[rr][j + 1], s[rr].inv);
+              const auto q = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(byte, 1.0f, 0);
+              const double e0 = fma(-(double)q[0], d, (double)v[rr][j]);      // product exact: 2 + 28 bits
+              const double e1 = fma(-(double)q[1], d, (double)v[rr][j + 1]);
+              errs[rr] = fma(e0, e0, errs[rr]);
+              errs[rr] = fma(e1, e1, errs[rr]);
+            }
+          }
+        } else {
+          IntScale s[R];
+          int_scales<FMT, R>(amax, s);
+#pragma unroll
+          for (int rr = 0; rr < R; ++rr) {
+            const double sd = (double)s[rr].s;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+              // The clip of the quantizer cannot act here: amax is the true maximum of the group, so
+              // |x * inv| <= Q (1 + 3 * 2^-24) < Q + 1/2 and the rounding already lands on +-Q
+              // (inv = 0 gives 0).  Adding and subtracting 1.5 * 2^23 rounds to the nearest integer.
+              const float t = (v[rr][j] * s[rr].inv + 12582912.0f) - 12582912.0f;
+              const double e = fma(-sd, (double)t, (double)v[rr][j]);       // product exact: 24 + 3 bits
+              errs[rr] = fma(e, e, errs[rr]);
+            }
+          }
+        }
+      }
+      double err = errs[0];
+#pragma unroll
+      for (int rr = 1; rr < R; ++rr) err += errs[rr];
+      err = wave_sum(err);                 // fixed xor-tree order
+      if (lane == cand) acc += err;
+    }
   }
+  if (lane < n_cand)
+    part[(((int64_t)blockIdx.y * gridDim.x + blockIdx.x) * (nthr >> 6) + wave) * n_cand + lane] = acc;
 }
 
 // out[seg][c] = sum over the rows of segment seg of row_err[r][c]; one workgroup per
@@ -234,36 +300,81 @@ __global__ __launch_bounds__(256) void reduce_rows_kernel(const double* __restri
   if (threadIdx.x == 0) out[(int64_t)blockIdx.y * out_stride + c] = red[0];
 }
 
-template <int FMT, int G>
-static int launch_qe(const TensorList& xs, int n_tensors, int64_t rows, int K, const int32_t* cands,
-                     int n_cand, int identity_first, float T, double* row_err, hipStream_t st) {
-  size_t shmem = (size_t)K * sizeof(float);
-  auto kern = quant_error_kernel<FMT, G>;
-  if (shmem > 48 * 1024) {
+// Launch shape of the error evaluation for `rows` rows per tensor of width K.
+struct QeShape {
+  int r;                 // rows resident in LDS together (1, 2 or 4)
+  int threads;           // a multiple of 64 that divides K / 8 when one exists
+  int rows_per_block;
+  int blocks;            // per tensor
+  size_t shmem;
+  int parts() const { return blocks * (threads / 64); }    // partial sums per tensor and candidate
+};
+
+static QeShape qe_shape(int64_t rows, int64_t K, int n_tensors) {
+  QeShape q;
+  const size_t slot_floats = (size_t)(K + K / 8);
+  q.r = slot_floats * 16 <= 64 * 1024 ? 4 : slot_floats * 8 <= 64 * 1024 ? 2 : 1;
+  const int chunks = (int)(K / 8);
+  q.threads = 256;
+  for (int t : {512, 384, 256, 192, 128, 64})
+    if (chunks % t == 0) {
+      q.threads = t;
+      break;
+    }
+  if (chunks < 64) q.threads = 64;
+  // enough workgroups to fill the chip several times over, at least kQeMinRowsPerBlock rows each
+  int64_t rpb = rows * n_tensors / 2048;
+  rpb = rpb / q.r * q.r;
+  if (rpb < kQeMinRowsPerBlock) rpb = kQeMinRowsPerBlock;
+  if (rpb > 64) rpb = 64;
+  q.rows_per_block = (int)rpb;
+  q.blocks = (int)((rows + rpb - 1) / rpb);
+  q.shmem = slot_floats * q.r * sizeof(float);
+  return q;
+}
+
+template <int FMT, int G, int R>
+static int launch_qe_r(const TensorList& xs, int n_tensors, int64_t rows, int K, const QeShape& q,
+                       const int32_t* cands, int n_cand, int identity_first, float T, double* part,
+                       hipStream_t st) {
+  auto kern = quant_error_kernel<FMT, G, R>;
+  if (q.shmem > 48 * 1024) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)q.shmem);
     if (e != hipSuccess) return check_hip(e, "hipFuncSetAttribute(quant_error_kernel)");
   }
-  hipLaunchKernelGGL(kern, dim3((unsigned)rows, (unsigned)n_tensors), dim3(256), shmem, st, xs, K, cands,
-                     n_cand, identity_first, T, row_err);
+  hipLaunchKernelGGL(kern, dim3((unsigned)q.blocks, (unsigned)n_tensors), dim3(q.threads), q.shmem, st, xs,
+                     (int)rows, K, cands, n_cand, identity_first, T, q.rows_per_block, part);
   return check_hip(hipGetLastError(), "quant_error_kernel");
 }
 
+template <int FMT, int G>
+static int launch_qe(const TensorList& xs, int n_tensors, int64_t rows, int K, const QeShape& q,
+                     const int32_t* cands, int n_cand, int identity_first, float T, double* part,
+                     hipStream_t st) {
+  switch (q.r) {
+    case 4: return launch_qe_r<FMT, G, 4>(xs, n_tensors, rows, K, q, cands, n_cand, identity_first, T, part, st);
+    case 2: return launch_qe_r<FMT, G, 2>(xs, n_tensors, rows, K, q, cands, n_cand, identity_first, T, part, st);
+    default: return launch_qe_r<FMT, G, 1>(xs, n_tensors, rows, K, q, cands, n_cand, identity_first, T, part, st);
+  }
+}
+
+// part: [n_tensors][q.parts()][n_cand]
 static int launch_quant_error(pq_format fmt, int group, const TensorList& x, int n_tensors, int64_t rows,
-                              int K, const int32_t* cands, int n_cand, int identity_first, float T,
-                              double* row_err, hipStream_t st) {
+                              int K, const QeShape& q, const int32_t* cands, int n_cand,
+                              int identity_first, float T, double* part, hipStream_t st) {
   if (rows > 0x7FFFFFFF) return fail(PQ_ERR_SHAPE, "too many rows");
-  if ((size_t)K * 4 > 150 * 1024) return fail(PQ_ERR_SHAPE, "K=%d too large for the LDS-resident row", K);
+  if (q.shmem > 150 * 1024) return fail(PQ_ERR_SHAPE, "K=%d too large for the LDS-resident row", K);
   if (fmt == PQ_FMT_NVFP4)
-    return launch_qe<kNvfp4, 16>(x, n_tensors, rows, K, cands, n_cand, identity_first, T, row_err, st);
-#define PQ_INT_CASE(F, FE)                                                                          \
-  if (fmt == F) {                                                                                   \
-    switch (group) {                                                                                \
-      case 32: return launch_qe<FE, 32>(x, n_tensors, rows, K, cands, n_cand, identity_first, T, row_err, st);  \
-      case 64: return launch_qe<FE, 64>(x, n_tensors, rows, K, cands, n_cand, identity_first, T, row_err, st);  \
-      case 128: return launch_qe<FE, 128>(x, n_tensors, rows, K, cands, n_cand, identity_first, T, row_err, st); \
-      case 256: return launch_qe<FE, 256>(x, n_tensors, rows, K, cands, n_cand, identity_first, T, row_err, st); \
-    }                                                                                               \
+    return launch_qe<kNvfp4, 16>(x, n_tensors, rows, K, q, cands, n_cand, identity_first, T, part, st);
+#define PQ_INT_CASE(F, FE)                                                                                  \
+  if (fmt == F) {                                                                                           \
+    switch (group) {                                                                                        \
+      case 32: return launch_qe<FE, 32>(x, n_tensors, rows, K, q, cands, n_cand, identity_first, T, part, st);   \
+      case 64: return launch_qe<FE, 64>(x, n_tensors, rows, K, q, cands, n_cand, identity_first, T, part, st);   \
+      case 128: return launch_qe<FE, 128>(x, n_tensors, rows, K, q, cands, n_cand, identity_first, T, part, st); \
+      case 256: return launch_qe<FE, 256>(x, n_tensors, rows, K, q, cands, n_cand, identity_first, T, part, st); \
+    }                                                                                                       \
   }
   PQ_INT_CASE(PQ_FMT_INT4, kInt4)
   PQ_INT_CASE(PQ_FMT_INT3, kInt3)
@@ -276,7 +387,7 @@ struct SelectWs {
   double* keys;      // [PQ_MAX_ALPHAS][K]
   int32_t* cands;    // [PQ_MAX_ALPHAS][K]
   int32_t* part;     // [PQ_MAX_ALPHAS][chunks][K] partial ranks
-  double* row_err;   // [n_batches * M + N][kMaxCand]
+  double* row_err;   // partial error sums: [n_batches][parts(M)][n_cand], then [parts(N)][n_cand]
   double* sums;      // [(n_batches + 1) * kMaxCand + 2] : per-batch errors, weight errors, |X|^2, |W|^2
   int* moved;        // [PQ_MAX_ALPHAS]
 };
@@ -293,7 +404,9 @@ static size_t carve_select(void* base, int64_t M, int64_t N, int64_t K, int n_ba
   size_t o_keys = take((size_t)PQ_MAX_ALPHAS * K * 8);
   size_t o_cands = take((size_t)PQ_MAX_ALPHAS * K * 4);
   size_t o_part = take((size_t)PQ_MAX_ALPHAS * rank_chunks(K) * K * 4);
-  size_t o_rowerr = take((size_t)((int64_t)n_batches * M + N) * kMaxCand * 8);
+  // a workgroup covers at least kQeMinRowsPerBlock rows with at most 8 waves: no more partial sums
+  // than rows + 8 per tensor
+  size_t o_rowerr = take((size_t)((int64_t)n_batches * (M + 8) + (N + 8)) * kMaxCand * 8);
   size_t o_sums = take(((size_t)(n_batches + 1) * kMaxCand + 2) * 8);
   size_t o_moved = take((size_t)PQ_MAX_ALPHAS * 4);
   if (w) {
@@ -312,16 +425,17 @@ size_t select_workspace_bytes(int64_t M, int64_t N, int64_t K, int n_batches) {
   return carve_select(nullptr, M, N, K, n_batches, nullptr);
 }
 
-size_t quant_error_workspace_bytes(int64_t rows) { return align_up((size_t)rows * 8, 256); }
+size_t quant_error_workspace_bytes(int64_t rows) { return align_up((size_t)(rows + 8) * 8, 256); }
 
 int run_quant_error(pq_format fmt, int group, const void* x, int64_t rows, int64_t K,
                     const int32_t* perm, float ts, double* err_out, void* ws, hipStream_t st) {
-  double* row_err = (double*)ws;
+  double* part = (double*)ws;
   TensorList tl;
   for (int b = 0; b < kMaxMomentBatches; ++b) tl.p[b] = (const uint16_t*)x;
-  int rc = launch_quant_error(fmt, group, tl, 1, rows, (int)K, perm, 1, perm ? 0 : 1, ts, row_err, st);
+  const QeShape q = qe_shape(rows, K, 1);
+  int rc = launch_quant_error(fmt, group, tl, 1, rows, (int)K, q, perm, 1, perm ? 0 : 1, ts, part, st);
   if (rc) return rc;
-  hipLaunchKernelGGL(reduce_rows_kernel, dim3(1, 1), dim3(256), 0, st, row_err, rows, 1, 1, err_out);
+  hipLaunchKernelGGL(reduce_rows_kernel, dim3(1, 1), dim3(256), 0, st, part, (int64_t)q.parts(), 1, 1, err_out);
   return check_hip(hipGetLastError(), "reduce_rows_kernel");
 }
 
@@ -346,23 +460,25 @@ int run_select(pq_format fmt, int group, const double* act_sumsq, const double* 
   hipLaunchKernelGGL(count_moved_kernel, dim3(n_alpha), dim3(256), 0, st, W.cands, (int)K, W.moved);
   double* sums = W.sums;
   // activations: all batches of a launch share one grid (up to kMaxMomentBatches per launch)
+  const QeShape qa = qe_shape(M, K, n_batches < kMaxMomentBatches ? n_batches : kMaxMomentBatches);
   for (int b0 = 0; b0 < n_batches; b0 += kMaxMomentBatches) {
     const int nb = n_batches - b0 < kMaxMomentBatches ? n_batches - b0 : kMaxMomentBatches;
     TensorList tl;
     for (int b = 0; b < kMaxMomentBatches; ++b) tl.p[b] = (const uint16_t*)x_calib[b0 + (b < nb ? b : 0)];
-    rc = launch_quant_error(fmt, group, tl, nb, M, (int)K, W.cands, n_cand, 1, act_ts,
-                            W.row_err + (size_t)b0 * M * n_cand, st);
+    rc = launch_quant_error(fmt, group, tl, nb, M, (int)K, qa, W.cands, n_cand, 1, act_ts,
+                            W.row_err + (size_t)b0 * qa.parts() * n_cand, st);
     if (rc) return rc;
   }
-  hipLaunchKernelGGL(reduce_rows_kernel, dim3(n_cand, n_batches), dim3(256), 0, st, W.row_err, M, n_cand,
-                     kMaxCand, sums);
-  double* w_row_err = W.row_err + (size_t)n_batches * M * n_cand;
+  hipLaunchKernelGGL(reduce_rows_kernel, dim3(n_cand, n_batches), dim3(256), 0, st, W.row_err,
+                     (int64_t)qa.parts(), n_cand, kMaxCand, sums);
+  double* w_part = W.row_err + (size_t)n_batches * qa.parts() * n_cand;
+  const QeShape qw = qe_shape(N, K, 1);
   TensorList wl;
   for (int b = 0; b < kMaxMomentBatches; ++b) wl.p[b] = (const uint16_t*)w;
-  rc = launch_quant_error(fmt, group, wl, 1, N, (int)K, W.cands, n_cand, 1, w_ts, w_row_err, st);
+  rc = launch_quant_error(fmt, group, wl, 1, N, (int)K, qw, W.cands, n_cand, 1, w_ts, w_part, st);
   if (rc) return rc;
-  hipLaunchKernelGGL(reduce_rows_kernel, dim3(n_cand, 1), dim3(256), 0, st, w_row_err, N, n_cand, kMaxCand,
-                     sums + (size_t)n_batches * kMaxCand);
+  hipLaunchKernelGGL(reduce_rows_kernel, dim3(n_cand, 1), dim3(256), 0, st, w_part, (int64_t)qw.parts(),
+                     n_cand, kMaxCand, sums + (size_t)n_batches * kMaxCand);
   double* tot = sums + (size_t)(n_batches + 1) * kMaxCand;
   hipLaunchKernelGGL(sum2_kernel, dim3(1), dim3(256), 0, st, act_sumsq, w_sumsq, K, tot);
   if ((rc = check_hip(hipGetLastError(), "error reduction kernels"))) return rc;
