@@ -8,13 +8,14 @@
 //                     stable descending sort by counting: rank(i) = #{j : key_j > key_i or
 //                     (key_j == key_i and j < i)}; perm[rank(i)] = i.  O(K^2) compares, K <= 65536,
 //                     split over (channel block, key chunk, candidate) workgroups, integer
-//                     partial counts, no data-dependent control flow, fully deterministic.
+//                     counts added atomically, fully deterministic.
 //   quant_error_kernel a workgroup stages a few rows in LDS at a time; for every candidate order
 //                     their channels are gathered from LDS (one read serves all resident rows),
 //                     quantized with the same lane-cooperative quantizer as the runtime kernels,
 //                     dequantized, and the squared error accumulated in fp64.  HBM traffic is one
 //                     read of the tensor for all candidates.
-//   reduce_rows_kernel fixed-order sum of the per-wave partial errors (deterministic).
+//   select_tail_kernel fixed-order sums of the per-wave partial errors, of the moments and of the
+//                     moved-channel counts (deterministic), one launch.
 // The final argmin / acceptance decision is a handful of scalar operations and runs on the host.
 #include <string.h>
 
@@ -34,9 +35,11 @@ struct AlphaList {
 // key[j][i] for every alpha_j of the grid (blockIdx.y = j)
 __global__ __launch_bounds__(256) void key_kernel(const double* __restrict__ sa,
                                                   const double* __restrict__ sw, int64_t K,
-                                                  AlphaList alphas, double* __restrict__ key) {
+                                                  AlphaList alphas, double* __restrict__ key,
+                                                  int32_t* __restrict__ rank) {
   int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (i >= K) return;
+  rank[(int64_t)blockIdx.y * K + i] = 0;          // the counting pass adds to it
   const double alpha = alphas.a[blockIdx.y];
   double k = 0.0;
   if (alpha != 0.0) k += alpha * log(sa[i]);
@@ -44,86 +47,53 @@ __global__ __launch_bounds__(256) void key_kernel(const double* __restrict__ sa,
   key[(int64_t)blockIdx.y * K + i] = k;
 }
 
-constexpr int kRankChunk = 1024;   // keys compared per workgroup of the counting pass
+constexpr int kRankChunk = 256;    // keys compared per workgroup of the counting pass
 
 // Counting pass of the stable descending sort: workgroup (x, y, z) compares its 256 channels i
-// with the keys j of chunk y of candidate z and writes how many of them sort before i.
+// with the 256 keys j of chunk y of candidate z and adds how many of them sort before i to
+// rank[z][i] (integer atomics: the sum does not depend on the order of the workgroups).
+// Chunks are aligned with the channel blocks, so every key of an earlier chunk has j < i (it
+// sorts before i when key_j >= key_i), every key of a later chunk has j > i (key_j > key_i), and
+// only the diagonal workgroup needs the index comparison: one compare and one add per key.
 __global__ __launch_bounds__(256) void rank_count_kernel(const double* __restrict__ keys, int K,
-                                                         int n_chunks, int32_t* __restrict__ part) {
+                                                         int32_t* __restrict__ rank) {
   __shared__ double tile[kRankChunk];
   const double* key = keys + (int64_t)blockIdx.z * K;
   const int i = blockIdx.x * 256 + threadIdx.x;
   const int j0 = blockIdx.y * kRankChunk;
   const int n = min(kRankChunk, K - j0);
-  for (int t = threadIdx.x; t < n; t += 256) tile[t] = key[j0 + t];
+  if ((int)threadIdx.x < n) tile[threadIdx.x] = key[j0 + threadIdx.x];
   __syncthreads();
   if (i >= K) return;
   const double ki = key[i];
   int before = 0;
-  int t = 0;
-  for (; t + 8 <= n; t += 8) {              // eight LDS reads in flight per trip
-    double kj[8];
-#pragma unroll
-    for (int u = 0; u < 8; ++u) kj[u] = tile[t + u];
-#pragma unroll
-    for (int u = 0; u < 8; ++u) before += (kj[u] > ki || (kj[u] == ki && j0 + t + u < i)) ? 1 : 0;
+  if (blockIdx.y < blockIdx.x) {
+#pragma unroll 8
+    for (int t = 0; t < n; ++t) before += tile[t] >= ki ? 1 : 0;
+  } else if (blockIdx.y > blockIdx.x) {
+#pragma unroll 8
+    for (int t = 0; t < n; ++t) before += tile[t] > ki ? 1 : 0;
+  } else {
+#pragma unroll 8
+    for (int t = 0; t < n; ++t) {
+      const double kj = tile[t];
+      before += (kj > ki || (kj == ki && j0 + t < i)) ? 1 : 0;
+    }
   }
-  for (; t < n; ++t) {
-    const double kj = tile[t];
-    before += (kj > ki || (kj == ki && j0 + t < i)) ? 1 : 0;
-  }
-  part[((int64_t)blockIdx.z * n_chunks + blockIdx.y) * K + i] = before;
+  atomicAdd(&rank[(int64_t)blockIdx.z * K + i], before);
 }
 
-// perm[z][rank(i)] = i with rank(i) the sum of the chunk counts
-__global__ __launch_bounds__(256) void rank_scatter_kernel(const int32_t* __restrict__ part, int K,
-                                                           int n_chunks, int32_t* __restrict__ perms) {
+// perm[z][rank(i)] = i
+__global__ __launch_bounds__(256) void rank_scatter_kernel(const int32_t* __restrict__ rank, int K,
+                                                           int32_t* __restrict__ perms) {
   const int i = blockIdx.x * 256 + threadIdx.x;
   if (i >= K) return;
-  int rank = 0;
-  for (int c = 0; c < n_chunks; ++c) rank += part[((int64_t)blockIdx.y * n_chunks + c) * K + i];
-  perms[(int64_t)blockIdx.y * K + rank] = i;
+  perms[(int64_t)blockIdx.y * K + rank[(int64_t)blockIdx.y * K + i]] = i;
 }
 
 __global__ __launch_bounds__(256) void iota_kernel(int32_t* p, int K) {
   int i = blockIdx.x * 256 + threadIdx.x;
   if (i < K) p[i] = i;
-}
-
-// moved[c] = number of positions where cand c differs from the identity
-__global__ __launch_bounds__(256) void count_moved_kernel(const int32_t* __restrict__ cands, int K,
-                                                          int* __restrict__ moved) {
-  const int32_t* p = cands + (int64_t)blockIdx.x * K;
-  int n = 0;
-  for (int i = threadIdx.x; i < K; i += 256) n += (p[i] != i);
-  __shared__ int red[256];
-  red[threadIdx.x] = n;
-  __syncthreads();
-  for (int s = 128; s > 0; s >>= 1) {
-    if (threadIdx.x < s) red[threadIdx.x] += red[threadIdx.x + s];
-    __syncthreads();
-  }
-  if (threadIdx.x == 0) moved[blockIdx.x] = red[0];
-}
-
-// out[0] = sum(a[0..K)), out[1] = sum(b[0..K)), fixed order
-__global__ __launch_bounds__(256) void sum2_kernel(const double* __restrict__ a,
-                                                   const double* __restrict__ b, int64_t K,
-                                                   double* __restrict__ out) {
-  __shared__ double red[256];
-  for (int which = 0; which < 2; ++which) {
-    const double* p = which ? b : a;
-    double s = 0.0;
-    for (int64_t i = threadIdx.x; i < K; i += 256) s += p[i];
-    red[threadIdx.x] = s;
-    __syncthreads();
-    for (int st = 128; st > 0; st >>= 1) {
-      if (threadIdx.x < st) red[threadIdx.x] += red[threadIdx.x + st];
-      __syncthreads();
-    }
-    if (threadIdx.x == 0) out[which] = red[0];
-    __syncthreads();
-  }
 }
 
 // up to kMaxMomentBatches tensors of equal shape handled by one launch
@@ -257,14 +227,17 @@ __global__ __launch_bounds__(512) void quant_error_kernel(TensorList xs, int row
           int_scales<FMT, R>(amax, s);
 #pragma unroll
           for (int rr = 0; rr < R; ++rr) {
-            const double sd = (double)s[rr].s;
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
               // The clip of the quantizer cannot act here: amax is the true maximum of the group, so
               // |x * inv| <= Q (1 + 3 * 2^-24) < Q + 1/2 and the rounding already lands on +-Q
               // (inv = 0 gives 0).  Adding and subtracting 1.5 * 2^23 rounds to the nearest integer.
               const float t = (v[rr][j] * s[rr].inv + 12582912.0f) - 12582912.0f;
-              const double e = fma(-sd, (double)t, (double)v[rr][j]);       // product exact: 24 + 3 bits
+              // v - s t is exact in binary32: for t != 0 both terms are multiples of the last place
+              // of s and the difference is at most about s / 2, so it needs no more than 24 bits;
+              // the fused multiply-add returns it unrounded
+              const float e32 = __builtin_fmaf(-s[rr].s, t, v[rr][j]);
+              const double e = (double)e32;
               errs[rr] = fma(e, e, errs[rr]);
             }
           }
@@ -298,6 +271,58 @@ __global__ __launch_bounds__(256) void reduce_rows_kernel(const double* __restri
     __syncthreads();
   }
   if (threadIdx.x == 0) out[(int64_t)blockIdx.y * out_stride + c] = red[0];
+}
+
+// Everything the host needs for the decision, in one launch.  Workgroup b of the grid computes
+// one fixed-order sum (per-thread strided partial sums, then a binary tree) into out[]:
+//   b <  n_cand * n_batches         error of candidate b % n_cand on calibration batch b / n_cand
+//                                   -> out[batch * kMaxCand + cand]
+//   next n_cand                     error of the candidate on the weights -> out[n_batches * kMaxCand + cand]
+//   next 2                          sum of act_sumsq, sum of w_sumsq      -> out[(n_batches + 1) * kMaxCand + 0 / 1]
+//   next n_alpha                    number of channels candidate j moves  -> out[... + 2 + j] (as a double)
+struct TailArgs {
+  const double* x_part;     // [n_batches][x_parts][n_cand]
+  const double* w_part;     // [w_parts][n_cand]
+  const double* act_sumsq;
+  const double* w_sumsq;
+  const int32_t* cands;     // [n_alpha][K]
+  int64_t x_parts, w_parts, K;
+  int n_cand, n_batches, n_alpha;
+};
+
+__global__ __launch_bounds__(256) void select_tail_kernel(TailArgs a, double* __restrict__ out) {
+  __shared__ double red[256];
+  const int n_x = a.n_cand * a.n_batches;
+  int b = blockIdx.x;
+  double s = 0.0;
+  int64_t dst;
+  if (b < n_x + a.n_cand) {
+    const bool is_w = b >= n_x;
+    const int seg = is_w ? 0 : b / a.n_cand, c = is_w ? b - n_x : b % a.n_cand;
+    const int64_t n = is_w ? a.w_parts : a.x_parts;
+    const double* base = is_w ? a.w_part : a.x_part + (int64_t)seg * n * a.n_cand;
+    for (int64_t r = threadIdx.x; r < n; r += 256) s += base[r * a.n_cand + c];
+    dst = (int64_t)(is_w ? a.n_batches : seg) * kMaxCand + c;
+  } else if (b < n_x + a.n_cand + 2) {
+    const int which = b - n_x - a.n_cand;
+    const double* p = which ? a.w_sumsq : a.act_sumsq;
+    for (int64_t i = threadIdx.x; i < a.K; i += 256) s += p[i];
+    dst = (int64_t)(a.n_batches + 1) * kMaxCand + which;
+  } else {
+    const int j = b - n_x - a.n_cand - 2;
+    const int32_t* p = a.cands + (int64_t)j * a.K;
+    int n = 0;
+    for (int64_t i = threadIdx.x; i < a.K; i += 256) n += (p[i] != (int32_t)i);
+    s = (double)n;                                    // small integers: every sum below is exact
+    dst = (int64_t)(a.n_batches + 1) * kMaxCand + 2 + j;
+  }
+  red[threadIdx.x] = s;
+  __syncthreads();
+  for (int st = 128; st > 0; st >>= 1) {
+    if (threadIdx.x < st) red[threadIdx.x] += red[threadIdx.x + st];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) out[dst] = red[0];
 }
 
 // Launch shape of the error evaluation for `rows` rows per tensor of width K.
@@ -386,10 +411,10 @@ static int launch_quant_error(pq_format fmt, int group, const TensorList& x, int
 struct SelectWs {
   double* keys;      // [PQ_MAX_ALPHAS][K]
   int32_t* cands;    // [PQ_MAX_ALPHAS][K]
-  int32_t* part;     // [PQ_MAX_ALPHAS][chunks][K] partial ranks
+  int32_t* rank;     // [PQ_MAX_ALPHAS][K] position of every channel in the sorted order
   double* row_err;   // partial error sums: [n_batches][parts(M)][n_cand], then [parts(N)][n_cand]
-  double* sums;      // [(n_batches + 1) * kMaxCand + 2] : per-batch errors, weight errors, |X|^2, |W|^2
-  int* moved;        // [PQ_MAX_ALPHAS]
+  double* sums;      // [(n_batches + 1) * kMaxCand + 2 + PQ_MAX_ALPHAS]: per-batch errors, weight
+                     // errors, |X|^2, |W|^2, moved-channel counts
 };
 
 static int rank_chunks(int64_t K) { return (int)((K + kRankChunk - 1) / kRankChunk); }
@@ -403,20 +428,18 @@ static size_t carve_select(void* base, int64_t M, int64_t N, int64_t K, int n_ba
   };
   size_t o_keys = take((size_t)PQ_MAX_ALPHAS * K * 8);
   size_t o_cands = take((size_t)PQ_MAX_ALPHAS * K * 4);
-  size_t o_part = take((size_t)PQ_MAX_ALPHAS * rank_chunks(K) * K * 4);
+  size_t o_rank = take((size_t)PQ_MAX_ALPHAS * K * 4);
   // a workgroup covers at least kQeMinRowsPerBlock rows with at most 8 waves: no more partial sums
   // than rows + 8 per tensor
   size_t o_rowerr = take((size_t)((int64_t)n_batches * (M + 8) + (N + 8)) * kMaxCand * 8);
-  size_t o_sums = take(((size_t)(n_batches + 1) * kMaxCand + 2) * 8);
-  size_t o_moved = take((size_t)PQ_MAX_ALPHAS * 4);
+  size_t o_sums = take(((size_t)(n_batches + 1) * kMaxCand + 2 + PQ_MAX_ALPHAS) * 8);
   if (w) {
     char* b = (char*)base;
     w->keys = (double*)(b + o_keys);
     w->cands = (int32_t*)(b + o_cands);
-    w->part = (int32_t*)(b + o_part);
+    w->rank = (int32_t*)(b + o_rank);
     w->row_err = (double*)(b + o_rowerr);
     w->sums = (double*)(b + o_sums);
-    w->moved = (int*)(b + o_moved);
   }
   return off;
 }
@@ -451,13 +474,11 @@ int run_select(pq_format fmt, int group, const double* act_sumsq, const double* 
   int rc;
   AlphaList al;
   for (int j = 0; j < PQ_MAX_ALPHAS; ++j) al.a[j] = j < n_alpha ? alphas[j] : 0.0;
-  hipLaunchKernelGGL(key_kernel, dim3(kb, n_alpha), dim3(256), 0, st, act_sumsq, w_sumsq, K, al, W.keys);
-  hipLaunchKernelGGL(rank_count_kernel, dim3(kb, chunks, n_alpha), dim3(256), 0, st, W.keys, (int)K, chunks,
-                     W.part);
-  hipLaunchKernelGGL(rank_scatter_kernel, dim3(kb, n_alpha), dim3(256), 0, st, W.part, (int)K, chunks,
-                     W.cands);
+  hipLaunchKernelGGL(key_kernel, dim3(kb, n_alpha), dim3(256), 0, st, act_sumsq, w_sumsq, K, al, W.keys,
+                     W.rank);
+  hipLaunchKernelGGL(rank_count_kernel, dim3(kb, chunks, n_alpha), dim3(256), 0, st, W.keys, (int)K, W.rank);
+  hipLaunchKernelGGL(rank_scatter_kernel, dim3(kb, n_alpha), dim3(256), 0, st, W.rank, (int)K, W.cands);
   if ((rc = check_hip(hipGetLastError(), "key/rank kernels"))) return rc;
-  hipLaunchKernelGGL(count_moved_kernel, dim3(n_alpha), dim3(256), 0, st, W.cands, (int)K, W.moved);
   double* sums = W.sums;
   // activations: all batches of a launch share one grid (up to kMaxMomentBatches per launch)
   const QeShape qa = qe_shape(M, K, n_batches < kMaxMomentBatches ? n_batches : kMaxMomentBatches);
@@ -469,30 +490,25 @@ int run_select(pq_format fmt, int group, const double* act_sumsq, const double* 
                             W.row_err + (size_t)b0 * qa.parts() * n_cand, st);
     if (rc) return rc;
   }
-  hipLaunchKernelGGL(reduce_rows_kernel, dim3(n_cand, n_batches), dim3(256), 0, st, W.row_err,
-                     (int64_t)qa.parts(), n_cand, kMaxCand, sums);
   double* w_part = W.row_err + (size_t)n_batches * qa.parts() * n_cand;
   const QeShape qw = qe_shape(N, K, 1);
   TensorList wl;
   for (int b = 0; b < kMaxMomentBatches; ++b) wl.p[b] = (const uint16_t*)w;
   rc = launch_quant_error(fmt, group, wl, 1, N, (int)K, qw, W.cands, n_cand, 1, w_ts, w_part, st);
   if (rc) return rc;
-  hipLaunchKernelGGL(reduce_rows_kernel, dim3(n_cand, 1), dim3(256), 0, st, w_part, (int64_t)qw.parts(),
-                     n_cand, kMaxCand, sums + (size_t)n_batches * kMaxCand);
-  double* tot = sums + (size_t)(n_batches + 1) * kMaxCand;
-  hipLaunchKernelGGL(sum2_kernel, dim3(1), dim3(256), 0, st, act_sumsq, w_sumsq, K, tot);
-  if ((rc = check_hip(hipGetLastError(), "error reduction kernels"))) return rc;
+  TailArgs ta{W.row_err, w_part, act_sumsq, w_sumsq, W.cands, qa.parts(), qw.parts(), K, n_cand, n_batches, n_alpha};
+  hipLaunchKernelGGL(select_tail_kernel, dim3((unsigned)(n_cand * (n_batches + 1) + 2 + n_alpha)), dim3(256), 0,
+                     st, ta, sums);
+  if ((rc = check_hip(hipGetLastError(), "select_tail_kernel"))) return rc;
 
-  const size_t n_sums = (size_t)(n_batches + 1) * kMaxCand + 2;
+  const size_t n_tot = (size_t)(n_batches + 1) * kMaxCand;      // offset of the two totals
+  const size_t n_sums = n_tot + 2 + (size_t)n_alpha;
   std::vector<double> h(n_sums);
-  int h_moved[PQ_MAX_ALPHAS];
   if ((rc = check_hip(hipMemcpyAsync(h.data(), sums, n_sums * 8, hipMemcpyDeviceToHost, st), "copy sums")))
-    return rc;
-  if ((rc = check_hip(hipMemcpyAsync(h_moved, W.moved, n_alpha * 4, hipMemcpyDeviceToHost, st), "copy flags")))
     return rc;
   if ((rc = check_hip(hipStreamSynchronize(st), "hipStreamSynchronize"))) return rc;
 
-  const double sum_x2 = h[n_sums - 2], sum_w2 = h[n_sums - 1];
+  const double sum_x2 = h[n_tot], sum_w2 = h[n_tot + 1];
   double E[kMaxCand];
   for (int c = 0; c < n_cand; ++c) {
     double ex = 0.0;
@@ -504,7 +520,7 @@ int run_select(pq_format fmt, int group, const double* act_sumsq, const double* 
   for (int j = 1; j < n_alpha; ++j)
     if (E[1 + j] < E[1 + best]) best = j;         // first minimum: smallest alpha on ties
   const double e_orig = E[0], e_best = E[1 + best];
-  const bool accepted = h_moved[best] != 0 && e_orig > 0.0 && ((e_orig - e_best) / e_orig > tau);
+  const bool accepted = h[n_tot + 2 + best] != 0.0 && e_orig > 0.0 && ((e_orig - e_best) / e_orig > tau);
   memset(report, 0, sizeof(*report));
   report->accepted = accepted ? 1 : 0;
   report->alpha_index = best;
