@@ -277,6 +277,60 @@ def test_quant_error(fmt, g):
         np.testing.assert_allclose(out.item(), ref, rtol=T.ERRSUM_RTOL)
 
 
+# Shapes that walk the launch variants of the error evaluation: one, two or four rows resident in
+# LDS (by K), workgroup sizes that do and do not divide K / 8, row counts with ragged tails.
+@pytest.mark.parametrize("fmt,g,rows,K", [
+    (pq.FMT_NVFP4, 16, 5, 272),       # 34 chunks of 8: a single wave with idle lanes
+    (pq.FMT_INT4, 32, 13, 4096),      # two rows resident
+    (pq.FMT_INT4, 64, 9, 8192),       # one row resident
+    (pq.FMT_INT3, 32, 70, 3072),      # four rows resident, 384 threads, 70 = 4 * 17 + 2 rows
+    (pq.FMT_NVFP4, 16, 3, 12288),     # widest configuration, fewer rows than a workgroup covers
+    (pq.FMT_INT4, 256, 1, 256),       # one row, one group
+])
+def test_quant_error_launch_variants(fmt, g, rows, K):
+    _say("quant_error variants fmt=%d g=%d rows=%d K=%d" % (fmt, g, rows, K))
+    rng = np.random.default_rng(900 + K + rows)
+    bits = _rand_bits(rng, rows, K)
+    x = _to_dev(bits)
+    x64 = OF.bf16_bits_to_f64(bits)
+    ts = float(OQ.nvfp4_tensor_scale(OC.absmax(x64))) if fmt == pq.FMT_NVFP4 else 1.0
+    perm = rng.permutation(K).astype(np.int32)
+    out = torch.zeros(1, dtype=torch.float64, device=DEV)
+    for p in (None, perm):
+        pq.pq_quant_error(fmt, g, x, None if p is None else torch.from_numpy(p).to(DEV), ts, out)
+        torch.cuda.synchronize()
+        ref = OC.squared_error(fmt, g, x64, p, np.float32(ts) if fmt == pq.FMT_NVFP4 else None)
+        np.testing.assert_allclose(out.item(), ref, rtol=T.ERRSUM_RTOL)
+
+
+def test_select_perm_equal_keys_across_sort_chunks():
+    """Two key values alternating over 1280 channels (five 256-key chunks of the counting sort):
+    the stable descending order is all even channels, then all odd ones.  Every alpha gives the
+    same order, so a threshold below any gain returns exactly that order."""
+    K, M, N = 1280, 24, 40
+    pattern = np.where(np.arange(K) % 2 == 0, 1.0, 0.25)
+    rng = np.random.default_rng(77)
+    xb = synth.f64_to_bf16_bits(np.sign(rng.standard_normal((M, K))) * pattern[None, :])
+    wb = synth.f64_to_bf16_bits(np.sign(rng.standard_normal((N, K))) * pattern[None, :])
+    xs = [_to_dev(xb)]
+    w = _to_dev(wb)
+    sa, sw, _, _ = _gpu_moments(xs, w, K)
+    want = np.concatenate([np.arange(0, K, 2), np.arange(1, K, 2)]).astype(np.int32)
+    for a in OC.DEFAULT_ALPHAS:
+        np.testing.assert_array_equal(OC.sort_descending(OC.joint_key(sa.cpu().numpy(), sw.cpu().numpy(), a)), want)
+    perm_out = torch.empty(K, dtype=torch.int32, device=DEV)
+    rep = pq.pq_select_perm(pq.FMT_INT4, 64, sa, sw, xs, w, 1.0, 1.0, perm_out, tau=-1e30)
+    torch.cuda.synchronize()
+    # groups of equal magnitudes leave only the rounding of the scale amax / Q as error
+    x64, w64 = OF.bf16_bits_to_f64(xb), OF.bf16_bits_to_f64(wb)
+    e_ref = (OC.squared_error(pq.FMT_INT4, 64, x64, want, None) / np.sum(x64 * x64)
+             + OC.squared_error(pq.FMT_INT4, 64, w64, want, None) / np.sum(w64 * w64))
+    assert rep.accepted and rep.alpha_index == 0 and rep.e_orig > 1e-4
+    assert e_ref < 1e-12
+    np.testing.assert_allclose(rep.e_best, e_ref, rtol=T.ERRSUM_RTOL)
+    np.testing.assert_array_equal(perm_out.cpu().numpy(), want)
+
+
 # ----------------------------------------------------------------------------------- GEMM
 
 def _gemm_case(fmt, g, M, N, K, seed, ldy_pad=0):
