@@ -42,6 +42,10 @@ def quant_bytes_per_elem(fmt, g):
     return 2.0 + 0.5 + (1.0 / 16 if fmt == 0 else 4.0 / g)
 
 
+def qbytes_out(fmt, g, M, K):
+    return (0.5 + (1.0 / 16 if fmt == 0 else 4.0 / g)) * M * K
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -162,6 +166,29 @@ def main():
     t_fwd = time_calls(lambda i: forward(), it)
     t_qw = time_calls(lambda i: pq.pq_quantize_weights(fmt, g, w, perm, w_codes, w_scales, ts_w), 5)
     t_cal = time_calls(lambda i: calibrate(), 3)
+    ta_h = ts_a.item() if fmt == pq.FMT_NVFP4 else 1.0
+    tw_h = ts_w.item() if fmt == pq.FMT_NVFP4 else 1.0
+    t_sel = time_calls(lambda i: pq.pq_select_perm(fmt, g, sa, sw, xs, w, ta_h, tw_h, perm, workspace=ws_sel), 3)
+
+    # references measured in the same run: a plain streaming kernel with the footprint of the
+    # quantizer (reads the bf16 tensor, writes codes + scales) and of the moments pass (reads
+    # only), on the same rotating inputs; and the matrix rate the device sustains on an
+    # MFMA-only loop at the clock it holds under that load
+    qout = torch.empty(int(qbytes_out(fmt, g, M, K)) // 16 * 16 + 16, dtype=torch.uint8, device=dev)
+    in_bytes = M * K * 2
+    pool = [x_run] + [torch.empty_like(x_run).copy_(x_run) for _ in range(n_rot - 1)]
+    t_floor_q = time_calls(lambda i: pq.pq_probe_stream(pool[i % n_rot], in_bytes, qout, qout.numel() - 16),
+                           max(it, n_rot))
+    t_floor_m = time_calls(lambda i: pq.pq_probe_stream(pool[i % n_rot], in_bytes, qout, 0), max(it, n_rot))
+    del pool
+    xcat = torch.cat([b.reshape(-1) for b in xs])            # the calibration set as one buffer
+    t_floor_mall = time_calls(lambda i: pq.pq_probe_stream(xcat, xcat.numel() * 2, qout, 0), 10)
+    del xcat
+    sink = torch.empty(256 * 512, dtype=torch.float32, device=dev)
+    mfma_iters = 4000
+    mfma_flops = pq.pq_probe_mfma(mfma_iters, sink)
+    t_mfma = time_calls(lambda i: pq.pq_probe_mfma(mfma_iters, sink), 5)
+    mfma_sustained = mfma_flops / t_mfma / 1e12
 
     qbytes = quant_bytes_per_elem(fmt, g) * M * K
     mbytes = 2.0 * M * K
@@ -182,6 +209,13 @@ def main():
         "forward_quantize_act_plus_qgemm": {"us": t_fwd * 1e6, "tflops": flops / t_fwd / 1e12},
         "quantize_weights": {"us": t_qw * 1e6},
         "calibrate_moments_plus_select": {"us": t_cal * 1e6},
+        "select_perm": {"us": t_sel * 1e6,
+                        "element_evaluations_per_s": 7.0 * (nb * M + N) * K / t_sel},
+        # same-run references (not part of the path)
+        "reference_stream_quantizer_footprint_cold": {"us": t_floor_q * 1e6, "gbs": qbytes / t_floor_q / 1e9},
+        "reference_stream_read_one_batch_cold": {"us": t_floor_m * 1e6, "gbs": mbytes / t_floor_m / 1e9},
+        "reference_stream_read_all_batches": {"us": t_floor_mall * 1e6, "gbs": nb * mbytes / t_floor_mall / 1e9},
+        "reference_mfma_only_loop": {"tflops": mfma_sustained, "frac_mfma_f16_peak": mfma_sustained / MFMA_F16_PEAK_TFLOPS},
     }
     for k, v in kernels.items():
         log("  %-34s %s" % (k, json.dumps({a: round(b, 4) for a, b in v.items()})))

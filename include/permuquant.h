@@ -236,6 +236,24 @@ int pq_qgemm_f32(pq_format fmt, int group, const uint8_t* a_codes, const void* a
                  const float* w_tensor_scale, int64_t M, int64_t N, int64_t K, float* y_f32,
                  int64_t ldy, void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * Measurement aids (no part of the method; they give the timings of the kernels above a
+ * reference measured on the same device in the same run).
+ *
+ * pq_probe_stream: a plain streaming kernel that reads read_bytes from src and writes
+ * write_bytes to dst (16 bytes per lane and access, no arithmetic worth naming) -- the time a
+ * bandwidth-bound kernel with that footprint cannot beat.  Both sizes multiples of 16; src, dst
+ * device buffers of at least those sizes, 16-byte aligned, may not overlap.
+ *
+ * pq_probe_mfma: every compute unit runs `iters` rounds of 8 independent
+ * v_mfma_f32_32x32x16_f16 per wave (8 waves per unit, operands in registers, no memory
+ * traffic); flops_out[0] (host double, may be NULL) receives the number of floating-point
+ * operations issued, so that flops / time is the matrix rate the device sustains at the clock
+ * it holds under that load.  sink: float [256 * 512] device buffer.
+ */
+int pq_probe_stream(const void* src, size_t read_bytes, void* dst, size_t write_bytes, void* stream);
+int pq_probe_mfma(int iters, float* sink, double* flops_out, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

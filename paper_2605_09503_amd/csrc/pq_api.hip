@@ -256,4 +256,22 @@ int pq_qgemm_f32(pq_format fmt, int group, const uint8_t* a_codes, const void* a
                       w_tensor_scale, M, N, K, y_f32, ldy, true, 3, workspace, workspace_bytes, stream);
 }
 
+int pq_probe_stream(const void* src, size_t read_bytes, void* dst, size_t write_bytes, void* stream) {
+  if ((read_bytes && !src) || (write_bytes && !dst))
+    return fail(PQ_ERR_NULL, "pq_probe_stream: NULL buffer with a non-zero size");
+  if (read_bytes % 16 || write_bytes % 16)
+    return fail(PQ_ERR_SHAPE, "pq_probe_stream: sizes must be multiples of 16 bytes");
+  if (!aligned16(src) || !aligned16(dst))
+    return fail(PQ_ERR_SHAPE, "pq_probe_stream: buffers must be 16-byte aligned");
+  if (write_bytes == 0 && read_bytes && !dst)
+    return fail(PQ_ERR_NULL, "pq_probe_stream: dst must be a valid 16-byte buffer even when nothing is written");
+  return launch_probe_stream(src, read_bytes, dst, write_bytes, (hipStream_t)stream);
+}
+
+int pq_probe_mfma(int iters, float* sink, double* flops_out, void* stream) {
+  if (!sink) return fail(PQ_ERR_NULL, "pq_probe_mfma: sink must not be NULL");
+  if (iters <= 0 || iters > (1 << 24)) return fail(PQ_ERR_SHAPE, "pq_probe_mfma: iters=%d out of range", iters);
+  return launch_probe_mfma(iters, sink, flops_out, (hipStream_t)stream);
+}
+
 }  // extern "C"

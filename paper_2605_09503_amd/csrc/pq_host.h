@@ -53,4 +53,8 @@ int run_qgemm(pq_format fmt, int group, const uint8_t* a_codes, const void* a_sc
               int64_t M, int64_t N, int64_t K, void* y, int64_t ldy, bool out_f32, int phases,
               void* ws, hipStream_t st);   // phases: 1 = scale preparation, 2 = product
 
+
+int launch_probe_stream(const void* src, size_t read_bytes, void* dst, size_t write_bytes, hipStream_t st);
+int launch_probe_mfma(int iters, float* sink, double* flops_out, hipStream_t st);
+
 }  // namespace pq

@@ -61,7 +61,7 @@ __device__ __forceinline__ void store_scale(void* scales, int64_t g, uint32_t s)
   else reinterpret_cast<uint32_t*>(scales)[g] = s;
 }
 
-constexpr int kFlatUnroll = 4;
+constexpr int kFlatUnroll = 2;
 
 template <int FMT, int G>
 __global__ __launch_bounds__(256) void quantize_flat_kernel(const uint4* __restrict__ x,

@@ -68,8 +68,11 @@ def load():
     lib.pq_qgemm_f32.argtypes = gemm_args
     lib.pq_qgemm_run.argtypes = gemm_args
     lib.pq_qgemm_prep.argtypes = [i32, i32, vp, vp, i64, i64, i64, vp, sz, vp]
+    lib.pq_probe_stream.argtypes = [vp, sz, vp, sz, vp]
+    lib.pq_probe_mfma.argtypes = [i32, vp, C.POINTER(C.c_double), vp]
     for name in ("pq_calib_moments", "pq_calib_moments_batched", "pq_select_perm", "pq_quant_error", "pq_quantize_weights",
-                 "pq_quantize_act", "pq_qgemm", "pq_qgemm_f32", "pq_qgemm_run", "pq_qgemm_prep"):
+                 "pq_quantize_act", "pq_qgemm", "pq_qgemm_f32", "pq_qgemm_run", "pq_qgemm_prep", "pq_probe_stream",
+                 "pq_probe_mfma"):
         getattr(lib, name).restype = i32
     _lib = lib
     return lib
@@ -239,6 +242,18 @@ def pq_qgemm_f32(fmt: int, group: int, a_codes, a_scales, a_tensor_scale, w_code
     """Same product, fp32 output (accumulator before the bf16 rounding)."""
     _gemm(load().pq_qgemm_f32, fmt, group, a_codes, a_scales, a_tensor_scale, w_codes, w_scales,
           w_tensor_scale, y, workspace, M, N, K, ldy)
+
+
+def pq_probe_stream(src: torch.Tensor, read_bytes: int, dst: torch.Tensor, write_bytes: int) -> None:
+    """Plain streaming kernel: reads read_bytes of src, writes write_bytes of dst."""
+    _check(load().pq_probe_stream(_ptr(src), read_bytes, _ptr(dst), write_bytes, _stream()))
+
+
+def pq_probe_mfma(iters: int, sink: torch.Tensor) -> float:
+    """Matrix-pipe-only loop on every compute unit; returns the floating-point operations issued."""
+    flops = C.c_double(0.0)
+    _check(load().pq_probe_mfma(iters, _ptr(sink), C.byref(flops), _stream()))
+    return flops.value
 
 
 # ------------------------------------------------------------------------ allocation helpers
