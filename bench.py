@@ -3,8 +3,9 @@
 
 A step is one pass of the whole hot path over one synthetic layer:
   calibration moments of every calibration batch and of W -> permutation selection ->
-  weight quantization in the selected order -> dynamic activation quantization of one token
-  batch -> low-bit GEMM with bf16 output.
+  weight quantization in the selected order (+ packing into the GEMM's operand layout) ->
+  dynamic activation quantization of one token batch (straight into that layout) ->
+  low-bit GEMM with bf16 output.
 Inputs are generated once (seeded, synthetic, FLUX-DiT-shaped) and are resident in HBM before
 the timed region.  One JSON line goes to stdout; everything else goes to stderr.
 
@@ -95,6 +96,8 @@ def main():
                          dtype=torch.uint8, device=dev)
     ws_sel = torch.empty(pq.pq_workspace_bytes(pq.OP_SELECT_PERM, fmt, g, M, N, K, nb), dtype=torch.uint8, device=dev)
     ws_gemm = torch.empty(max(pq.pq_workspace_bytes(pq.OP_QGEMM, fmt, g, M, N, K), 16), dtype=torch.uint8, device=dev)
+    a_op = torch.empty(max(pq.pq_operand_bytes(fmt, g, M, K), 16), dtype=torch.uint8, device=dev)   # GEMM operands
+    w_op = torch.empty(max(pq.pq_operand_bytes(fmt, g, N, K), 16), dtype=torch.uint8, device=dev)
 
     def calibrate():
         sa.zero_(); sw.zero_(); amax_a.zero_(); amax_w.zero_()
@@ -115,13 +118,19 @@ def main():
     log("selection: accepted=%s alpha_index=%d E_orig=%.6g E_best=%.6g" %
         (rep.accepted, rep.alpha_index, rep.e_orig, rep.e_best))
 
+    # forward path: the activation quantizer writes the GEMM's panel layout directly, the
+    # weights were packed into it offline
     def forward():
-        pq.pq_quantize_act(fmt, g, x_run, None, ts_a, a_codes, a_scales)
-        pq.pq_qgemm(fmt, g, a_codes, a_scales, ts_a, w_codes, w_scales, ts_w, y, workspace=ws_gemm)
+        pq.pq_quantize_act_packed(fmt, g, x_run, ts_a, a_op)
+        pq.pq_qgemm_packed(fmt, g, a_op, ts_a, w_op, ts_w, y, M, N, K)
+
+    def prepare_weights():
+        pq.pq_quantize_weights(fmt, g, w, perm, w_codes, w_scales, ts_w)
+        pq.pq_pack_operand(fmt, g, w_codes, w_scales, w_op)
 
     def step():
         calibrate()
-        pq.pq_quantize_weights(fmt, g, w, perm, w_codes, w_scales, ts_w)
+        prepare_weights()
         forward()
 
     for _ in range(args.warmup):
@@ -147,24 +156,31 @@ def main():
         return e0.elapsed_time(e1) * 1e-3 / iters            # seconds per call
 
     it = args.kernel_iters
-    # the product kernel alone (scale preparation done once before), and the whole call
+    # the product kernel on packed operands (what the forward path runs); for comparison the same
+    # kernel on the quantizers' row-major layout, alone and with its INT scale preparation
+    t_gemm = time_calls(lambda i: pq.pq_qgemm_packed(fmt, g, a_op, ts_a, w_op, ts_w, y, M, N, K), it)
+    pq.pq_quantize_act(fmt, g, x_run, None, ts_a, a_codes, a_scales)
     pq.pq_qgemm_prep(fmt, g, a_scales, w_scales, M, N, K, ws_gemm)
-    t_gemm = time_calls(lambda i: pq.pq_qgemm_run(fmt, g, a_codes, a_scales, ts_a, w_codes, w_scales, ts_w, y,
-                                                  workspace=ws_gemm), it)
+    t_gemm_rm = time_calls(lambda i: pq.pq_qgemm_run(fmt, g, a_codes, a_scales, ts_a, w_codes, w_scales, ts_w, y,
+                                                     workspace=ws_gemm), it)
     t_gemm_call = time_calls(lambda i: pq.pq_qgemm(fmt, g, a_codes, a_scales, ts_a, w_codes, w_scales, ts_w, y,
                                                    workspace=ws_gemm), it)
-    t_qa_warm = time_calls(lambda i: pq.pq_quantize_act(fmt, g, x_run, None, ts_a, a_codes, a_scales), it)
+    t_pack_a = time_calls(lambda i: pq.pq_pack_operand(fmt, g, a_codes, a_scales, a_op), it)
+    t_qa_warm = time_calls(lambda i: pq.pq_quantize_act_packed(fmt, g, x_run, ts_a, a_op), it)
+    t_qa_rm_warm = time_calls(lambda i: pq.pq_quantize_act(fmt, g, x_run, None, ts_a, a_codes, a_scales), it)
     # cold: rotate through > 1 GB of distinct inputs so that no input is cache-resident
     n_rot = max(2, int(1.2e9 // (M * K * 2)) + 1)
     pool = [x_run] + [torch.empty_like(x_run).copy_(x_run) for _ in range(n_rot - 1)]
-    t_qa_cold = time_calls(lambda i: pq.pq_quantize_act(fmt, g, pool[i % n_rot], None, ts_a, a_codes, a_scales),
-                           max(it, n_rot))
+    t_qa_cold = time_calls(lambda i: pq.pq_quantize_act_packed(fmt, g, pool[i % n_rot], ts_a, a_op), max(it, n_rot))
+    t_qa_rm_cold = time_calls(lambda i: pq.pq_quantize_act(fmt, g, pool[i % n_rot], None, ts_a, a_codes, a_scales),
+                              max(it, n_rot))
+    forward()                       # leave a_op / y as the forward path produces them
     t_mom_cold = time_calls(lambda i: pq.pq_calib_moments(pool[i % n_rot], sa, None, ws_mom), max(it, n_rot))
     t_mom_warm = time_calls(lambda i: pq.pq_calib_moments(x_run, sa, None, ws_mom), it)
     del pool
     t_mom_all = time_calls(lambda i: pq.pq_calib_moments_batched(xs, sa, amax_a, ws_mom), 10)
     t_fwd = time_calls(lambda i: forward(), it)
-    t_qw = time_calls(lambda i: pq.pq_quantize_weights(fmt, g, w, perm, w_codes, w_scales, ts_w), 5)
+    t_qw = time_calls(lambda i: prepare_weights(), 5)
     t_cal = time_calls(lambda i: calibrate(), 3)
     ta_h = ts_a.item() if fmt == pq.FMT_NVFP4 else 1.0
     tw_h = ts_w.item() if fmt == pq.FMT_NVFP4 else 1.0
@@ -195,11 +211,17 @@ def main():
     gemm_tflops = flops / t_gemm / 1e12
     kernels = {
         "qgemm_kernel": {"us": t_gemm * 1e6, "tflops": gemm_tflops, "frac_mfma_f16_peak": gemm_tflops / MFMA_F16_PEAK_TFLOPS},
-        "qgemm_call_with_scale_prep": {"us": t_gemm_call * 1e6, "tflops": flops / t_gemm_call / 1e12},
+        "qgemm_kernel_row_major_operands": {"us": t_gemm_rm * 1e6, "tflops": flops / t_gemm_rm / 1e12},
+        "qgemm_call_row_major_with_scale_prep": {"us": t_gemm_call * 1e6, "tflops": flops / t_gemm_call / 1e12},
+        "pack_operand_activations": {"us": t_pack_a * 1e6},
         "quantize_act_warm": {"us": t_qa_warm * 1e6, "gbs": qbytes / t_qa_warm / 1e9,
                               "frac_hbm_peak": qbytes / t_qa_warm / 1e9 / HBM_PEAK_GBS},
         "quantize_act_cold": {"us": t_qa_cold * 1e6, "gbs": qbytes / t_qa_cold / 1e9,
                               "frac_hbm_peak": qbytes / t_qa_cold / 1e9 / HBM_PEAK_GBS},
+        "quantize_act_row_major_warm": {"us": t_qa_rm_warm * 1e6, "gbs": qbytes / t_qa_rm_warm / 1e9,
+                                        "frac_hbm_peak": qbytes / t_qa_rm_warm / 1e9 / HBM_PEAK_GBS},
+        "quantize_act_row_major_cold": {"us": t_qa_rm_cold * 1e6, "gbs": qbytes / t_qa_rm_cold / 1e9,
+                                        "frac_hbm_peak": qbytes / t_qa_rm_cold / 1e9 / HBM_PEAK_GBS},
         "calib_moments_warm": {"us": t_mom_warm * 1e6, "gbs": mbytes / t_mom_warm / 1e9,
                                "frac_hbm_peak": mbytes / t_mom_warm / 1e9 / HBM_PEAK_GBS},
         "calib_moments_cold": {"us": t_mom_cold * 1e6, "gbs": mbytes / t_mom_cold / 1e9,
@@ -207,7 +229,7 @@ def main():
         "calib_moments_all_batches": {"us": t_mom_all * 1e6, "gbs": nb * mbytes / t_mom_all / 1e9,
                                       "frac_hbm_peak": nb * mbytes / t_mom_all / 1e9 / HBM_PEAK_GBS},
         "forward_quantize_act_plus_qgemm": {"us": t_fwd * 1e6, "tflops": flops / t_fwd / 1e12},
-        "quantize_weights": {"us": t_qw * 1e6},
+        "quantize_weights_and_pack": {"us": t_qw * 1e6},
         "calibrate_moments_plus_select": {"us": t_cal * 1e6},
         "select_perm": {"us": t_sel * 1e6,
                         "element_evaluations_per_s": 7.0 * (nb * M + N) * K / t_sel},
@@ -302,8 +324,8 @@ def main():
         "dtype": "f16",
         "data": "synthetic",
         "config": {"workload": "%s: %s" % (args.config, WORKLOADS[args.config]),
-                   "step": "moments of all calibration batches and W, select_perm, quantize_weights, "
-                           "quantize_act, qgemm; value = 2*M*N*K / step time",
+                   "step": "moments of all calibration batches and W, select_perm, quantize_weights + pack_operand, "
+                           "quantize_act_packed, qgemm_packed; value = 2*M*N*K / step time",
                    "format": ["nvfp4", "int4", "int3"][fmt], "group": g, "M": M, "N": N, "K": K,
                    "calib_batches": nb, "accepted": bool(rep.accepted)},
         "roofline": {"bound": "mfma", "kernel": "qgemm_kernel", "achieved": gemm_tflops,

@@ -237,6 +237,37 @@ int pq_qgemm_f32(pq_format fmt, int group, const uint8_t* a_codes, const void* a
                  int64_t ldy, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * The same product from operands in the GEMM's own layout (paper Eq. 8; Sec. 3.3: the weights
+ * are prepared offline).  pq_pack_operand rearranges the stored output of a quantizer -- codes
+ * [rows, K/2] and scales [rows, K/group] -- into a K-step-major panel in which the 64-k pieces
+ * of consecutive rows are adjacent, and for INT also applies the scale preparation of
+ * pq_qgemm_prep.  Pack the weights once; pack the activations once per forward; then
+ *     pq_qgemm_packed(pack(A), pack(W)) == pq_qgemm(A, W)      bit for bit,
+ * with the product kernel reading whole cache lines instead of 32-byte pieces.
+ *
+ * operand: device buffer of pq_operand_bytes(fmt, group, rows, K) bytes (0 for an invalid
+ * shape), 16-byte aligned, written by pq_pack_operand; its layout is private to the library.
+ * K must be a multiple of 32.  Tensor scales as for pq_qgemm (NVFP4 only).
+ *
+ * pq_quantize_act_packed is pq_quantize_act (no gather: the producer emits the selected channel
+ * order) writing the panel directly, so that the forward path has no packing pass: the operand
+ * it leaves is byte for byte pq_pack_operand of pq_quantize_act's output.  codes / scales:
+ * optional row-major copies as pq_quantize_act stores them (both or neither; NULL to skip).
+ */
+size_t pq_operand_bytes(pq_format fmt, int group, int64_t rows, int64_t K);
+int pq_quantize_act_packed(pq_format fmt, int group, const void* x_bf16, int64_t M, int64_t K,
+                           int64_t ld, const float* tensor_scale, void* operand, size_t operand_size,
+                           uint8_t* codes, void* scales, void* stream);
+int pq_pack_operand(pq_format fmt, int group, const uint8_t* codes, const void* scales, int64_t rows,
+                    int64_t K, void* operand, size_t operand_size, void* stream);
+int pq_qgemm_packed(pq_format fmt, int group, const void* a_operand, const float* a_tensor_scale,
+                    const void* w_operand, const float* w_tensor_scale, int64_t M, int64_t N, int64_t K,
+                    void* y_bf16, int64_t ldy, void* stream);
+int pq_qgemm_packed_f32(pq_format fmt, int group, const void* a_operand, const float* a_tensor_scale,
+                        const void* w_operand, const float* w_tensor_scale, int64_t M, int64_t N,
+                        int64_t K, float* y_f32, int64_t ldy, void* stream);
+
+/*
  * Measurement aids (no part of the method; they give the timings of the kernels above a
  * reference measured on the same device in the same run).
  *

@@ -256,6 +256,89 @@ int pq_qgemm_f32(pq_format fmt, int group, const uint8_t* a_codes, const void* a
                       w_tensor_scale, M, N, K, y_f32, ldy, true, 3, workspace, workspace_bytes, stream);
 }
 
+size_t pq_operand_bytes(pq_format fmt, int group, int64_t rows, int64_t K) {
+  if (check_format(fmt, group, K) || rows <= 0 || K % 32) return 0;
+  return operand_bytes(fmt, group, rows, K);
+}
+
+int pq_pack_operand(pq_format fmt, int group, const uint8_t* codes, const void* scales, int64_t rows,
+                    int64_t K, void* operand, size_t operand_size, void* stream) {
+  if (!codes || !scales || !operand) return fail(PQ_ERR_NULL, "pq_pack_operand: a required pointer is NULL");
+  int rc = check_format(fmt, group, K);
+  if (rc) return rc;
+  if (rows <= 0) return fail(PQ_ERR_SHAPE, "pq_pack_operand: rows=%lld must be positive", (long long)rows);
+  if (K % 32) return fail(PQ_ERR_SHAPE, "pq_pack_operand: K=%lld must be a multiple of 32", (long long)K);
+  if (rows > (1 << 24) || K > (1 << 24)) return fail(PQ_ERR_SHAPE, "pq_pack_operand: a dimension exceeds 2^24");
+  if (!aligned16(codes) || !aligned16(scales) || !aligned16(operand))
+    return fail(PQ_ERR_SHAPE, "pq_pack_operand: buffers must be 16-byte aligned");
+  const size_t need = operand_bytes(fmt, group, rows, K);
+  if (operand_size < need)
+    return fail(PQ_ERR_WORKSPACE, "pq_pack_operand: operand buffer of %zu bytes needed, %zu given", need,
+                operand_size);
+  return run_pack_operand(fmt, group, codes, scales, rows, K, operand, as_stream(stream));
+}
+
+int pq_quantize_act_packed(pq_format fmt, int group, const void* x, int64_t M, int64_t K, int64_t ld,
+                           const float* tensor_scale, void* operand, size_t operand_size,
+                           uint8_t* codes, void* scales, void* stream) {
+  if (!x || !operand) return fail(PQ_ERR_NULL, "pq_quantize_act_packed: a required pointer is NULL");
+  if ((codes == nullptr) != (scales == nullptr))
+    return fail(PQ_ERR_NULL, "pq_quantize_act_packed: give both of codes and scales or neither");
+  int rc = check_format(fmt, group, K);
+  if (rc) return rc;
+  if (fmt == PQ_FMT_NVFP4 && !tensor_scale)
+    return fail(PQ_ERR_NULL, "pq_quantize_act_packed: NVFP4 needs the per-tensor scale");
+  if (M <= 0) return fail(PQ_ERR_SHAPE, "pq_quantize_act_packed: M=%lld must be positive", (long long)M);
+  if (K % 32) return fail(PQ_ERR_SHAPE, "pq_quantize_act_packed: K=%lld must be a multiple of 32", (long long)K);
+  if (M > (1 << 24) || K > (1 << 24)) return fail(PQ_ERR_SHAPE, "pq_quantize_act_packed: a dimension exceeds 2^24");
+  if (ld < K || ld % 8)
+    return fail(PQ_ERR_SHAPE, "pq_quantize_act_packed: ld=%lld must be >= K=%lld and a multiple of 8",
+                (long long)ld, (long long)K);
+  if (!aligned16(x) || !aligned16(operand) || !aligned16(codes) || !aligned16(scales))
+    return fail(PQ_ERR_SHAPE, "pq_quantize_act_packed: buffers must be 16-byte aligned");
+  const size_t need = operand_bytes(fmt, group, M, K);
+  if (operand_size < need)
+    return fail(PQ_ERR_WORKSPACE, "pq_quantize_act_packed: operand buffer of %zu bytes needed, %zu given", need,
+                operand_size);
+  return run_quantize_packed(fmt, group, x, M, K, ld, tensor_scale, operand, codes, scales, as_stream(stream));
+}
+
+static int qgemm_packed_common(pq_format fmt, int group, const void* a_operand, const float* a_ts,
+                               const void* w_operand, const float* w_ts, int64_t M, int64_t N, int64_t K,
+                               void* y, int64_t ldy, bool out_f32, void* stream) {
+  if (!a_operand || !w_operand || !y) return fail(PQ_ERR_NULL, "pq_qgemm_packed: a required pointer is NULL");
+  int rc = check_format(fmt, group, K);
+  if (rc) return rc;
+  if (fmt == PQ_FMT_NVFP4 && (!a_ts || !w_ts))
+    return fail(PQ_ERR_NULL, "pq_qgemm_packed: NVFP4 needs both per-tensor scales");
+  if (M <= 0 || N <= 0) return fail(PQ_ERR_SHAPE, "pq_qgemm_packed: M=%lld N=%lld must be positive",
+                                    (long long)M, (long long)N);
+  if (K % 32) return fail(PQ_ERR_SHAPE, "pq_qgemm_packed: K=%lld must be a multiple of 32", (long long)K);
+  if (M > (1 << 24) || N > (1 << 24) || K > (1 << 24))
+    return fail(PQ_ERR_SHAPE, "pq_qgemm_packed: a dimension exceeds 2^24");
+  if (ldy < N || ldy % 8)
+    return fail(PQ_ERR_SHAPE, "pq_qgemm_packed: ldy=%lld must be >= N=%lld and a multiple of 8",
+                (long long)ldy, (long long)N);
+  if (!aligned16(a_operand) || !aligned16(w_operand) || !aligned16(y))
+    return fail(PQ_ERR_SHAPE, "pq_qgemm_packed: buffers must be 16-byte aligned");
+  return run_qgemm_packed(fmt, group, a_operand, a_ts, w_operand, w_ts, M, N, K, y, ldy, out_f32,
+                          as_stream(stream));
+}
+
+int pq_qgemm_packed(pq_format fmt, int group, const void* a_operand, const float* a_tensor_scale,
+                    const void* w_operand, const float* w_tensor_scale, int64_t M, int64_t N, int64_t K,
+                    void* y_bf16, int64_t ldy, void* stream) {
+  return qgemm_packed_common(fmt, group, a_operand, a_tensor_scale, w_operand, w_tensor_scale, M, N, K,
+                             y_bf16, ldy, false, stream);
+}
+
+int pq_qgemm_packed_f32(pq_format fmt, int group, const void* a_operand, const float* a_tensor_scale,
+                        const void* w_operand, const float* w_tensor_scale, int64_t M, int64_t N,
+                        int64_t K, float* y_f32, int64_t ldy, void* stream) {
+  return qgemm_packed_common(fmt, group, a_operand, a_tensor_scale, w_operand, w_tensor_scale, M, N, K,
+                             y_f32, ldy, true, stream);
+}
+
 int pq_probe_stream(const void* src, size_t read_bytes, void* dst, size_t write_bytes, void* stream) {
   if ((read_bytes && !src) || (write_bytes && !dst))
     return fail(PQ_ERR_NULL, "pq_probe_stream: NULL buffer with a non-zero size");
@@ -265,13 +348,13 @@ int pq_probe_stream(const void* src, size_t read_bytes, void* dst, size_t write_
     return fail(PQ_ERR_SHAPE, "pq_probe_stream: buffers must be 16-byte aligned");
   if (write_bytes == 0 && read_bytes && !dst)
     return fail(PQ_ERR_NULL, "pq_probe_stream: dst must be a valid 16-byte buffer even when nothing is written");
-  return launch_probe_stream(src, read_bytes, dst, write_bytes, (hipStream_t)stream);
+  return launch_probe_stream(src, read_bytes, dst, write_bytes, as_stream(stream));
 }
 
 int pq_probe_mfma(int iters, float* sink, double* flops_out, void* stream) {
   if (!sink) return fail(PQ_ERR_NULL, "pq_probe_mfma: sink must not be NULL");
   if (iters <= 0 || iters > (1 << 24)) return fail(PQ_ERR_SHAPE, "pq_probe_mfma: iters=%d out of range", iters);
-  return launch_probe_mfma(iters, sink, flops_out, (hipStream_t)stream);
+  return launch_probe_mfma(iters, sink, flops_out, as_stream(stream));
 }
 
 }  // extern "C"

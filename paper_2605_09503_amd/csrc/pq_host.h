@@ -54,6 +54,15 @@ int run_qgemm(pq_format fmt, int group, const uint8_t* a_codes, const void* a_sc
               void* ws, hipStream_t st);   // phases: 1 = scale preparation, 2 = product
 
 
+size_t operand_bytes(pq_format fmt, int group, int64_t rows, int64_t K);
+int run_pack_operand(pq_format fmt, int group, const uint8_t* codes, const void* scales, int64_t rows,
+                     int64_t K, void* operand, hipStream_t st);
+int run_quantize_packed(pq_format fmt, int group, const void* x, int64_t rows, int64_t K, int64_t ld,
+                        const float* ts, void* operand, uint8_t* codes, void* scales, hipStream_t st);
+int run_qgemm_packed(pq_format fmt, int group, const void* a_operand, const float* a_ts,
+                     const void* w_operand, const float* w_ts, int64_t M, int64_t N, int64_t K, void* y,
+                     int64_t ldy, bool out_f32, hipStream_t st);
+
 int launch_probe_stream(const void* src, size_t read_bytes, void* dst, size_t write_bytes, hipStream_t st);
 int launch_probe_mfma(int iters, float* sink, double* flops_out, hipStream_t st);
 

@@ -40,11 +40,12 @@ namespace pq {
 // with scheduling barriers, so that the matrix pipe and the vector ALU overlap inside a wave
 // instead of alternating in phases.
 template <int FMT, int G, int BM, int BN, int WGM, int WGN, bool OUT_F32>
-__global__ __launch_bounds__(WGM* WGN * 64) void qgemm_kernel(
-    const uint8_t* __restrict__ a_codes, ScaleSrc a_sc, const uint8_t* __restrict__ w_codes,
-    ScaleSrc w_sc, const float* __restrict__ a_mul, int a_mul_stride,
-    const float* __restrict__ w_mul, int w_mul_stride, int M, int N, int K, void* __restrict__ y,
-    int64_t ldy, int tiles_m, int tiles_n) {
+__global__ __launch_bounds__(WGM* WGN * 64) void qgemm_kernel(OperandView A, OperandView W, int M, int N,
+                                                              int K, void* __restrict__ y, int64_t ldy,
+                                                              int tiles_m, int tiles_n) {
+  const float* __restrict__ a_mul = A.mul;
+  const float* __restrict__ w_mul = W.mul;
+  const int a_mul_stride = A.mul_stride, w_mul_stride = W.mul_stride;
   constexpr int T = WGM * WGN * 64;
   constexpr int WTM = BM / WGM, WTN = BN / WGN;      // wave tile
   constexpr int TM = WTM / 32, TN = WTN / 32;        // MFMA tiles per wave
@@ -84,32 +85,27 @@ __global__ __launch_bounds__(WGM* WGN * 64) void qgemm_kernel(
   const int ld_row = tid >> 1, ld_half = tid & 1;
   bool a_ok[SL], w_ok[SL];
   const uint8_t *a_crow[SL], *w_crow[SL];
-  const void *a_srow[SL], *w_srow[SL];
+  const uint8_t *a_srow[SL], *w_srow[SL];
 #pragma unroll
   for (int q = 0; q < SL; ++q) {
     const int r = ld_row + q * (T / 2);
     a_ok[q] = m0 + r < M;
     w_ok[q] = n0 + r < N;
     const int a_row = min(m0 + r, M - 1), w_row = min(n0 + r, N - 1);
-    a_crow[q] = a_codes + (int64_t)a_row * (K / 2);
-    w_crow[q] = w_codes + (int64_t)w_row * (K / 2);
-    if constexpr (FMT == kNvfp4) {
-      a_srow[q] = a_sc.e4m3 + (int64_t)a_row * (K / 16);
-      w_srow[q] = w_sc.e4m3 + (int64_t)w_row * (K / 16);
-    } else {
-      a_srow[q] = a_sc.f16 + (int64_t)a_row * (K / G);
-      w_srow[q] = w_sc.f16 + (int64_t)w_row * (K / G);
-    }
+    a_crow[q] = A.codes + (int64_t)a_row * A.code_row;
+    w_crow[q] = W.codes + (int64_t)w_row * W.code_row;
+    a_srow[q] = A.scales + (int64_t)a_row * A.sc_row;
+    w_srow[q] = W.scales + (int64_t)w_row * W.sc_row;
   }
   auto load_a = [&](int step, Slice (&ra)[SL]) {
-    const int k0 = step * kBK + ld_half * 32;
 #pragma unroll
-    for (int q = 0; q < SL; ++q) ra[q] = load_slice<FMT, G>(a_crow[q], a_srow[q], K, k0);
+    for (int q = 0; q < SL; ++q)
+      ra[q] = load_slice<FMT, G>(a_crow[q], A.code_step, a_srow[q], A.sc_step, K, step, ld_half);
   };
   auto load_w = [&](int step, Slice (&rw)[SL]) {
-    const int k0 = step * kBK + ld_half * 32;
 #pragma unroll
-    for (int q = 0; q < SL; ++q) rw[q] = load_slice<FMT, G>(w_crow[q], w_srow[q], K, k0);
+    for (int q = 0; q < SL; ++q)
+      rw[q] = load_slice<FMT, G>(w_crow[q], W.code_step, w_srow[q], W.sc_step, K, step, ld_half);
   };
   // byte offsets of this thread's 16-byte pieces inside an operand tile: [slot][piece]
   int st_off[SL][4];
@@ -384,9 +380,8 @@ size_t qgemm_workspace_bytes(pq_format fmt, int group, int64_t M, int64_t N, int
 }
 
 template <int FMT, int G, int BM, int BN, int WGM, int WGN, bool OUT_F32>
-static int launch_gemm(const uint8_t* a_codes, ScaleSrc a_sc, const uint8_t* w_codes, ScaleSrc w_sc,
-                       const float* a_mul, int a_stride, const float* w_mul, int w_stride, int M, int N,
-                       int K, void* y, int64_t ldy, hipStream_t st) {
+static int launch_gemm(const OperandView& A, const OperandView& W, int M, int N, int K, void* y, int64_t ldy,
+                       hipStream_t st) {
   constexpr int T = WGM * WGN * 64;
   constexpr size_t shmem = 2 * (size_t)(BM + BN) * kRowBytes;
   auto kern = qgemm_kernel<FMT, G, BM, BN, WGM, WGN, OUT_F32>;
@@ -398,8 +393,7 @@ static int launch_gemm(const uint8_t* a_codes, ScaleSrc a_sc, const uint8_t* w_c
   int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
   int64_t n_tiles = (int64_t)tiles_m * tiles_n;
   if (n_tiles > 0x7FFFFFFF) return fail(PQ_ERR_SHAPE, "too many output tiles");
-  hipLaunchKernelGGL(kern, dim3((unsigned)n_tiles), dim3(T), shmem, st, a_codes, a_sc, w_codes, w_sc, a_mul,
-                     a_stride, w_mul, w_stride, M, N, K, y, ldy, tiles_m, tiles_n);
+  hipLaunchKernelGGL(kern, dim3((unsigned)n_tiles), dim3(T), shmem, st, A, W, M, N, K, y, ldy, tiles_m, tiles_n);
   return check_hip(hipGetLastError(), "qgemm_kernel");
 }
 
@@ -427,81 +421,85 @@ static int choose_tile(int M, int N) {
 }
 
 template <int FMT, int G, bool OUT_F32>
-static int pick_tile(const uint8_t* a_codes, ScaleSrc a_sc, const uint8_t* w_codes, ScaleSrc w_sc,
-                     const float* a_mul, int a_stride, const float* w_mul, int w_stride, int M, int N,
-                     int K, void* y, int64_t ldy, hipStream_t st) {
+static int pick_tile(const OperandView& A, const OperandView& W, int M, int N, int K, void* y, int64_t ldy,
+                     hipStream_t st) {
   int choice = choose_tile(M, N);
   if (tile_override() >= 0 && tile_override() <= 2) choice = tile_override();
-#define PQ_GEMM_ARGS a_codes, a_sc, w_codes, w_sc, a_mul, a_stride, w_mul, w_stride, M, N, K, y, ldy, st
-  if (choice == 0) return launch_gemm<FMT, G, 256, 256, 2, 2, OUT_F32>(PQ_GEMM_ARGS);
-  if (choice == 1) return launch_gemm<FMT, G, 256, 256, 2, 4, OUT_F32>(PQ_GEMM_ARGS);
-  return launch_gemm<FMT, G, 128, 128, 2, 2, OUT_F32>(PQ_GEMM_ARGS);
-#undef PQ_GEMM_ARGS
+  if (choice == 0) return launch_gemm<FMT, G, 256, 256, 2, 2, OUT_F32>(A, W, M, N, K, y, ldy, st);
+  if (choice == 1) return launch_gemm<FMT, G, 256, 256, 2, 4, OUT_F32>(A, W, M, N, K, y, ldy, st);
+  return launch_gemm<FMT, G, 128, 128, 2, 2, OUT_F32>(A, W, M, N, K, y, ldy, st);
 }
 
 template <int FMT, int G>
-static int run_fmt(const uint8_t* a_codes, const void* a_scales, const float* a_ts,
-                   const uint8_t* w_codes, const void* w_scales, const float* w_ts, int M, int N, int K,
-                   void* y, int64_t ldy, bool out_f32, int phases, void* ws, hipStream_t st) {
-  ScaleSrc a_sc{nullptr, nullptr}, w_sc{nullptr, nullptr};
-  const float *a_mul, *w_mul;
-  int a_stride, w_stride;
-  if constexpr (FMT == kNvfp4) {
-    a_sc.e4m3 = (const uint8_t*)a_scales;
-    w_sc.e4m3 = (const uint8_t*)w_scales;
-    a_mul = a_ts;
-    w_mul = w_ts;
-    a_stride = w_stride = 0;
-  } else {
-    GemmWs W;
-    carve_gemm(ws, (pq_format)FMT, G, M, N, K, &W);
-    const float Q = qmax_of(FMT);
-    if (phases & 1) {
-      hipLaunchKernelGGL(int_scale_prep_kernel, dim3((unsigned)((M + 3) / 4)), dim3(256), 0, st,
-                         (const float*)a_scales, M, K / G, Q, W.a_h, W.a_mul);
-      hipLaunchKernelGGL(int_scale_prep_kernel, dim3((unsigned)((N + 3) / 4)), dim3(256), 0, st,
-                         (const float*)w_scales, N, K / G, Q, W.w_h, W.w_mul);
-      int rc = check_hip(hipGetLastError(), "int_scale_prep_kernel");
-      if (rc) return rc;
-    }
-    a_sc.f16 = W.a_h;
-    w_sc.f16 = W.w_h;
-    a_mul = W.a_mul;
-    w_mul = W.w_mul;
-    a_stride = w_stride = 1;
-  }
-  if (!(phases & 2)) return PQ_OK;
-  if (out_f32)
-    return pick_tile<FMT, G, true>(a_codes, a_sc, w_codes, w_sc, a_mul, a_stride, w_mul, w_stride, M, N, K,
-                                   y, ldy, st);
-  return pick_tile<FMT, G, false>(a_codes, a_sc, w_codes, w_sc, a_mul, a_stride, w_mul, w_stride, M, N, K,
-                                  y, ldy, st);
+static int launch_views_fg(const OperandView& A, const OperandView& W, int M, int N, int K, void* y,
+                           int64_t ldy, bool out_f32, hipStream_t st) {
+  if (out_f32) return pick_tile<FMT, G, true>(A, W, M, N, K, y, ldy, st);
+  return pick_tile<FMT, G, false>(A, W, M, N, K, y, ldy, st);
 }
 
-int run_qgemm(pq_format fmt, int group, const uint8_t* a_codes, const void* a_scales,
-              const float* a_ts, const uint8_t* w_codes, const void* w_scales, const float* w_ts,
-              int64_t M, int64_t N, int64_t K, void* y, int64_t ldy, bool out_f32, int phases,
-              void* ws, hipStream_t st) {
-#define PQ_ARGS a_codes, a_scales, a_ts, w_codes, w_scales, w_ts, (int)M, (int)N, (int)K, y, ldy, out_f32, phases, ws, st
-  if (fmt == PQ_FMT_NVFP4) return run_fmt<kNvfp4, 16>(PQ_ARGS);
+// the product kernel on two operand views (any mix of layouts)
+int launch_qgemm_views(pq_format fmt, int group, const OperandView& A, const OperandView& W, int64_t M,
+                       int64_t N, int64_t K, void* y, int64_t ldy, bool out_f32, hipStream_t st) {
+#define PQ_ARGS A, W, (int)M, (int)N, (int)K, y, ldy, out_f32, st
+  if (fmt == PQ_FMT_NVFP4) return launch_views_fg<kNvfp4, 16>(PQ_ARGS);
   if (fmt == PQ_FMT_INT4) {
     switch (group) {
-      case 32: return run_fmt<kInt4, 32>(PQ_ARGS);
-      case 64: return run_fmt<kInt4, 64>(PQ_ARGS);
-      case 128: return run_fmt<kInt4, 128>(PQ_ARGS);
-      case 256: return run_fmt<kInt4, 256>(PQ_ARGS);
+      case 32: return launch_views_fg<kInt4, 32>(PQ_ARGS);
+      case 64: return launch_views_fg<kInt4, 64>(PQ_ARGS);
+      case 128: return launch_views_fg<kInt4, 128>(PQ_ARGS);
+      case 256: return launch_views_fg<kInt4, 256>(PQ_ARGS);
     }
   }
   if (fmt == PQ_FMT_INT3) {
     switch (group) {
-      case 32: return run_fmt<kInt3, 32>(PQ_ARGS);
-      case 64: return run_fmt<kInt3, 64>(PQ_ARGS);
-      case 128: return run_fmt<kInt3, 128>(PQ_ARGS);
-      case 256: return run_fmt<kInt3, 256>(PQ_ARGS);
+      case 32: return launch_views_fg<kInt3, 32>(PQ_ARGS);
+      case 64: return launch_views_fg<kInt3, 64>(PQ_ARGS);
+      case 128: return launch_views_fg<kInt3, 128>(PQ_ARGS);
+      case 256: return launch_views_fg<kInt3, 256>(PQ_ARGS);
     }
   }
 #undef PQ_ARGS
   return fail(PQ_ERR_FORMAT, "unsupported (format, group) = (%d, %d)", (int)fmt, group);
+}
+
+// Operands in the row-major layout of the quantizers.  NVFP4 scales are read in place; INT
+// scales go through the per-row normalisation pass into `ws` first (phases & 1), the product
+// (phases & 2) then reads that working copy.
+int run_qgemm(pq_format fmt, int group, const uint8_t* a_codes, const void* a_scales,
+              const float* a_ts, const uint8_t* w_codes, const void* w_scales, const float* w_ts,
+              int64_t M, int64_t N, int64_t K, void* y, int64_t ldy, bool out_f32, int phases,
+              void* ws, hipStream_t st) {
+  OperandView A{a_codes, K / 2, 32, nullptr, 0, 2, nullptr, 0};
+  OperandView W{w_codes, K / 2, 32, nullptr, 0, 2, nullptr, 0};
+  if (fmt == PQ_FMT_NVFP4) {
+    A.scales = (const uint8_t*)a_scales;
+    W.scales = (const uint8_t*)w_scales;
+    A.sc_row = W.sc_row = K / 16;
+    A.mul = a_ts;
+    W.mul = w_ts;
+  } else {
+    if (fmt != PQ_FMT_INT4 && fmt != PQ_FMT_INT3)
+      return fail(PQ_ERR_FORMAT, "unsupported (format, group) = (%d, %d)", (int)fmt, group);
+    GemmWs G;
+    carve_gemm(ws, fmt, group, M, N, K, &G);
+    const float Q = qmax_of((int)fmt);
+    if (phases & 1) {
+      hipLaunchKernelGGL(int_scale_prep_kernel, dim3((unsigned)((M + 3) / 4)), dim3(256), 0, st,
+                         (const float*)a_scales, (int)M, (int)(K / group), Q, G.a_h, G.a_mul);
+      hipLaunchKernelGGL(int_scale_prep_kernel, dim3((unsigned)((N + 3) / 4)), dim3(256), 0, st,
+                         (const float*)w_scales, (int)N, (int)(K / group), Q, G.w_h, G.w_mul);
+      int rc = check_hip(hipGetLastError(), "int_scale_prep_kernel");
+      if (rc) return rc;
+    }
+    A.scales = (const uint8_t*)G.a_h;
+    W.scales = (const uint8_t*)G.w_h;
+    A.sc_row = W.sc_row = (K / group) * 2;
+    A.mul = G.a_mul;
+    W.mul = G.w_mul;
+    A.mul_stride = W.mul_stride = 1;
+  }
+  if (!(phases & 2)) return PQ_OK;
+  return launch_qgemm_views(fmt, group, A, W, M, N, K, y, ldy, out_f32, st);
 }
 
 }  // namespace pq

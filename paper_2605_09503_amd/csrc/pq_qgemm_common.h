@@ -25,28 +25,42 @@ struct Slice {
   uint32_t sc;      // NVFP4: two E4M3 bytes (k 0-15, 16-31); INT: one fp16 in the low half
 };
 
-// scale source for one operand
-struct ScaleSrc {
-  const uint8_t* e4m3;      // NVFP4: [rows, K/16]
-  const uint16_t* f16;      // INT: normalised group maxima, [rows, K/G]
+// Where a quantized operand lives.  One description covers both layouts the kernel reads:
+//   codes of (row, K step, half)  at codes  + row * code_row + step * code_step + half * 16
+//   scale unit u of a row         at scales + row * sc_row   + u * sc_step          (2 bytes)
+// where a scale unit is the pair of E4M3 bytes of 32 consecutive k (NVFP4, u = k / 32) or the
+// fp16 normalised maximum of a group (INT, u = k / G).
+//   row-major (as the quantizers store it): code_row = K / 2, code_step = 32;
+//                                           sc_row = K / 16 (NVFP4) or 2 K / G, sc_step = 2
+//   panel (K-step-major, see pq_pack.hip):  code_row = 32, code_step = 32 * rows;
+//                                           sc_row = 2, sc_step = 2 * rows
+// mul: per-row epilogue factor (stride 1) or a single factor (stride 0).
+struct OperandView {
+  const uint8_t* codes;
+  int64_t code_row;
+  int code_step;
+  const uint8_t* scales;
+  int64_t sc_row;
+  int sc_step;
+  const float* mul;
+  int mul_stride;
 };
 
 // Branch-free load of one slice.  `codes_row` / `sc_row` point at a valid row (the caller
-// clamps the row index) and k0 beyond K is redirected to the row start, so the address is
+// clamps the row index) and a k beyond K is redirected to the row start, so the address is
 // always valid.  The loaded registers are not touched here (a use would make the wave wait for
 // the load at once); a slice that is out of range is neutralised when it is unpacked, by
 // zeroing its scale (see slice_scales).
 template <int FMT, int G>
-__device__ __forceinline__ Slice load_slice(const uint8_t* __restrict__ codes_row,
-                                            const void* __restrict__ sc_row, int K, int k0) {
-  const int kk = k0 < K ? k0 : 0;
+__device__ __forceinline__ Slice load_slice(const uint8_t* __restrict__ codes_row, int code_step,
+                                            const uint8_t* __restrict__ sc_row, int sc_step, int K,
+                                            int step, int half) {
+  const int k0 = step * kBK + half * 32;
+  const bool ok = k0 < K;
+  const int unit = FMT == kNvfp4 ? k0 >> 5 : k0 / G;
   Slice s;
-  s.codes = *reinterpret_cast<const uint4*>(codes_row + kk / 2);
-  if constexpr (FMT == kNvfp4) {
-    s.sc = *reinterpret_cast<const uint16_t*>(reinterpret_cast<const uint8_t*>(sc_row) + kk / 16);
-  } else {
-    s.sc = reinterpret_cast<const uint16_t*>(sc_row)[kk / G];
-  }
+  s.codes = *reinterpret_cast<const uint4*>(codes_row + (ok ? (int64_t)step * code_step + half * 16 : 0));
+  s.sc = *reinterpret_cast<const uint16_t*>(sc_row + (ok ? (int64_t)unit * sc_step : 0));
   return s;
 }
 
@@ -101,5 +115,9 @@ template <int V>
 struct IntC {
   static constexpr int value = V;
 };
+
+// the product kernel on two operand views (pq_qgemm.hip)
+int launch_qgemm_views(pq_format fmt, int group, const OperandView& A, const OperandView& W, int64_t M,
+                       int64_t N, int64_t K, void* y, int64_t ldy, bool out_f32, hipStream_t st);
 
 }  // namespace pq

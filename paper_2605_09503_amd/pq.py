@@ -68,11 +68,19 @@ def load():
     lib.pq_qgemm_f32.argtypes = gemm_args
     lib.pq_qgemm_run.argtypes = gemm_args
     lib.pq_qgemm_prep.argtypes = [i32, i32, vp, vp, i64, i64, i64, vp, sz, vp]
+    lib.pq_operand_bytes.restype = sz
+    lib.pq_operand_bytes.argtypes = [i32, i32, i64, i64]
+    lib.pq_pack_operand.argtypes = [i32, i32, vp, vp, i64, i64, vp, sz, vp]
+    lib.pq_quantize_act_packed.argtypes = [i32, i32, vp, i64, i64, i64, vp, vp, sz, vp, vp, vp]
+    packed_args = [i32, i32, vp, vp, vp, vp, i64, i64, i64, vp, i64, vp]
+    lib.pq_qgemm_packed.argtypes = packed_args
+    lib.pq_qgemm_packed_f32.argtypes = packed_args
     lib.pq_probe_stream.argtypes = [vp, sz, vp, sz, vp]
     lib.pq_probe_mfma.argtypes = [i32, vp, C.POINTER(C.c_double), vp]
     for name in ("pq_calib_moments", "pq_calib_moments_batched", "pq_select_perm", "pq_quant_error", "pq_quantize_weights",
                  "pq_quantize_act", "pq_qgemm", "pq_qgemm_f32", "pq_qgemm_run", "pq_qgemm_prep", "pq_probe_stream",
-                 "pq_probe_mfma"):
+                 "pq_probe_mfma", "pq_pack_operand", "pq_qgemm_packed", "pq_qgemm_packed_f32",
+                 "pq_quantize_act_packed"):
         getattr(lib, name).restype = i32
     _lib = lib
     return lib
@@ -242,6 +250,51 @@ def pq_qgemm_f32(fmt: int, group: int, a_codes, a_scales, a_tensor_scale, w_code
     """Same product, fp32 output (accumulator before the bf16 rounding)."""
     _gemm(load().pq_qgemm_f32, fmt, group, a_codes, a_scales, a_tensor_scale, w_codes, w_scales,
           w_tensor_scale, y, workspace, M, N, K, ldy)
+
+
+def pq_operand_bytes(fmt: int, group: int, rows: int, K: int) -> int:
+    return int(load().pq_operand_bytes(fmt, group, rows, K))
+
+
+def pq_pack_operand(fmt: int, group: int, codes: torch.Tensor, scales: torch.Tensor,
+                    operand: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Stored quantizer output -> the GEMM's panel layout (allocates the buffer unless given)."""
+    rows, K = codes.shape[0], codes.shape[1] * 2
+    if operand is None:
+        operand = torch.empty(max(pq_operand_bytes(fmt, group, rows, K), 16), dtype=torch.uint8, device=codes.device)
+    _check(load().pq_pack_operand(fmt, group, _ptr(codes), _ptr(scales), rows, K, _ptr(operand),
+                                  operand.numel(), _stream()))
+    return operand
+
+
+def pq_quantize_act_packed(fmt: int, group: int, x: torch.Tensor, tensor_scale: Optional[torch.Tensor],
+                           operand: Optional[torch.Tensor] = None, codes: Optional[torch.Tensor] = None,
+                           scales: Optional[torch.Tensor] = None, K: Optional[int] = None) -> torch.Tensor:
+    """Dynamic activation quantization straight into the GEMM's panel layout."""
+    M = x.shape[0]
+    K = x.shape[1] if K is None else K
+    if operand is None:
+        operand = torch.empty(max(pq_operand_bytes(fmt, group, M, K), 16), dtype=torch.uint8, device=x.device)
+    _check(load().pq_quantize_act_packed(fmt, group, _ptr(x), M, K, x.stride(0), _ptr(tensor_scale),
+                                         _ptr(operand), operand.numel(), _ptr(codes), _ptr(scales), _stream()))
+    return operand
+
+
+def _gemm_packed(fn, fmt, group, a_operand, a_ts, w_operand, w_ts, y, M, N, K, ldy):
+    _check(fn(fmt, group, _ptr(a_operand), _ptr(a_ts), _ptr(w_operand), _ptr(w_ts), M, N, K, _ptr(y),
+              y.stride(0) if ldy is None else ldy, _stream()))
+
+
+def pq_qgemm_packed(fmt: int, group: int, a_operand, a_tensor_scale, w_operand, w_tensor_scale,
+                    y: torch.Tensor, M: int, N: int, K: int, ldy=None) -> None:
+    _gemm_packed(load().pq_qgemm_packed, fmt, group, a_operand, a_tensor_scale, w_operand, w_tensor_scale,
+                 y, M, N, K, ldy)
+
+
+def pq_qgemm_packed_f32(fmt: int, group: int, a_operand, a_tensor_scale, w_operand, w_tensor_scale,
+                        y: torch.Tensor, M: int, N: int, K: int, ldy=None) -> None:
+    _gemm_packed(load().pq_qgemm_packed_f32, fmt, group, a_operand, a_tensor_scale, w_operand,
+                 w_tensor_scale, y, M, N, K, ldy)
 
 
 def pq_probe_stream(src: torch.Tensor, read_bytes: int, dst: torch.Tensor, write_bytes: int) -> None:

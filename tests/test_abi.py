@@ -141,3 +141,29 @@ def test_workspace_sizes(lib):
     assert w(pq.OP_QUANT_ERROR, pq.FMT_INT4, 64, 100, 0, 64) >= 800
     assert w(pq.OP_QGEMM, pq.FMT_INT4, 64, 0, 0, 0) == 0
     assert w(99, 0, 0, 1, 1, 1) == 0
+
+
+def test_packed_operand_validation(lib):
+    ob = pq.pq_operand_bytes
+    # codes + scale units + (INT) row factors, each part rounded up to 256 bytes
+    assert ob(pq.FMT_INT4, 64, 4608, 3072) >= 4608 * 3072 // 2 + 4608 * (3072 // 64) * 2 + 4608 * 4
+    assert ob(pq.FMT_NVFP4, 16, 4608, 3072) >= 4608 * 3072 // 2 + 4608 * (3072 // 16)
+    assert ob(pq.FMT_NVFP4, 16, 4, 96) >= 2 * 4 * 32 + 3 * 4 * 2     # 96 = one and a half steps
+    assert ob(pq.FMT_INT4, 64, 0, 3072) == 0 and ob(pq.FMT_INT4, 48, 8, 96) == 0 and ob(pq.FMT_NVFP4, 16, 8, 48) == 0
+    f = lib.pq_pack_operand
+    assert f(1, 64, None, FAKE, 8, 64, FAKE, 1 << 20, None) == PQ_ERR_NULL
+    assert f(1, 64, FAKE, FAKE, 8, 64, None, 1 << 20, None) == PQ_ERR_NULL
+    assert f(1, 64, FAKE, FAKE, 0, 64, FAKE, 1 << 20, None) == PQ_ERR_SHAPE
+    assert f(0, 16, FAKE, FAKE, 8, 48, FAKE, 1 << 20, None) == PQ_ERR_SHAPE      # K % 32
+    assert f(1, 48, FAKE, FAKE, 8, 96, FAKE, 1 << 20, None) == PQ_ERR_FORMAT
+    assert f(1, 64, FAKE, FAKE, 8, 64, FAKE, 16, None) == PQ_ERR_WORKSPACE
+    assert f(1, 64, C.c_void_p(0x1004), FAKE, 8, 64, FAKE, 1 << 20, None) == PQ_ERR_SHAPE
+    g = lib.pq_qgemm_packed
+    assert g(1, 64, None, None, FAKE, None, 8, 8, 64, FAKE, 8, None) == PQ_ERR_NULL
+    assert g(0, 16, FAKE, None, FAKE, FAKE, 8, 8, 64, FAKE, 8, None) == PQ_ERR_NULL   # NVFP4 tensor scales
+    assert g(1, 64, FAKE, None, FAKE, None, 8, 8, 64, FAKE, 4, None) == PQ_ERR_SHAPE   # ldy < N
+    assert g(1, 64, FAKE, None, FAKE, None, 8, 8, 48, FAKE, 8, None) == PQ_ERR_SHAPE   # K % group
+    assert g(2, 16, FAKE, None, FAKE, None, 8, 8, 64, FAKE, 8, None) == PQ_ERR_FORMAT
+    assert lib.pq_probe_mfma(0, FAKE, None, None) == PQ_ERR_SHAPE
+    assert lib.pq_probe_stream(None, 16, FAKE, 0, None) == PQ_ERR_NULL
+    assert lib.pq_probe_stream(FAKE, 24, FAKE, 0, None) == PQ_ERR_SHAPE
