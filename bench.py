@@ -55,6 +55,8 @@ def main():
     ap.add_argument("--config", default="c1", choices=sorted(WORKLOADS))
     ap.add_argument("--kernel-iters", type=int, default=50, help="launches per kernel timing")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-row-major-comparison", action="store_true",
+                    help="skip the timings of the row-major operand path (keeps a profile of qgemm_kernel pure)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         log("bench.py: this build runs on one GPU only (every step of the path shards over token "
@@ -160,11 +162,13 @@ def main():
     # kernel on the quantizers' row-major layout, alone and with its INT scale preparation
     t_gemm = time_calls(lambda i: pq.pq_qgemm_packed(fmt, g, a_op, ts_a, w_op, ts_w, y, M, N, K), it)
     pq.pq_quantize_act(fmt, g, x_run, None, ts_a, a_codes, a_scales)
-    pq.pq_qgemm_prep(fmt, g, a_scales, w_scales, M, N, K, ws_gemm)
-    t_gemm_rm = time_calls(lambda i: pq.pq_qgemm_run(fmt, g, a_codes, a_scales, ts_a, w_codes, w_scales, ts_w, y,
-                                                     workspace=ws_gemm), it)
-    t_gemm_call = time_calls(lambda i: pq.pq_qgemm(fmt, g, a_codes, a_scales, ts_a, w_codes, w_scales, ts_w, y,
-                                                   workspace=ws_gemm), it)
+    t_gemm_rm = t_gemm_call = float("nan")
+    if not args.no_row_major_comparison:
+        pq.pq_qgemm_prep(fmt, g, a_scales, w_scales, M, N, K, ws_gemm)
+        t_gemm_rm = time_calls(lambda i: pq.pq_qgemm_run(fmt, g, a_codes, a_scales, ts_a, w_codes, w_scales, ts_w, y,
+                                                         workspace=ws_gemm), it)
+        t_gemm_call = time_calls(lambda i: pq.pq_qgemm(fmt, g, a_codes, a_scales, ts_a, w_codes, w_scales, ts_w, y,
+                                                       workspace=ws_gemm), it)
     t_pack_a = time_calls(lambda i: pq.pq_pack_operand(fmt, g, a_codes, a_scales, a_op), it)
     t_qa_warm = time_calls(lambda i: pq.pq_quantize_act_packed(fmt, g, x_run, ts_a, a_op), it)
     t_qa_rm_warm = time_calls(lambda i: pq.pq_quantize_act(fmt, g, x_run, None, ts_a, a_codes, a_scales), it)
@@ -239,6 +243,8 @@ def main():
         "reference_stream_read_all_batches": {"us": t_floor_mall * 1e6, "gbs": nb * mbytes / t_floor_mall / 1e9},
         "reference_mfma_only_loop": {"tflops": mfma_sustained, "frac_mfma_f16_peak": mfma_sustained / MFMA_F16_PEAK_TFLOPS},
     }
+    if args.no_row_major_comparison:
+        del kernels["qgemm_kernel_row_major_operands"], kernels["qgemm_call_row_major_with_scale_prep"]
     for k, v in kernels.items():
         log("  %-34s %s" % (k, json.dumps({a: round(b, 4) for a, b in v.items()})))
 
