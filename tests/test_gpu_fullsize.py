@@ -119,7 +119,21 @@ def test_forward_path_full_size(name, nb):
     y_ref = OG.dequant_product(fmt, g, qa, qw)
     got16 = y16[rows_t][:, cols_t].view(torch.int16).cpu().numpy().view(np.uint16)
     same = T.gemm_bf16_check(got16, y_ref, name)
-    del y16
+    # the forward path the benchmark times: activations quantized straight into the operand layout,
+    # weights packed into it, product from the packed operands -- the same bits as above, so every
+    # check against the oracle carries over
+    a_op = pq.pq_quantize_act_packed(fmt, g, x_perm, ts_a)
+    ref_op = torch.zeros_like(a_op)
+    got_op = torch.zeros_like(a_op)
+    pq.pq_pack_operand(fmt, g, a_codes, a_scales, ref_op)
+    pq.pq_quantize_act_packed(fmt, g, x_perm, ts_a, got_op)
+    w_op = pq.pq_pack_operand(fmt, g, w_codes, w_scales)
+    y16p = torch.empty((M, N), dtype=torch.bfloat16, device=DEV)
+    pq.pq_qgemm_packed(fmt, g, a_op, ts_a, w_op, ts_w, y16p, M, N, K)
+    torch.cuda.synchronize()
+    assert torch.equal(got_op, ref_op), "fused quantizer and quantize + pack disagree"
+    assert torch.equal(y16p.view(torch.int16), y16.view(torch.int16)), "packed and row-major products differ"
+    del y16, y16p, a_op, ref_op, got_op, w_op
     y32 = torch.empty((M, N), dtype=torch.float32, device=DEV)
     pq.pq_qgemm_f32(fmt, g, a_codes, a_scales, ts_a, w_codes, w_scales, ts_w, y32)
     torch.cuda.synchronize()
