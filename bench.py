@@ -146,27 +146,43 @@ def main():
     flops = 2.0 * M * N * K
 
     # ---- per-kernel timings with events on the launch stream ------------------------------
-    def time_calls(fn, iters, rotate=None):
+    # The launches of a timing loop are captured into a graph and replayed: a Python loop issues
+    # one launch per ~8 us, which would hide every kernel shorter than that behind the host.
+    # (Calls that synchronise -- pq_select_perm -- cannot be captured and are timed eagerly.)
+    def time_calls(fn, iters, graph=True, warm_replays=2):
         fn(0)
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for i in range(iters):
-            fn(i)
-        e1.record()
+        if graph:
+            g_ = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g_):
+                for i in range(iters):
+                    fn(i)
+            for _ in range(warm_replays):    # untimed: first touch, and the clocks settle
+                g_.replay()
+            torch.cuda.synchronize()
+            e0.record()
+            g_.replay()
+            e1.record()
+        else:
+            e0.record()
+            for i in range(iters):
+                fn(i)
+            e1.record()
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) * 1e-3 / iters            # seconds per call
 
     it = args.kernel_iters
     # the product kernel on packed operands (what the forward path runs); for comparison the same
     # kernel on the quantizers' row-major layout, alone and with its INT scale preparation
-    t_gemm = time_calls(lambda i: pq.pq_qgemm_packed(fmt, g, a_op, ts_a, w_op, ts_w, y, M, N, K), it)
+    # (the matrix clock takes some 20 ms of this load to settle: several untimed replays first)
+    t_gemm = time_calls(lambda i: pq.pq_qgemm_packed(fmt, g, a_op, ts_a, w_op, ts_w, y, M, N, K), it, warm_replays=6)
     pq.pq_quantize_act(fmt, g, x_run, None, ts_a, a_codes, a_scales)
     t_gemm_rm = t_gemm_call = float("nan")
     if not args.no_row_major_comparison:
         pq.pq_qgemm_prep(fmt, g, a_scales, w_scales, M, N, K, ws_gemm)
         t_gemm_rm = time_calls(lambda i: pq.pq_qgemm_run(fmt, g, a_codes, a_scales, ts_a, w_codes, w_scales, ts_w, y,
-                                                         workspace=ws_gemm), it)
+                                                         workspace=ws_gemm), it, warm_replays=3)
         t_gemm_call = time_calls(lambda i: pq.pq_qgemm(fmt, g, a_codes, a_scales, ts_a, w_codes, w_scales, ts_w, y,
                                                        workspace=ws_gemm), it)
     t_pack_a = time_calls(lambda i: pq.pq_pack_operand(fmt, g, a_codes, a_scales, a_op), it)
@@ -183,12 +199,19 @@ def main():
     t_mom_warm = time_calls(lambda i: pq.pq_calib_moments(x_run, sa, None, ws_mom), it)
     del pool
     t_mom_all = time_calls(lambda i: pq.pq_calib_moments_batched(xs, sa, amax_a, ws_mom), 10)
-    t_fwd = time_calls(lambda i: forward(), it)
+    # cold: rotate through whole sets of batches (> 1 GB together, beyond the 256 MB Infinity Cache)
+    n_sets = max(2, int(1.2e9 // (nb * M * K * 2)) + 1)
+    sets = [xs] + [[torch.empty_like(b).copy_(b) for b in xs] for _ in range(n_sets - 1)]
+    t_mom_all_cold = time_calls(lambda i: pq.pq_calib_moments_batched(sets[i % n_sets], sa, amax_a, ws_mom),
+                                2 * n_sets)
+    del sets
+    t_fwd = time_calls(lambda i: forward(), it, warm_replays=4)
     t_qw = time_calls(lambda i: prepare_weights(), 5)
-    t_cal = time_calls(lambda i: calibrate(), 3)
+    t_cal = time_calls(lambda i: calibrate(), 3, graph=False)
     ta_h = ts_a.item() if fmt == pq.FMT_NVFP4 else 1.0
     tw_h = ts_w.item() if fmt == pq.FMT_NVFP4 else 1.0
-    t_sel = time_calls(lambda i: pq.pq_select_perm(fmt, g, sa, sw, xs, w, ta_h, tw_h, perm, workspace=ws_sel), 3)
+    t_sel = time_calls(lambda i: pq.pq_select_perm(fmt, g, sa, sw, xs, w, ta_h, tw_h, perm, workspace=ws_sel), 3,
+                       graph=False)
 
     # references measured in the same run: a plain streaming kernel with the footprint of the
     # quantizer (reads the bf16 tensor, writes codes + scales) and of the moments pass (reads
@@ -201,9 +224,11 @@ def main():
                            max(it, n_rot))
     t_floor_m = time_calls(lambda i: pq.pq_probe_stream(pool[i % n_rot], in_bytes, qout, 0), max(it, n_rot))
     del pool
-    xcat = torch.cat([b.reshape(-1) for b in xs])            # the calibration set as one buffer
-    t_floor_mall = time_calls(lambda i: pq.pq_probe_stream(xcat, xcat.numel() * 2, qout, 0), 10)
-    del xcat
+    # the calibration set as one buffer, rotating over enough copies to stay out of the caches
+    xcats = [torch.cat([b.reshape(-1) for b in xs]) for _ in range(n_sets)]
+    t_floor_mall = time_calls(lambda i: pq.pq_probe_stream(xcats[i % n_sets], xcats[0].numel() * 2, qout, 0),
+                              2 * n_sets)
+    del xcats
     sink = torch.empty(256 * 512, dtype=torch.float32, device=dev)
     mfma_iters = 4000
     mfma_flops = pq.pq_probe_mfma(mfma_iters, sink)
@@ -230,8 +255,10 @@ def main():
                                "frac_hbm_peak": mbytes / t_mom_warm / 1e9 / HBM_PEAK_GBS},
         "calib_moments_cold": {"us": t_mom_cold * 1e6, "gbs": mbytes / t_mom_cold / 1e9,
                                "frac_hbm_peak": mbytes / t_mom_cold / 1e9 / HBM_PEAK_GBS},
-        "calib_moments_all_batches": {"us": t_mom_all * 1e6, "gbs": nb * mbytes / t_mom_all / 1e9,
-                                      "frac_hbm_peak": nb * mbytes / t_mom_all / 1e9 / HBM_PEAK_GBS},
+        "calib_moments_all_batches_warm": {"us": t_mom_all * 1e6, "gbs": nb * mbytes / t_mom_all / 1e9,
+                                           "frac_hbm_peak": nb * mbytes / t_mom_all / 1e9 / HBM_PEAK_GBS},
+        "calib_moments_all_batches_cold": {"us": t_mom_all_cold * 1e6, "gbs": nb * mbytes / t_mom_all_cold / 1e9,
+                                           "frac_hbm_peak": nb * mbytes / t_mom_all_cold / 1e9 / HBM_PEAK_GBS},
         "forward_quantize_act_plus_qgemm": {"us": t_fwd * 1e6, "tflops": flops / t_fwd / 1e12},
         "quantize_weights_and_pack": {"us": t_qw * 1e6},
         "calibrate_moments_plus_select": {"us": t_cal * 1e6},
@@ -240,7 +267,7 @@ def main():
         # same-run references (not part of the path)
         "reference_stream_quantizer_footprint_cold": {"us": t_floor_q * 1e6, "gbs": qbytes / t_floor_q / 1e9},
         "reference_stream_read_one_batch_cold": {"us": t_floor_m * 1e6, "gbs": mbytes / t_floor_m / 1e9},
-        "reference_stream_read_all_batches": {"us": t_floor_mall * 1e6, "gbs": nb * mbytes / t_floor_mall / 1e9},
+        "reference_stream_read_all_batches_cold": {"us": t_floor_mall * 1e6, "gbs": nb * mbytes / t_floor_mall / 1e9},
         "reference_mfma_only_loop": {"tflops": mfma_sustained, "frac_mfma_f16_peak": mfma_sustained / MFMA_F16_PEAK_TFLOPS},
     }
     if args.no_row_major_comparison:

@@ -300,7 +300,10 @@ __global__ __launch_bounds__(WGM* WGN * 64) void qgemm_kernel(OperandView A, Ope
       const uint4 v = *reinterpret_cast<const uint4*>(smem + row * C_ROW_BYTES + cc * 16);
       uint16_t* yo = yb + (int64_t)m * ldy + n;
       if (n + 7 < N) {
-        *reinterpret_cast<uint4*>(yo) = v;
+        // the output is not read again by this kernel: a streaming store keeps it from displacing
+        // the operand strips in L2
+        typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+        __builtin_nontemporal_store((u32x4){v.x, v.y, v.z, v.w}, reinterpret_cast<u32x4*>(yo));
       } else {
         const uint32_t w[4] = {v.x, v.y, v.z, v.w};
         for (int e = 0; e < 8 && n + e < N; ++e) yo[e] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
