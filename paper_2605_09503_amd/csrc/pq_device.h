@@ -175,6 +175,21 @@ __device__ __forceinline__ uint32_t int_code_bits(float x, float inv, float Q) {
 __device__ __forceinline__ uint32_t int_code(float x, float inv, float Q) {
   return int_code_bits(x, inv, Q) & 0xFu;
 }
+// Eight codes of one chunk, packed (element j at bits 4j, two's complement nibbles), for values
+// whose group maximum produced `inv`: then |x * inv| <= Q (1 + 3 * 2^-24) < Q + 1/2, the rounding
+// already lands inside [-Q, Q] and the clip is a no-op (inv = 0 gives 0).  Adding 1.5 * 2^23 + 8
+// rounds to the nearest integer (ties to even) and leaves z + 8, in 1..15, in the low nibble under
+// constant upper bits; the eight words are summed at nibble offsets (one shift-add each, carries
+// into the discarded upper bits only), the constant part is subtracted once and bit 3 of every
+// nibble flipped, which turns z + 8 into the two's complement of z.
+__device__ __forceinline__ uint32_t int_codes8(const float (&x)[8], float inv) {
+  constexpr uint32_t kBase = 0x4B400000u;                 // bits of 1.5 * 2^23
+  constexpr uint32_t kConst = kBase * 0x11111111u;        // sum of kBase << 4j, modulo 2^32
+  uint32_t acc = 0;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) acc = (as_u32(x[j] * inv + 12582920.0f) << (4 * j)) + acc;
+  return (acc - kConst) ^ 0x88888888u;
+}
 // the same integer as a float (for the error evaluation)
 __device__ __forceinline__ float int_code_value(float x, float inv, float Q) {
   const float v = __builtin_amdgcn_fmed3f(x * inv, -Q, Q);

@@ -38,10 +38,8 @@ __device__ __forceinline__ ChunkOut<FMT> quantize_chunk(const float (&v)[8], flo
     c = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(c, v[6] * s.inv, v[7] * s.inv, 1.0f, 3);
     o.scale = s.byte;
   } else {
-    constexpr float Q = qmax_of(FMT);
     IntScale s = int_scale<FMT>(a);
-#pragma unroll
-    for (int j = 0; j < 8; ++j) c |= int_code(v[j], s.inv, Q) << (4 * j);
+    c = int_codes8(v, s.inv);
     o.scale = as_u32(s.s);
   }
   o.codes = c;
