@@ -253,11 +253,22 @@ __global__ __launch_bounds__(WGM* WGN * 64) void qgemm_kernel(OperandView A, Ope
   // lane and contiguous along n; the fp32 variant (a checking aid) stores directly.
   constexpr int C_ROW_BYTES = BN * 2 + 16;
   static_assert(BM * C_ROW_BYTES <= 2 * STAGE_BYTES, "output tile fits in the operand stages");
+  // The column factors do not depend on the row block: loaded once (16 per MFMA tile column).
+  float wm[TN][16];
+#pragma unroll
+  for (int i = 0; i < TN; ++i)
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int n = n0 + wave_n * WTN + i * 32 + q * 8 + frag_half * 4 + e;
+        wm[i][q * 4 + e] = w_mul[(int64_t)(min(n, N - 1) * w_mul_stride)];
+      }
 #pragma unroll
   for (int j = 0; j < TM; ++j) {
     const int ml = wave_m * WTM + j * 32 + frag_row;
     const int m = m0 + ml;
-    const float am = a_mul[(int64_t)min(m, M - 1) * a_mul_stride];
+    const float am = a_mul[(int64_t)(min(m, M - 1) * a_mul_stride)];
 #pragma unroll
     for (int i = 0; i < TN; ++i) {
 #pragma unroll
@@ -266,10 +277,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void qgemm_kernel(OperandView A, Ope
         const int n = n0 + nl;
         float v[4];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const float wm = w_mul[(int64_t)min(n + e, N - 1) * w_mul_stride];
-          v[e] = acc[i][j][q * 4 + e] * (am * wm);
-        }
+        for (int e = 0; e < 4; ++e) v[e] = acc[i][j][q * 4 + e] * (am * wm[i][q * 4 + e]);
         if constexpr (OUT_F32) {
           if (m < M && n < N) {
             float* yo = reinterpret_cast<float*>(y) + (int64_t)m * ldy + n;
@@ -280,10 +288,13 @@ __global__ __launch_bounds__(WGM* WGN * 64) void qgemm_kernel(OperandView A, Ope
             }
           }
         } else {
-          const uint32_t b0 = f32_to_bf16_rne(v[0]), b1 = f32_to_bf16_rne(v[1]);
-          const uint32_t b2 = f32_to_bf16_rne(v[2]), b3 = f32_to_bf16_rne(v[3]);
+          // round to nearest even, two values per instruction (v_cvt_pk_bf16_f32)
+          typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+          typedef float f32x2_t __attribute__((ext_vector_type(2)));
+          const bf16x2_t lo = __builtin_convertvector((f32x2_t){v[0], v[1]}, bf16x2_t);
+          const bf16x2_t hi = __builtin_convertvector((f32x2_t){v[2], v[3]}, bf16x2_t);
           *reinterpret_cast<uint2*>(smem + ml * C_ROW_BYTES + nl * 2) =
-              make_uint2(b0 | (b1 << 16), b2 | (b3 << 16));
+              make_uint2(__builtin_bit_cast(uint32_t, lo), __builtin_bit_cast(uint32_t, hi));
         }
       }
     }
