@@ -268,6 +268,52 @@ int pq_qgemm_packed_f32(pq_format fmt, int group, const void* a_operand, const f
                         int64_t K, float* y_f32, int64_t ldy, void* stream);
 
 /*
+ * The normalisation layer in front of a quantized linear layer, with the channel reorder
+ * absorbed into its row load (paper App. C: RMSNorm and LayerNorm commute with a channel
+ * permutation if the channel-wise vectors are permuted with it, so the layer can emit
+ * y_P[m, j] = y[m, pi(j)] directly and the reorder costs no pass of its own).
+ *
+ *   PQ_NORM_RMS:    y[m, i] = x[m, i] / sqrt(mean_i x[m, i]^2 + eps) * gamma[i]
+ *   PQ_NORM_ADALN:  y[m, i] = (1 + s[b(m), i]) * LN(x[m, :])[i] + b[b(m), i],
+ *                   LN(x) = (x - mu) / sqrt(sigma^2 + eps), sigma^2 the biased variance,
+ *                   b(m) = m / rows_per_mod (modulation vectors per sample).  A plain affine
+ *                   LayerNorm is s = gamma - 1, b = beta with one modulation row.
+ * Statistics and the affine part are computed in fp32 from the bf16 inputs; the result is
+ * rounded once to bf16 (nearest even).  The quantizing variant then quantizes those bf16 values:
+ *     pq_norm_quantize_act_packed(p, x) == pq_quantize_act_packed(pq_norm_reorder(p, x))   bit for bit.
+ *
+ * pq_norm_params (all pointers device memory, 16-byte aligned; vectors in the ORIGINAL channel order,
+ * the library gathers them with the same pi):
+ *   perm          int32 [K], a permutation of 0..K-1 as pq_select_perm emits it, or NULL (identity)
+ *   gamma         bf16 [K] (RMS), NULL = ones
+ *   mod_scale     bf16 [ceil(M / rows_per_mod), K] (ADALN), NULL = zeros
+ *   mod_shift     bf16 [ceil(M / rows_per_mod), K] (ADALN), NULL = zeros
+ *   rows_per_mod  tokens per modulation row; <= 0 means one row for all tokens
+ *   eps           added to the mean square / variance under the root
+ * x: bf16 [M, ld], ld >= K, ld % 8 == 0.  y: bf16 [M, ldy], ldy >= K, ldy % 8 == 0, may not overlap x.
+ * K % 8 == 0 (K % 32 == 0 for the quantizing variant) and small enough for eight rows and the
+ * vectors to be staged in one workgroup's LDS: 20 K bytes (RMS: 18 K) plus 32 bytes per INT group of a
+ * row must stay below 158 KB (K <= 7680 for AdaLN + INT4 g64), else PQ_ERR_SHAPE.
+ * pq_norm_quantize_act_packed: operand as for pq_quantize_act_packed; y optional (NULL to skip;
+ * ldy ignored then).  Both run on `stream` and return PQ_OK or a PQ_ERR_* code.
+ */
+typedef enum { PQ_NORM_RMS = 0, PQ_NORM_ADALN = 1 } pq_norm_kind;
+typedef struct {
+  pq_norm_kind kind;
+  const int32_t* perm;
+  const void* gamma;
+  const void* mod_scale;
+  const void* mod_shift;
+  int64_t rows_per_mod;
+  float eps;
+} pq_norm_params;
+int pq_norm_reorder(const pq_norm_params* p, const void* x_bf16, int64_t M, int64_t K, int64_t ld,
+                    void* y_bf16, int64_t ldy, void* stream);
+int pq_norm_quantize_act_packed(const pq_norm_params* p, pq_format fmt, int group, const void* x_bf16,
+                                int64_t M, int64_t K, int64_t ld, const float* tensor_scale, void* operand,
+                                size_t operand_size, void* y_bf16, int64_t ldy, void* stream);
+
+/*
  * Measurement aids (no part of the method; they give the timings of the kernels above a
  * reference measured on the same device in the same run).
  *

@@ -35,6 +35,15 @@ class _Report(C.Structure):
                 ("sum_x2", C.c_double), ("sum_w2", C.c_double)]
 
 
+class NormParams(C.Structure):
+    """pq_norm_params of the header."""
+    _fields_ = [("kind", C.c_int), ("perm", C.c_void_p), ("gamma", C.c_void_p), ("mod_scale", C.c_void_p),
+                ("mod_shift", C.c_void_p), ("rows_per_mod", C.c_int64), ("eps", C.c_float)]
+
+
+NORM_RMS, NORM_ADALN = 0, 1
+
+
 def lib_path() -> str:
     return _LIB_PATH
 
@@ -75,6 +84,9 @@ def load():
     packed_args = [i32, i32, vp, vp, vp, vp, i64, i64, i64, vp, i64, vp]
     lib.pq_qgemm_packed.argtypes = packed_args
     lib.pq_qgemm_packed_f32.argtypes = packed_args
+    lib.pq_norm_reorder.argtypes = [C.POINTER(NormParams), vp, i64, i64, i64, vp, i64, vp]
+    lib.pq_norm_quantize_act_packed.argtypes = [C.POINTER(NormParams), i32, i32, vp, i64, i64, i64, vp, vp, sz,
+                                                vp, i64, vp]
     lib.pq_probe_stream.argtypes = [vp, sz, vp, sz, vp]
     lib.pq_probe_mfma.argtypes = [i32, vp, C.POINTER(C.c_double), vp]
     for name in ("pq_calib_moments", "pq_calib_moments_batched", "pq_select_perm", "pq_quant_error", "pq_quantize_weights",
@@ -277,6 +289,43 @@ def pq_quantize_act_packed(fmt: int, group: int, x: torch.Tensor, tensor_scale: 
         operand = torch.empty(max(pq_operand_bytes(fmt, group, M, K), 16), dtype=torch.uint8, device=x.device)
     _check(load().pq_quantize_act_packed(fmt, group, _ptr(x), M, K, x.stride(0), _ptr(tensor_scale),
                                          _ptr(operand), operand.numel(), _ptr(codes), _ptr(scales), _stream()))
+    return operand
+
+
+def _norm_params(kind, perm, gamma, mod_scale, mod_shift, rows_per_mod, eps) -> "NormParams":
+    raw = [None if t is None else t.data_ptr() for t in (perm, gamma, mod_scale, mod_shift)]
+    return NormParams(int(kind), raw[0], raw[1], raw[2], raw[3], int(rows_per_mod), float(eps))
+
+
+def pq_norm_reorder(kind: int, x: torch.Tensor, eps: float, perm: Optional[torch.Tensor] = None,
+                    gamma: Optional[torch.Tensor] = None, mod_scale: Optional[torch.Tensor] = None,
+                    mod_shift: Optional[torch.Tensor] = None, rows_per_mod: int = 0,
+                    y: Optional[torch.Tensor] = None, K: Optional[int] = None) -> torch.Tensor:
+    """RMSNorm / modulated LayerNorm whose output comes out in the channel order `perm` (bf16 [M, K])."""
+    M = x.shape[0]
+    K = x.shape[1] if K is None else K
+    if y is None:
+        y = torch.empty((M, K), dtype=torch.bfloat16, device=x.device)
+    p = _norm_params(kind, perm, gamma, mod_scale, mod_shift, rows_per_mod, eps)
+    _check(load().pq_norm_reorder(C.byref(p), _ptr(x), M, K, x.stride(0), _ptr(y), y.stride(0), _stream()))
+    return y
+
+
+def pq_norm_quantize_act_packed(kind: int, fmt: int, group: int, x: torch.Tensor, eps: float,
+                                tensor_scale: Optional[torch.Tensor], perm: Optional[torch.Tensor] = None,
+                                gamma: Optional[torch.Tensor] = None, mod_scale: Optional[torch.Tensor] = None,
+                                mod_shift: Optional[torch.Tensor] = None, rows_per_mod: int = 0,
+                                operand: Optional[torch.Tensor] = None, y: Optional[torch.Tensor] = None,
+                                K: Optional[int] = None) -> torch.Tensor:
+    """The same layer feeding the activation quantizer directly: returns the GEMM operand."""
+    M = x.shape[0]
+    K = x.shape[1] if K is None else K
+    if operand is None:
+        operand = torch.empty(max(pq_operand_bytes(fmt, group, M, K), 16), dtype=torch.uint8, device=x.device)
+    p = _norm_params(kind, perm, gamma, mod_scale, mod_shift, rows_per_mod, eps)
+    _check(load().pq_norm_quantize_act_packed(C.byref(p), fmt, group, _ptr(x), M, K, x.stride(0),
+                                              _ptr(tensor_scale), _ptr(operand), operand.numel(), _ptr(y),
+                                              0 if y is None else y.stride(0), _stream()))
     return operand
 
 

@@ -167,3 +167,27 @@ def test_packed_operand_validation(lib):
     assert lib.pq_probe_mfma(0, FAKE, None, None) == PQ_ERR_SHAPE
     assert lib.pq_probe_stream(None, 16, FAKE, 0, None) == PQ_ERR_NULL
     assert lib.pq_probe_stream(FAKE, 24, FAKE, 0, None) == PQ_ERR_SHAPE
+
+
+def test_norm_validation(lib):
+    def params(kind=0, perm=None, gamma=None, eps=1e-6):
+        return pq.NormParams(kind, perm, gamma, None, None, 0, eps)
+    f = lib.pq_norm_reorder
+    ok = params()
+    assert f(None, FAKE, 8, 64, 64, FAKE, 64, None) == PQ_ERR_NULL
+    assert f(C.byref(ok), None, 8, 64, 64, FAKE, 64, None) == PQ_ERR_NULL
+    assert f(C.byref(ok), FAKE, 8, 64, 64, None, 64, None) == PQ_ERR_NULL
+    assert f(C.byref(params(kind=5)), FAKE, 8, 64, 64, FAKE, 64, None) == PQ_ERR_FORMAT
+    assert f(C.byref(ok), FAKE, 0, 64, 64, FAKE, 64, None) == PQ_ERR_SHAPE
+    assert f(C.byref(ok), FAKE, 8, 60, 64, FAKE, 64, None) == PQ_ERR_SHAPE          # K % 8
+    assert f(C.byref(ok), FAKE, 8, 64, 56, FAKE, 64, None) == PQ_ERR_SHAPE          # ld < K
+    assert f(C.byref(ok), FAKE, 8, 64, 64, FAKE, 60, None) == PQ_ERR_SHAPE          # ldy
+    assert f(C.byref(params(eps=-1.0)), FAKE, 8, 64, 64, FAKE, 64, None) == PQ_ERR_SHAPE
+    assert f(C.byref(params(perm=0x1004)), FAKE, 8, 64, 64, FAKE, 64, None) == PQ_ERR_SHAPE   # alignment
+    g = lib.pq_norm_quantize_act_packed
+    assert g(C.byref(ok), 1, 64, FAKE, 8, 64, 64, None, None, 1 << 20, None, 0, None) == PQ_ERR_NULL
+    assert g(C.byref(ok), 0, 16, FAKE, 8, 64, 64, None, FAKE, 1 << 20, None, 0, None) == PQ_ERR_NULL   # NVFP4 scale
+    assert g(C.byref(ok), 1, 48, FAKE, 8, 96, 96, None, FAKE, 1 << 20, None, 0, None) == PQ_ERR_FORMAT
+    assert g(C.byref(ok), 0, 16, FAKE, 8, 48, 48, FAKE, FAKE, 1 << 20, None, 0, None) == PQ_ERR_SHAPE   # K % 32
+    assert g(C.byref(ok), 1, 64, FAKE, 8, 64, 64, None, FAKE, 16, None, 0, None) == PQ_ERR_WORKSPACE
+    assert b"operand buffer" in lib.pq_last_error()
