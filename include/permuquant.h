@@ -291,9 +291,9 @@ int pq_qgemm_packed_f32(pq_format fmt, int group, const void* a_operand, const f
  *   rows_per_mod  tokens per modulation row; <= 0 means one row for all tokens
  *   eps           added to the mean square / variance under the root
  * x: bf16 [M, ld], ld >= K, ld % 8 == 0.  y: bf16 [M, ldy], ldy >= K, ldy % 8 == 0, may not overlap x.
- * K % 8 == 0 (K % 32 == 0 for the quantizing variant) and small enough for eight rows and the
- * vectors to be staged in one workgroup's LDS: 20 K bytes (RMS: 18 K) plus 32 bytes per INT group of a
- * row must stay below 158 KB (K <= 7680 for AdaLN + INT4 g64), else PQ_ERR_SHAPE.
+ * K % 8 == 0 (K % 32 == 0 for the quantizing variant) and small enough for one row and the vectors
+ * to be staged in a workgroup's LDS: 6 K bytes (RMS: 4 K) plus 4 bytes per INT group of a row must
+ * stay below 159 KB (K <= 26000 for AdaLN), else PQ_ERR_SHAPE.
  * pq_norm_quantize_act_packed: operand as for pq_quantize_act_packed; y optional (NULL to skip;
  * ldy ignored then).  Both run on `stream` and return PQ_OK or a PQ_ERR_* code.
  */

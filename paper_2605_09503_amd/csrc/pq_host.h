@@ -54,6 +54,21 @@ int run_qgemm(pq_format fmt, int group, const uint8_t* a_codes, const void* a_sc
               void* ws, hipStream_t st);   // phases: 1 = scale preparation, 2 = product
 
 
+// Panel layout of a quantized operand (see pq_pack.hip): byte offsets of its parts.
+struct OperandLayout {
+  size_t codes, scales, mul, total;     // byte offsets and total size
+  int64_t steps, units;
+};
+inline OperandLayout operand_layout(pq_format fmt, int group, int64_t rows, int64_t K) {
+  OperandLayout L;
+  L.steps = (K + 63) / 64;
+  L.units = fmt == PQ_FMT_NVFP4 ? (K + 31) / 32 : K / group;
+  L.codes = 0;
+  L.scales = align_up((size_t)L.steps * rows * 32, 256);
+  L.mul = L.scales + align_up((size_t)L.units * rows * 2, 256);
+  L.total = L.mul + (fmt == PQ_FMT_NVFP4 ? 0 : align_up((size_t)rows * 4, 256));
+  return L;
+}
 size_t operand_bytes(pq_format fmt, int group, int64_t rows, int64_t K);
 int run_pack_operand(pq_format fmt, int group, const uint8_t* codes, const void* scales, int64_t rows,
                      int64_t K, void* operand, hipStream_t st);

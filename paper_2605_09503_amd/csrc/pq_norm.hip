@@ -1,0 +1,472 @@
+// The normalisation layer in front of a quantized linear layer with the channel reorder absorbed
+// into it (paper App. C): RMSNorm, or LayerNorm followed by a per-sample scale and shift, emitting
+// y_P[m, j] = y[m, pi(j)] as a bf16 tensor, as the activation operand of the GEMM (the dynamic
+// quantizer of Eq. 1-2 applied to those bf16 values), or both.
+//
+// One wave owns one token row from load to store, so no step waits for another wave:
+//   1. the row is read as it lies in memory (16 bytes per lane and access, whole lines), its sum
+//      and sum of squares come from v_dot2c_f32_bf16 on the packed pairs, and it is parked in the
+//      wave's own slab of LDS;
+//   2. lane l then produces chunks l, l + 64, ... (8 consecutive positions j each) of the reordered
+//      row: it loads pi(j) for its positions and gathers x[pi(j)] from the slab with 2-byte LDS
+//      reads -- where the paper's kernel issues indexed global loads -- normalises, applies the
+//      channel-wise vectors and rounds to bf16;
+//   3. the bf16 chunk is stored (consecutive lanes, consecutive 16 bytes) and / or quantized: a
+//      group of G positions is G / 8 consecutive lanes, so the group maximum is a lane reduction
+//      and the per-row power of two of the INT operand layout a wave reduction.
+// The channel-wise vectors are shared by the rows of a workgroup: they are staged in LDS already
+// reordered (position j holds the value of channel pi(j)) once per workgroup, which is the only
+// step all waves wait for.
+#include <algorithm>
+
+#include "pq_qgemm_common.h"
+
+namespace pq {
+
+namespace {
+
+enum Norm : int { kNormRms = 0, kNormAdaLn = 1 };
+constexpr int kFmtNone = -1;                  // normalise and reorder only, no quantization
+constexpr int kNormMaxWaves = 8;
+
+struct NormArgs {
+  const int32_t* perm;          // pi, or null for the identity
+  const uint16_t* gamma;        // RMSNorm: bf16 [K], or null for ones
+  const uint16_t* mod_scale;    // AdaLN: bf16 [n_mod][K] s (the factor is 1 + s), or null for zeros
+  const uint16_t* mod_shift;    // AdaLN: bf16 [n_mod][K] b, or null for zeros
+  int64_t rows_per_mod;         // token row m uses modulation row m / rows_per_mod
+  float eps;
+  uint16_t* y;                  // bf16 [rows][ldy] normalised, reordered output, or null
+  int64_t ldy;
+};
+
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ float wave_sum_f32(float v) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, kWave);
+  return v;
+}
+
+__device__ __forceinline__ uint32_t pack_bf16_rne(float lo, float hi) {
+  typedef float f32x2_t __attribute__((ext_vector_type(2)));
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2_t){lo, hi}, bf16x2_t));
+}
+
+struct Idx8 {
+  int4 lo, hi;
+};
+
+template <int FMT, int G, int NORM>
+__global__ __launch_bounds__(64 * kNormMaxWaves) void norm_rows_kernel(
+    const uint16_t* __restrict__ x, int64_t rows, int64_t K, int64_t ld, const float* __restrict__ tensor_scale,
+    int64_t steps, int64_t units, uint8_t* __restrict__ p_codes, uint16_t* __restrict__ p_scales,
+    float* __restrict__ p_mul, NormArgs na) {
+  constexpr bool QUANT = FMT != kFmtNone;
+  constexpr bool IS_INT = FMT == kInt4 || FMT == kInt3;
+  constexpr int LPG = G / 8;                                 // lanes that share a group
+  // chunks a lane works on at a time (AdaLN holds more per chunk: two keep it at five waves per SIMD)
+  constexpr int kBatch = NORM == kNormAdaLn ? 2 : 3;
+  static_assert(LPG >= 1 && LPG <= 64, "a group lies inside one wave-wide run of chunks");
+  // dynamic LDS: [vectors: K bf16 (RMSNorm) or K words (AdaLN)] [per wave: K bf16 row slab]
+  //              [per wave, INT: `units` fp32 group maxima]
+  extern __shared__ __align__(16) unsigned char lds_raw[];
+  const int tid = threadIdx.x, lane = tid & 63, n_waves = blockDim.x >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int Ki = (int)K;
+  const int k_chunks = Ki / 8;                               // chunks that exist
+  const int n_chunks = (int)steps * 8;                       // chunks the panel holds (a half step past K included)
+  const int n_units = (int)units;
+  const int64_t row0 = (int64_t)blockIdx.x * n_waves;
+  const int64_t row = row0 + wave;
+
+  uint16_t* vec_g = reinterpret_cast<uint16_t*>(lds_raw);
+  uint32_t* vec_sb = reinterpret_cast<uint32_t*>(lds_raw);
+  const size_t vec_bytes = (size_t)Ki * (NORM == kNormRms ? 2 : 4);
+  uint16_t* slab = reinterpret_cast<uint16_t*>(lds_raw + vec_bytes) + (size_t)wave * Ki;
+  float* h_lds = reinterpret_cast<float*>(lds_raw + vec_bytes + (size_t)n_waves * Ki * 2) + (size_t)wave * n_units;
+
+  // ---- the vectors of the first row's sample, reordered, into LDS (all threads).  Scattered
+  // 2-byte loads from memory cost the texture addresser a cycle per lane, so the vectors are first
+  // copied as they lie (whole lines) into the space of the row slabs, which is still free, and
+  // reordered from there with LDS reads.  (If a single slab is smaller than the two AdaLN vectors,
+  // they are gathered from memory instead.)
+  int64_t mod0 = 0;
+  if constexpr (NORM == kNormAdaLn) mod0 = row0 / na.rows_per_mod;
+  {
+    const uint16_t* v0 = NORM == kNormRms ? na.gamma : (na.mod_scale ? na.mod_scale + mod0 * K : nullptr);
+    const uint16_t* v1 = NORM == kNormRms ? nullptr : (na.mod_shift ? na.mod_shift + mod0 * K : nullptr);
+    constexpr uint32_t kDefault0 = NORM == kNormRms ? 0x3F80u : 0u;      // gamma = 1, s = 0
+    uint16_t* tmp0 = reinterpret_cast<uint16_t*>(lds_raw + vec_bytes);
+    uint16_t* tmp1 = tmp0 + Ki;
+    const bool via_lds = (size_t)n_waves * Ki * 2 >= vec_bytes;          // uniform over the workgroup
+    if (via_lds) {
+      for (int c = tid; c < k_chunks; c += blockDim.x) {
+        if (v0) *reinterpret_cast<uint4*>(tmp0 + c * 8) = *reinterpret_cast<const uint4*>(v0 + (size_t)c * 8);
+        if (v1) *reinterpret_cast<uint4*>(tmp1 + c * 8) = *reinterpret_cast<const uint4*>(v1 + (size_t)c * 8);
+      }
+      __syncthreads();
+    }
+    for (int c = tid; c < k_chunks; c += blockDim.x) {
+      int idx[8];
+      if (na.perm) {
+        const int4 i0 = *reinterpret_cast<const int4*>(na.perm + (size_t)c * 8);
+        const int4 i1 = *reinterpret_cast<const int4*>(na.perm + (size_t)c * 8 + 4);
+        idx[0] = i0.x; idx[1] = i0.y; idx[2] = i0.z; idx[3] = i0.w;
+        idx[4] = i1.x; idx[5] = i1.y; idx[6] = i1.z; idx[7] = i1.w;
+      } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) idx[e] = c * 8 + e;
+      }
+      uint32_t a0[8], a1[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) a0[e] = kDefault0, a1[e] = 0u;
+      if (v0) {
+        if (via_lds) {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) a0[e] = tmp0[idx[e]];
+        } else {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) a0[e] = v0[idx[e]];
+        }
+      }
+      if (v1) {
+        if (via_lds) {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) a1[e] = tmp1[idx[e]];
+        } else {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) a1[e] = v1[idx[e]];
+        }
+      }
+      if constexpr (NORM == kNormRms) {
+        *reinterpret_cast<uint4*>(vec_g + c * 8) = make_uint4(a0[0] | (a0[1] << 16), a0[2] | (a0[3] << 16),
+                                                               a0[4] | (a0[5] << 16), a0[6] | (a0[7] << 16));
+      } else {
+        *reinterpret_cast<uint4*>(vec_sb + c * 8) = make_uint4(a0[0] | (a1[0] << 16), a0[1] | (a1[1] << 16),
+                                                                a0[2] | (a1[2] << 16), a0[3] | (a1[3] << 16));
+        *reinterpret_cast<uint4*>(vec_sb + c * 8 + 4) = make_uint4(a0[4] | (a1[4] << 16), a0[5] | (a1[5] << 16),
+                                                                    a0[6] | (a1[6] << 16), a0[7] | (a1[7] << 16));
+      }
+    }
+  }
+  __syncthreads();                       // the last barrier; every wave reaches it (the slabs are free again)
+  if (row >= rows) return;               // wave-uniform
+
+  // indices pi(j) of chunk c (clamped to an existing chunk: the address is always valid)
+  auto load_idx = [&](int c) -> Idx8 {
+    const int cc = min(c, k_chunks - 1);
+    Idx8 ix;
+    if (na.perm) {
+      ix.lo = *reinterpret_cast<const int4*>(na.perm + (size_t)cc * 8);
+      ix.hi = *reinterpret_cast<const int4*>(na.perm + (size_t)cc * 8 + 4);
+    } else {
+      ix.lo = make_int4(cc * 8, cc * 8 + 1, cc * 8 + 2, cc * 8 + 3);
+      ix.hi = make_int4(cc * 8 + 4, cc * 8 + 5, cc * 8 + 6, cc * 8 + 7);
+    }
+    return ix;
+  };
+  const float k_f = (float)Ki;
+  float T = 0.0f, encT = 0.0f;
+  if constexpr (FMT == kNvfp4) {
+    T = *tensor_scale;
+    encT = nv4_enc_scale(T);
+  }
+  const int n_iter = (n_chunks + 63) / 64;
+
+  // the first batch of indices does not depend on the row's values
+  Idx8 ix_cur[kBatch];
+#pragma unroll
+  for (int q = 0; q < kBatch; ++q) ix_cur[q] = load_idx(lane + 64 * q);
+
+  // ---- 1. the row: statistics, and a copy in the wave's slab
+  const uint16_t* xr = x + row * ld;
+  float s1 = 0.0f, s2 = 0.0f;
+  {
+    const bf16x2_t ones = __builtin_bit_cast(bf16x2_t, 0x3F803F80u);
+    constexpr int kInFlight = 8;                            // lines per lane requested together
+    for (int c0 = 0; c0 < k_chunks; c0 += kInFlight * 64) {
+      uint4 lines[kInFlight];
+#pragma unroll
+      for (int t = 0; t < kInFlight; ++t) {
+        const int c = min(c0 + t * 64 + lane, k_chunks - 1);
+        lines[t] = *reinterpret_cast<const uint4*>(xr + (size_t)c * 8);
+      }
+#pragma unroll
+      for (int t = 0; t < kInFlight; ++t) {
+        const int c = c0 + t * 64 + lane;
+        if (c < k_chunks) {
+          *reinterpret_cast<uint4*>(slab + c * 8) = lines[t];
+          const uint32_t d[4] = {lines[t].x, lines[t].y, lines[t].z, lines[t].w};
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const bf16x2_t v = __builtin_bit_cast(bf16x2_t, d[e]);
+            if constexpr (NORM == kNormAdaLn) s1 = __builtin_amdgcn_fdot2_f32_bf16(v, ones, s1, false);
+            s2 = __builtin_amdgcn_fdot2_f32_bf16(v, v, s2, false);
+          }
+        }
+      }
+    }
+  }
+  s2 = wave_sum_f32(s2);
+  float mean = 0.0f;
+  if constexpr (NORM == kNormAdaLn) {
+    mean = wave_sum_f32(s1) / k_f;
+    // variance = mean square - mean^2 loses accuracy when the mean dominates; then (rare, uniform
+    // over the wave) it is recomputed from the deviations, on the lane's own chunks in LDS
+    const float mean_sq = s2 / k_f;
+    const float var = mean_sq - mean * mean;
+    if (mean_sq > 16.0f * var) {
+      float s3 = 0.0f;
+      for (int c = lane; c < k_chunks; c += 64) {
+        const uint4 p = *reinterpret_cast<const uint4*>(slab + c * 8);
+        const uint32_t d[4] = {p.x, p.y, p.z, p.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float lo = bf16_lo(d[e]) - mean, hi = bf16_hi(d[e]) - mean;
+          s3 = fmaf(hi, hi, fmaf(lo, lo, s3));
+        }
+      }
+      s2 = wave_sum_f32(s3);
+    } else {
+      s2 = var * k_f;
+    }
+  }
+  const float rstd = 1.0f / sqrtf(s2 / k_f + na.eps);
+  const float nmr = -mean * rstd;                            // LN(x) = x * rstd + nmr
+
+  // AdaLN: a row of another sample than the staged one reads its vectors from memory
+  bool own_mod = false;
+  const uint16_t* g_scale = nullptr;
+  const uint16_t* g_shift = nullptr;
+  if constexpr (NORM == kNormAdaLn) {
+    const int64_t mod = row / na.rows_per_mod;
+    own_mod = mod != mod0;                                   // wave-uniform
+    g_scale = na.mod_scale ? na.mod_scale + mod * K : nullptr;
+    g_shift = na.mod_shift ? na.mod_shift + mod * K : nullptr;
+  }
+
+  float row_max = 0.0f;
+  uint16_t* y_row = na.y ? na.y + row * na.ldy : nullptr;
+
+  // ---- 2./3. chunks lane, lane + 64, ... of the reordered row, kBatch at a time
+  for (int it0 = 0; it0 < n_iter; it0 += kBatch) {
+    // next batch's indices while this one is worked on
+    Idx8 ix_next[kBatch];
+#pragma unroll
+    for (int q = 0; q < kBatch; ++q) ix_next[q] = load_idx(lane + 64 * (it0 + kBatch + q));
+    // gathers of the whole batch in flight together
+    float xv[kBatch][8];
+#pragma unroll
+    for (int q = 0; q < kBatch; ++q) {
+      const int idx[8] = {ix_cur[q].lo.x, ix_cur[q].lo.y, ix_cur[q].lo.z, ix_cur[q].lo.w,
+                          ix_cur[q].hi.x, ix_cur[q].hi.y, ix_cur[q].hi.z, ix_cur[q].hi.w};
+#pragma unroll
+      for (int e = 0; e < 8; ++e) xv[q][e] = bf16_to_f32(slab[idx[e]]);
+    }
+#pragma unroll
+    for (int q = 0; q < kBatch; ++q) {
+      const int c = lane + 64 * (it0 + q);
+      if (it0 + q >= n_iter) break;                          // wave-uniform
+      const bool in_row = c < k_chunks;
+      const int cc = min(c, k_chunks - 1);
+      float yv[8];
+      if constexpr (NORM == kNormRms) {
+        const uint4 gq = *reinterpret_cast<const uint4*>(vec_g + cc * 8);
+        const uint32_t gw[4] = {gq.x, gq.y, gq.z, gq.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          yv[2 * e] = (xv[q][2 * e] * rstd) * bf16_lo(gw[e]);
+          yv[2 * e + 1] = (xv[q][2 * e + 1] * rstd) * bf16_hi(gw[e]);
+        }
+      } else {
+        uint32_t sb[8];
+        if (own_mod) {
+          const int idx[8] = {ix_cur[q].lo.x, ix_cur[q].lo.y, ix_cur[q].lo.z, ix_cur[q].lo.w,
+                              ix_cur[q].hi.x, ix_cur[q].hi.y, ix_cur[q].hi.z, ix_cur[q].hi.w};
+#pragma unroll
+          for (int e = 0; e < 8; ++e)
+            sb[e] = (g_scale ? (uint32_t)g_scale[idx[e]] : 0u) | (g_shift ? (uint32_t)g_shift[idx[e]] << 16 : 0u);
+        } else {
+          const uint4 q0 = *reinterpret_cast<const uint4*>(vec_sb + cc * 8);
+          const uint4 q1 = *reinterpret_cast<const uint4*>(vec_sb + cc * 8 + 4);
+          sb[0] = q0.x; sb[1] = q0.y; sb[2] = q0.z; sb[3] = q0.w;
+          sb[4] = q1.x; sb[5] = q1.y; sb[6] = q1.z; sb[7] = q1.w;
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const float ln = fmaf(xv[q][e], rstd, nmr);
+          yv[e] = fmaf(bf16_lo(sb[e]), ln, bf16_hi(sb[e])) + ln;       // (1 + s) ln + b
+        }
+      }
+      uint4 yb = make_uint4(pack_bf16_rne(yv[0], yv[1]), pack_bf16_rne(yv[2], yv[3]),
+                            pack_bf16_rne(yv[4], yv[5]), pack_bf16_rne(yv[6], yv[7]));
+      if (!in_row) yb = make_uint4(0u, 0u, 0u, 0u);          // the half step past K holds zeros
+      if (y_row && in_row) *reinterpret_cast<uint4*>(y_row + (size_t)c * 8) = yb;
+
+      if constexpr (QUANT) {
+        // the quantizer of pq_quantize.hip on the rounded values
+        float v[8] = {bf16_lo(yb.x), bf16_hi(yb.x), bf16_lo(yb.y), bf16_hi(yb.y),
+                      bf16_lo(yb.z), bf16_hi(yb.z), bf16_lo(yb.w), bf16_hi(yb.w)};
+        float a = 0.0f;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) a = fmaxf(a, fabsf(v[j]));
+        a = group_max<LPG>(a);
+        uint32_t codes;
+        if constexpr (FMT == kNvfp4) {
+          const Nv4Scale sc = nv4_scale(a, T, encT);
+          codes = 0;
+          codes = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(codes, v[0] * sc.inv, v[1] * sc.inv, 1.0f, 0);
+          codes = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(codes, v[2] * sc.inv, v[3] * sc.inv, 1.0f, 1);
+          codes = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(codes, v[4] * sc.inv, v[5] * sc.inv, 1.0f, 2);
+          codes = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(codes, v[6] * sc.inv, v[7] * sc.inv, 1.0f, 3);
+          // a scale unit is the two bytes of 32 positions = four lanes; the first lane of the quad
+          // collects the byte of the second pair
+          const uint32_t other = dpp_u32<0x4E>(sc.byte);         // lane ^ 2
+          const int u = c >> 2;
+          if ((lane & 3) == 0 && u < n_units) p_scales[(int64_t)u * rows + row] = (uint16_t)(sc.byte | (other << 8));
+        } else {
+          constexpr int FI = IS_INT ? FMT : kInt4;
+          const IntScale sc = int_scale<FI>(a);
+          codes = int_codes8(v, sc.inv);
+          row_max = fmaxf(row_max, a);
+          const int g = c / LPG;
+          if (lane % LPG == 0 && g < n_units) h_lds[g] = a;
+        }
+        if (c < n_chunks) *reinterpret_cast<uint32_t*>(p_codes + ((int64_t)(c >> 3) * rows + row) * 32 + (c & 7) * 4) = codes;
+      }
+    }
+#pragma unroll
+    for (int q = 0; q < kBatch; ++q) ix_cur[q] = ix_next[q];
+  }
+
+  if constexpr (IS_INT) {
+    // the per-row power of two of the operand layout: E = exponent(row maximum) - 10 puts the
+    // largest group maximum in [2^10, 2^11) (see pack_operand_kernel); scale units are the fp16
+    // group maxima times 2^-E, the row factor 2^E / Q
+    constexpr float Q = qmax_of(FMT);
+    const float mx = wave_max(row_max);
+    int e = (int)((as_u32(mx) >> 23) & 0xFF) - 127;
+    if (mx == 0.0f) e = 0;
+    const int E = max(-120, min(120, e - 10));
+    const float down = as_f32((uint32_t)(127 - E) << 23);
+    if (lane == 0) p_mul[row] = as_f32((uint32_t)(127 + E) << 23) / Q;
+    for (int u = lane; u < n_units; u += 64) {       // the wave's own LDS writes, in order
+      const _Float16 hn = (_Float16)(h_lds[u] * down);
+      p_scales[(int64_t)u * rows + row] = __builtin_bit_cast(uint16_t, hn);
+    }
+  }
+}
+
+constexpr size_t kNormLdsLimit = 160 * 1024 - 1024;      // dynamic LDS a workgroup may ask for
+
+size_t norm_lds_bytes(int norm, bool is_int, int n_waves, int64_t K, int64_t units) {
+  return (size_t)K * (norm == kNormRms ? 2 : 4) + (size_t)n_waves * K * 2 + (is_int ? (size_t)n_waves * units * 4 : 0);
+}
+
+// Waves (= rows) per workgroup: as many as still let the launch run in one round of resident
+// workgroups, so that the reordered vectors are built as rarely as possible without leaving a
+// tail of workgroups that start when the others are done.  How many workgroups of a given size a
+// compute unit holds (registers, LDS, wave slots) is asked of the runtime.
+template <typename Kern>
+int norm_waves_per_group(Kern kern, int norm, bool is_int, int64_t rows, int64_t K, int64_t units) {
+  int best = 1;
+  double best_cost = 1e30;
+  for (int w = 1; w <= kNormMaxWaves; ++w) {
+    const size_t lds = norm_lds_bytes(norm, is_int, w, K, units);
+    if (lds > kNormLdsLimit) break;
+    int per_cu = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, 64 * w, lds) != hipSuccess || per_cu < 1)
+      per_cu = 1;
+    const int64_t groups = (rows + w - 1) / w;
+    const int64_t rounds = (groups + 256 * (int64_t)per_cu - 1) / (256 * (int64_t)per_cu);
+    // time ~ rounds x (row work + vector staging shared by w rows), in units of one row's work;
+    // among equal costs prefer more waves in flight per compute unit
+    const double cost = (double)rounds * (1.0 + 0.35 / w) - 1e-3 * (double)std::min(per_cu * w, 32);
+    if (cost < best_cost) best_cost = cost, best = w;
+  }
+  return best;
+}
+
+template <int FMT, int G, int NORM>
+int launch_norm_rows(const void* x, int64_t rows, int64_t K, int64_t ld, const float* ts, const OperandLayout& L,
+                     uint8_t* operand, const NormArgs& na, hipStream_t st) {
+  constexpr bool is_int = FMT == kInt4 || FMT == kInt3;
+  if (norm_lds_bytes(NORM, is_int, 1, K, L.units) > kNormLdsLimit)
+    return fail(PQ_ERR_SHAPE, "K=%lld needs %zu bytes of LDS for one row and the vectors, more than the %zu available",
+                (long long)K, norm_lds_bytes(NORM, is_int, 1, K, L.units), kNormLdsLimit);
+  auto kern = norm_rows_kernel<FMT, G, NORM>;
+  // the choice depends on the shape only: remembered from the previous launch of this kernel
+  static thread_local struct { int64_t rows, K; int n_waves; } memo = {0, 0, 0};
+  if (memo.rows != rows || memo.K != K) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)kNormLdsLimit);
+    if (e != hipSuccess) return check_hip(e, "hipFuncSetAttribute(norm_rows_kernel)");
+    memo.n_waves = norm_waves_per_group(kern, NORM, is_int, rows, K, L.units);
+    memo.rows = rows;
+    memo.K = K;
+  }
+  const int n_waves = memo.n_waves;
+  const size_t shmem = norm_lds_bytes(NORM, is_int, n_waves, K, L.units);
+  const int64_t groups = (rows + n_waves - 1) / n_waves;
+  hipLaunchKernelGGL(kern, dim3((unsigned)groups), dim3(64 * n_waves), shmem, st, (const uint16_t*)x, rows, K, ld, ts,
+                     L.steps, L.units, operand ? operand + L.codes : nullptr,
+                     (uint16_t*)(operand ? operand + L.scales : nullptr),
+                     (float*)(operand ? operand + L.mul : nullptr), na);
+  return check_hip(hipGetLastError(), "norm_rows_kernel");
+}
+
+template <int FMT, int G>
+int launch_norm(int norm, const void* x, int64_t rows, int64_t K, int64_t ld, const float* ts,
+                const OperandLayout& L, uint8_t* operand, const NormArgs& na, hipStream_t st) {
+  if (norm == kNormRms) return launch_norm_rows<FMT, G, kNormRms>(x, rows, K, ld, ts, L, operand, na, st);
+  return launch_norm_rows<FMT, G, kNormAdaLn>(x, rows, K, ld, ts, L, operand, na, st);
+}
+
+NormArgs norm_args(const pq_norm_params& p, void* y, int64_t ldy) {
+  NormArgs na;
+  na.perm = p.perm;
+  na.gamma = (const uint16_t*)p.gamma;
+  na.mod_scale = (const uint16_t*)p.mod_scale;
+  na.mod_shift = (const uint16_t*)p.mod_shift;
+  na.rows_per_mod = p.rows_per_mod > 0 ? p.rows_per_mod : INT64_MAX;
+  na.eps = p.eps;
+  na.y = (uint16_t*)y;
+  na.ldy = ldy;
+  return na;
+}
+
+}  // namespace
+
+int run_norm_reorder(const pq_norm_params& p, const void* x, int64_t rows, int64_t K, int64_t ld, void* y,
+                     int64_t ldy, hipStream_t st) {
+  OperandLayout L = {};
+  L.steps = (K + 63) / 64;
+  const int norm = p.kind == PQ_NORM_RMS ? kNormRms : kNormAdaLn;
+  return launch_norm<kFmtNone, 64>(norm, x, rows, K, ld, nullptr, L, nullptr, norm_args(p, y, ldy), st);
+}
+
+int run_norm_quantize_packed(const pq_norm_params& p, pq_format fmt, int group, const void* x, int64_t rows,
+                             int64_t K, int64_t ld, const float* ts, void* operand, void* y, int64_t ldy,
+                             hipStream_t st) {
+  const OperandLayout L = operand_layout(fmt, group, rows, K);
+  const int norm = p.kind == PQ_NORM_RMS ? kNormRms : kNormAdaLn;
+  const NormArgs na = norm_args(p, y, ldy);
+  uint8_t* o = (uint8_t*)operand;
+  if (fmt == PQ_FMT_NVFP4) return launch_norm<kNvfp4, 16>(norm, x, rows, K, ld, ts, L, o, na, st);
+#define PQ_INT_CASE(F, FE)                                                      \
+  if (fmt == F) {                                                               \
+    switch (group) {                                                            \
+      case 32: return launch_norm<FE, 32>(norm, x, rows, K, ld, ts, L, o, na, st);   \
+      case 64: return launch_norm<FE, 64>(norm, x, rows, K, ld, ts, L, o, na, st);   \
+      case 128: return launch_norm<FE, 128>(norm, x, rows, K, ld, ts, L, o, na, st); \
+      case 256: return launch_norm<FE, 256>(norm, x, rows, K, ld, ts, L, o, na, st); \
+    }                                                                           \
+  }
+  PQ_INT_CASE(PQ_FMT_INT4, kInt4)
+  PQ_INT_CASE(PQ_FMT_INT3, kInt3)
+#undef PQ_INT_CASE
+  return fail(PQ_ERR_FORMAT, "unsupported (format, group) = (%d, %d)", (int)fmt, group);
+}
+
+}  // namespace pq

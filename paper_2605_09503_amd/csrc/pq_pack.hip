@@ -19,22 +19,6 @@
 
 namespace pq {
 
-struct OperandLayout {
-  size_t codes, scales, mul, total;     // byte offsets and total size
-  int64_t steps, units;
-};
-
-static OperandLayout operand_layout(pq_format fmt, int group, int64_t rows, int64_t K) {
-  OperandLayout L;
-  L.steps = (K + 63) / 64;
-  L.units = fmt == PQ_FMT_NVFP4 ? (K + 31) / 32 : K / group;
-  L.codes = 0;
-  L.scales = align_up((size_t)L.steps * rows * 32, 256);
-  L.mul = L.scales + align_up((size_t)L.units * rows * 2, 256);
-  L.total = L.mul + (fmt == PQ_FMT_NVFP4 ? 0 : align_up((size_t)rows * 4, 256));
-  return L;
-}
-
 size_t operand_bytes(pq_format fmt, int group, int64_t rows, int64_t K) {
   return operand_layout(fmt, group, rows, K).total;
 }
@@ -155,63 +139,24 @@ int run_pack_operand(pq_format fmt, int group, const uint8_t* codes, const void*
 // ------------------------------------------------------------------ fused quantizer -> panel
 // Dynamic activation quantization (paper Eq. 1-2, the contract of pq_quantize.hip) that stores
 // its result directly in the panel layout, so that the forward path needs no packing pass.
-// A workgroup of up to sixteen waves owns RPW rows (8); a wave works on 64 / RPW chunks (one
-// 64-wide K step) of all its rows at a time: lane (64 / RPW) r + c holds chunk c (8
+// A workgroup of up to sixteen waves owns RPW rows (8 or 4); a wave works on 64 / RPW chunks (one
+// or two 64-wide K steps) of all its rows at a time: lane (64 / RPW) r + c holds chunk c (8
 // channels) of row r, the wave loads whole 128-byte lines and stores the rows' codes of a step as
 // one contiguous run of 32 RPW bytes.  Groups wider than what a wave covers per trip take
 // several trips' chunks at once.  INT: the group maxima of the rows are kept in LDS until the row
 // maximum, and with it the per-row power of two, is known.
-//
-// The same kernel also runs the layer in front of the quantizer (paper App. C): RMSNorm, or
-// LayerNorm followed by a per-sample scale and shift, with the channel reorder absorbed into the
-// row load.  The RPW rows are first staged in LDS as they are in memory (contiguous, coalesced
-// loads; each wave takes whole rows and reduces their statistics), then every lane produces the
-// eight reordered, normalised bf16 values of its chunk by gathering x[pi(j)] -- and the scale
-// vectors at the same pi(j) -- from LDS, where the paper's kernel issues indexed global loads.
-// Those values go to a contiguous bf16 output, to the quantizer above, or to both.
 constexpr int kQuantPanelMaxWaves = 16;
-constexpr int kFmtNone = -1;                  // normalise and reorder only, no quantization
 
-enum Norm : int { kNormNone = 0, kNormRms = 1, kNormAdaLn = 2 };
-
-struct NormArgs {
-  const int32_t* perm;          // pi, or null for the identity
-  const uint16_t* gamma;        // RMSNorm: bf16 [K], or null for ones
-  const uint16_t* mod_scale;    // AdaLN: bf16 [n_mod][K] s (the factor is 1 + s), or null for zeros
-  const uint16_t* mod_shift;    // AdaLN: bf16 [n_mod][K] b, or null for zeros
-  int64_t rows_per_mod;         // token row m uses modulation row m / rows_per_mod
-  float eps;
-  uint16_t* y;                  // bf16 [rows][ldy] normalised, reordered output, or null
-  int64_t ldy;
-};
-
-__device__ __forceinline__ float wave_sum_f32(float v) {
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, kWave);
-  return v;
-}
-
-__device__ __forceinline__ uint32_t pack_bf16_rne(float lo, float hi) {
-  typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
-  typedef float f32x2_t __attribute__((ext_vector_type(2)));
-  return __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2_t){lo, hi}, bf16x2_t));
-}
-
-template <int FMT, int G, int RPW, int NORM>
+template <int FMT, int G, int RPW>
 __global__ __launch_bounds__(64 * kQuantPanelMaxWaves) void quantize_panel_kernel(
     const uint16_t* __restrict__ x, int64_t rows, int64_t K, int64_t ld, const float* __restrict__ tensor_scale,
     int64_t steps, int64_t units, uint8_t* __restrict__ p_codes, uint16_t* __restrict__ p_scales,
-    float* __restrict__ p_mul, uint32_t* __restrict__ c_codes, void* __restrict__ c_scales, NormArgs na) {
-  constexpr bool QUANT = FMT != kFmtNone;
-  constexpr bool IS_INT = FMT == kInt4 || FMT == kInt3;
+    float* __restrict__ p_mul, uint32_t* __restrict__ c_codes, void* __restrict__ c_scales) {
   constexpr int LPR = 64 / RPW;                             // lanes (= chunks per trip) of a row
   constexpr int SPG = G > LPR * 8 ? G / (LPR * 8) : 1;      // trips' worth of chunks a group spans
   constexpr int LPG = G / 8 < LPR ? G / 8 : LPR;            // lanes of a row that share a group
-  // dynamic LDS: [INT: RPW x units group maxima (fp32)] [NORM: RPW rows of K bf16, then one
-  // (RMSNorm) or two (AdaLN) vectors of K bf16]
-  extern __shared__ __align__(16) float h_lds[];
+  extern __shared__ float h_lds[];                          // INT: [RPW][units] group maxima
   __shared__ float wave_rowmax[kQuantPanelMaxWaves][RPW];
-  __shared__ float row_stat[RPW][2];                        // mean, 1 / sqrt(statistic + eps)
   // the wave index is uniform over a wave: held in a scalar register, so is every address part
   // that depends only on the group block
   const int tid = threadIdx.x, lane = tid & 63, n_waves = blockDim.x >> 6;
@@ -223,7 +168,6 @@ __global__ __launch_bounds__(64 * kQuantPanelMaxWaves) void quantize_panel_kerne
   const int n_chunks = (int)steps * 8;                      // chunks per row, a half step past K included
   const int k_chunks = (int)(K / 8);                        // chunks that exist
   const int n_units = (int)units;
-  const int Ki = (int)K;
   float T = 0.0f, encT = 0.0f;
   if constexpr (FMT == kNvfp4) {
     T = *tensor_scale;
@@ -231,136 +175,12 @@ __global__ __launch_bounds__(64 * kQuantPanelMaxWaves) void quantize_panel_kerne
   }
   float row_max = 0.0f;
   const int blocks = (n_chunks + SPG * LPR - 1) / (SPG * LPR);       // group blocks along K
-
-  // ---- normalisation front end: stage the rows and the vectors, reduce the statistics
-  uint16_t* rows_lds = reinterpret_cast<uint16_t*>(h_lds + (IS_INT ? RPW * n_units : 0));
-  uint16_t* vec_a = rows_lds + (size_t)RPW * Ki;            // gamma, or s of the first row's sample
-  uint16_t* vec_b = vec_a + Ki;                             // b of the first row's sample
-  int64_t mod0 = 0;
-  if constexpr (NORM != kNormNone) {
-    if constexpr (NORM == kNormAdaLn) mod0 = r0 / na.rows_per_mod;
-    for (int c = tid; c < k_chunks; c += blockDim.x) {
-      if constexpr (NORM == kNormRms) {
-        uint4 g = make_uint4(0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u);     // ones
-        if (na.gamma) g = *reinterpret_cast<const uint4*>(na.gamma + (size_t)c * 8);
-        *reinterpret_cast<uint4*>(vec_a + c * 8) = g;
-      } else {
-        uint4 sv = make_uint4(0u, 0u, 0u, 0u), bv = sv;
-        if (na.mod_scale) sv = *reinterpret_cast<const uint4*>(na.mod_scale + mod0 * K + (size_t)c * 8);
-        if (na.mod_shift) bv = *reinterpret_cast<const uint4*>(na.mod_shift + mod0 * K + (size_t)c * 8);
-        *reinterpret_cast<uint4*>(vec_a + c * 8) = sv;
-        *reinterpret_cast<uint4*>(vec_b + c * 8) = bv;
-      }
-    }
-    const float k_f = (float)Ki;
-    for (int rl = wave; rl < RPW; rl += n_waves) {          // whole rows per wave
-      const int64_t row = r0 + rl;
-      if (row >= rows) continue;                            // wave-uniform
-      const uint16_t* xr = x + row * ld;
-      uint16_t* dst = rows_lds + (size_t)rl * Ki;
-      float s1 = 0.0f, s2 = 0.0f;
-      for (int c0 = 0; c0 < k_chunks; c0 += 4 * 64) {       // four lines per lane in flight
-        uint4 p[4];
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-          const int c = c0 + t * 64 + lane;
-          p[t] = make_uint4(0u, 0u, 0u, 0u);
-          if (c < k_chunks) p[t] = *reinterpret_cast<const uint4*>(xr + (size_t)c * 8);
-        }
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-          const int c = c0 + t * 64 + lane;
-          if (c < k_chunks) *reinterpret_cast<uint4*>(dst + c * 8) = p[t];
-          const uint32_t d[4] = {p[t].x, p[t].y, p[t].z, p[t].w};
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const float lo = bf16_lo(d[e]), hi = bf16_hi(d[e]);
-            if constexpr (NORM == kNormAdaLn) s1 += lo + hi;
-            else s2 = fmaf(hi, hi, fmaf(lo, lo, s2));
-          }
-        }
-      }
-      float mean = 0.0f;
-      if constexpr (NORM == kNormAdaLn) {
-        // the variance from the deviations (the printed two-pass form), on the lane's own chunks
-        mean = wave_sum_f32(s1) / k_f;
-        for (int c = lane; c < k_chunks; c += 64) {
-          const uint4 p = *reinterpret_cast<const uint4*>(dst + c * 8);
-          const uint32_t d[4] = {p.x, p.y, p.z, p.w};
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const float lo = bf16_lo(d[e]) - mean, hi = bf16_hi(d[e]) - mean;
-            s2 = fmaf(hi, hi, fmaf(lo, lo, s2));
-          }
-        }
-      }
-      const float stat = wave_sum_f32(s2) / k_f + na.eps;
-      if (lane == 0) {
-        row_stat[rl][0] = mean;
-        row_stat[rl][1] = 1.0f / sqrtf(stat);
-      }
-    }
-    __syncthreads();
-  }
-  float mean = 0.0f, rstd = 0.0f;
-  bool own_mod = false;             // AdaLN: this row's sample is not the one staged in LDS
-  const uint16_t* g_scale = nullptr;
-  const uint16_t* g_shift = nullptr;
-  if constexpr (NORM != kNormNone) {
-    if (r_ok) {
-      mean = row_stat[r_local][0];
-      rstd = row_stat[r_local][1];
-    }
-    if constexpr (NORM == kNormAdaLn) {
-      const int64_t mod = r_ok ? r / na.rows_per_mod : mod0;
-      own_mod = mod != mod0;
-      g_scale = na.mod_scale ? na.mod_scale + mod * K : nullptr;
-      g_shift = na.mod_shift ? na.mod_shift + mod * K : nullptr;
-    }
-  }
-  const uint16_t* row_lds = rows_lds + (size_t)r_local * Ki;
-  // the eight reordered, normalised values of chunk `cidx`, as bf16 (zeros beyond the row)
-  auto fetch = [&](int cidx) -> uint4 {
-    if (!r_ok || cidx >= k_chunks) return make_uint4(0u, 0u, 0u, 0u);
-    int idx[8];
-    if (na.perm) {
-      const int4 i0 = *reinterpret_cast<const int4*>(na.perm + (size_t)cidx * 8);
-      const int4 i1 = *reinterpret_cast<const int4*>(na.perm + (size_t)cidx * 8 + 4);
-      idx[0] = i0.x; idx[1] = i0.y; idx[2] = i0.z; idx[3] = i0.w;
-      idx[4] = i1.x; idx[5] = i1.y; idx[6] = i1.z; idx[7] = i1.w;
-    } else {
-#pragma unroll
-      for (int e = 0; e < 8; ++e) idx[e] = cidx * 8 + e;
-    }
-    float yv[8];
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const float xv = bf16_to_f32(row_lds[idx[e]]);
-      if constexpr (NORM == kNormRms) {
-        yv[e] = (xv * rstd) * bf16_to_f32(vec_a[idx[e]]);
-      } else {
-        float sv, bv;
-        if (own_mod) {
-          sv = g_scale ? bf16_to_f32(g_scale[idx[e]]) : 0.0f;
-          bv = g_shift ? bf16_to_f32(g_shift[idx[e]]) : 0.0f;
-        } else {
-          sv = bf16_to_f32(vec_a[idx[e]]);
-          bv = bf16_to_f32(vec_b[idx[e]]);
-        }
-        yv[e] = (1.0f + sv) * ((xv - mean) * rstd) + bv;
-      }
-    }
-    return make_uint4(pack_bf16_rne(yv[0], yv[1]), pack_bf16_rne(yv[2], yv[3]), pack_bf16_rne(yv[4], yv[5]),
-                      pack_bf16_rne(yv[6], yv[7]));
-  };
-
   // per-lane parts of the addresses; chunk cb + c_local (cb a multiple of LPR, uniform) lives at
   //   x_lane + 8 cb,   pc_lane + 32 rows (cb / 8),   ps_lane + rows (cb / 4)   (NVFP4 unit)
   const uint16_t* x_lane = x + (r_ok ? r : 0) * ld + c_local * 8;
   uint8_t* pc_lane = p_codes + ((int64_t)(c_local >> 3) * rows + r) * 32 + (c_local & 7) * 4;
   uint16_t* ps_lane = p_scales + (int64_t)(c_local >> 2) * rows + r;
   uint32_t* cc_lane = c_codes ? c_codes + r * k_chunks + c_local : nullptr;
-  uint16_t* y_lane = na.y ? na.y + r * na.ldy + c_local * 8 : nullptr;
   // one group block: quantize, store codes and scales
   auto process = [&](int b, const uint4 (&raw)[SPG]) {
     float v[SPG][8];
@@ -391,8 +211,7 @@ __global__ __launch_bounds__(64 * kQuantPanelMaxWaves) void quantize_panel_kerne
       }
       sc_bits = sc.byte;
     } else {
-      constexpr int FI = IS_INT ? FMT : kInt4;
-      const IntScale sc = int_scale<FI>(a);
+      const IntScale sc = int_scale<FMT>(a);
 #pragma unroll
       for (int t = 0; t < SPG; ++t) codes[t] = int_codes8(v[t], sc.inv);
       sc_bits = as_u32(sc.s);
@@ -429,8 +248,8 @@ __global__ __launch_bounds__(64 * kQuantPanelMaxWaves) void quantize_panel_kerne
     }
   };
   // U group blocks per trip: their loads are all issued before the first is processed, so that a
-  // wave keeps several lines in flight (with a normalisation front end the values come from LDS)
-  constexpr int U = (SPG == 1 && NORM == kNormNone) ? 3 : 1;
+  // wave keeps several lines in flight
+  constexpr int U = SPG == 1 ? 3 : 1;
   for (int b0 = wave; b0 < blocks; b0 += U * n_waves) {
     uint4 raw[U][SPG];
 #pragma unroll
@@ -438,23 +257,16 @@ __global__ __launch_bounds__(64 * kQuantPanelMaxWaves) void quantize_panel_kerne
 #pragma unroll
       for (int t = 0; t < SPG; ++t) {
         const int cb = ((b0 + q * n_waves) * SPG + t) * LPR;          // uniform
-        if constexpr (NORM == kNormNone) {
-          raw[q][t] = make_uint4(0u, 0u, 0u, 0u);
-          if (r_ok && cb + c_local < k_chunks) raw[q][t] = *reinterpret_cast<const uint4*>(x_lane + (int64_t)cb * 8);
-        } else {
-          raw[q][t] = fetch(cb + c_local);
-          if (y_lane && r_ok && cb + c_local < k_chunks) *reinterpret_cast<uint4*>(y_lane + (int64_t)cb * 8) = raw[q][t];
-        }
+        raw[q][t] = make_uint4(0u, 0u, 0u, 0u);
+        if (r_ok && cb + c_local < k_chunks) raw[q][t] = *reinterpret_cast<const uint4*>(x_lane + (int64_t)cb * 8);
       }
-    if constexpr (QUANT) {
 #pragma unroll
-      for (int q = 0; q < U; ++q) {
-        const int b = b0 + q * n_waves;
-        if (b < blocks) process(b, raw[q]);              // wave-uniform
-      }
+    for (int q = 0; q < U; ++q) {
+      const int b = b0 + q * n_waves;
+      if (b < blocks) process(b, raw[q]);              // wave-uniform
     }
   }
-  if constexpr (IS_INT) {
+  if constexpr (FMT != kNvfp4) {
     constexpr float Q = qmax_of(FMT);
     row_max = group_max<LPR>(row_max);               // the lanes of a row
     if (c_local == 0) wave_rowmax[wave][r_local] = row_max;
@@ -480,21 +292,13 @@ __global__ __launch_bounds__(64 * kQuantPanelMaxWaves) void quantize_panel_kerne
   }
 }
 
-constexpr size_t kPanelLdsLimit = 160 * 1024 - 2048;      // dynamic LDS a workgroup may ask for
-
-// FMT: a quantized format or kFmtNone; L is the operand layout (steps and units are used even
-// without quantization: steps = ceil(K / 64))
-template <int FMT, int G, int RPW, int NORM>
+template <int FMT, int G, int RPW>
 static int launch_qpanel_r(const void* x, int64_t rows, int64_t K, int64_t ld, const float* ts,
                            const OperandLayout& L, uint8_t* operand, uint8_t* codes, void* scales,
-                           const NormArgs& na, hipStream_t st) {
+                           hipStream_t st) {
   const int64_t blocks = (rows + RPW - 1) / RPW;
-  size_t shmem = (FMT == kInt4 || FMT == kInt3) ? (size_t)RPW * L.units * sizeof(float) : 0;
-  if (NORM != kNormNone) shmem += (size_t)(RPW + (NORM == kNormRms ? 1 : 2)) * K * 2;
-  if (shmem > kPanelLdsLimit)
-    return fail(PQ_ERR_SHAPE, "K=%lld needs %zu bytes of LDS per workgroup, more than the %zu available",
-                (long long)K, shmem, kPanelLdsLimit);
-  auto kern = quantize_panel_kernel<FMT, G, RPW, NORM>;
+  const size_t shmem = FMT == kNvfp4 ? 0 : (size_t)RPW * L.units * sizeof(float);
+  auto kern = quantize_panel_kernel<FMT, G, RPW>;
   if (shmem > 48 * 1024) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
@@ -507,9 +311,8 @@ static int launch_qpanel_r(const void* x, int64_t rows, int64_t K, int64_t ld, c
   int n_waves = 1;
   while (n_waves < 8 && n_waves * 3 <= k_blocks) n_waves *= 2;   // >= 2-3 trips per wave
   hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(64 * n_waves), shmem, st, (const uint16_t*)x, rows, K, ld, ts,
-                     L.steps, L.units, operand ? operand + L.codes : nullptr,
-                     (uint16_t*)(operand ? operand + L.scales : nullptr),
-                     (float*)(operand ? operand + L.mul : nullptr), (uint32_t*)codes, scales, na);
+                     L.steps, L.units, operand + L.codes, (uint16_t*)(operand + L.scales),
+                     (float*)(operand + L.mul), (uint32_t*)codes, scales);
   return check_hip(hipGetLastError(), "quantize_panel_kernel");
 }
 
@@ -517,82 +320,33 @@ static int launch_qpanel_r(const void* x, int64_t rows, int64_t K, int64_t ld, c
 // units when rows / 8 is a little above a multiple of 256) measured the same within 2 % on
 // 4608 x 3072 with either four or eight waves, so the template is instantiated for 8 only.
 template <int FMT, int G>
-static int launch_qpanel(int norm, const void* x, int64_t rows, int64_t K, int64_t ld, const float* ts,
+static int launch_qpanel(const void* x, int64_t rows, int64_t K, int64_t ld, const float* ts,
                          const OperandLayout& L, uint8_t* operand, uint8_t* codes, void* scales,
-                         const NormArgs& na, hipStream_t st) {
-  switch (norm) {
-    case kNormNone: return launch_qpanel_r<FMT, G, 8, kNormNone>(x, rows, K, ld, ts, L, operand, codes, scales, na, st);
-    case kNormRms: return launch_qpanel_r<FMT, G, 8, kNormRms>(x, rows, K, ld, ts, L, operand, codes, scales, na, st);
-    case kNormAdaLn: return launch_qpanel_r<FMT, G, 8, kNormAdaLn>(x, rows, K, ld, ts, L, operand, codes, scales, na, st);
-  }
-  return fail(PQ_ERR_FORMAT, "unknown normalisation %d", norm);
+                         hipStream_t st) {
+  return launch_qpanel_r<FMT, G, 8>(x, rows, K, ld, ts, L, operand, codes, scales, st);
 }
 
-static int dispatch_qpanel(int norm, pq_format fmt, int group, const void* x, int64_t rows, int64_t K,
-                           int64_t ld, const float* ts, void* operand, uint8_t* codes, void* scales,
-                           const NormArgs& na, hipStream_t st) {
+int run_quantize_packed(pq_format fmt, int group, const void* x, int64_t rows, int64_t K, int64_t ld,
+                        const float* ts, void* operand, uint8_t* codes, void* scales, hipStream_t st) {
   if (rows > 0x7FFFFFF0) return fail(PQ_ERR_SHAPE, "too many rows");
   const OperandLayout L = operand_layout(fmt, group, rows, K);
   if (fmt != PQ_FMT_NVFP4 && (size_t)8 * L.units * 4 > 150 * 1024)
     return fail(PQ_ERR_SHAPE, "K=%lld has too many groups for the fused quantizer", (long long)K);
   uint8_t* o = (uint8_t*)operand;
-  if (fmt == PQ_FMT_NVFP4)
-    return launch_qpanel<kNvfp4, 16>(norm, x, rows, K, ld, ts, L, o, codes, scales, na, st);
-#define PQ_INT_CASE(F, FE)                                                                            \
-  if (fmt == F) {                                                                                     \
-    switch (group) {                                                                                  \
-      case 32: return launch_qpanel<FE, 32>(norm, x, rows, K, ld, ts, L, o, codes, scales, na, st);   \
-      case 64: return launch_qpanel<FE, 64>(norm, x, rows, K, ld, ts, L, o, codes, scales, na, st);   \
-      case 128: return launch_qpanel<FE, 128>(norm, x, rows, K, ld, ts, L, o, codes, scales, na, st); \
-      case 256: return launch_qpanel<FE, 256>(norm, x, rows, K, ld, ts, L, o, codes, scales, na, st); \
-    }                                                                                                 \
+  if (fmt == PQ_FMT_NVFP4) return launch_qpanel<kNvfp4, 16>(x, rows, K, ld, ts, L, o, codes, scales, st);
+#define PQ_INT_CASE(F, FE)                                                                  \
+  if (fmt == F) {                                                                           \
+    switch (group) {                                                                        \
+      case 32: return launch_qpanel<FE, 32>(x, rows, K, ld, ts, L, o, codes, scales, st);   \
+      case 64: return launch_qpanel<FE, 64>(x, rows, K, ld, ts, L, o, codes, scales, st);   \
+      case 128: return launch_qpanel<FE, 128>(x, rows, K, ld, ts, L, o, codes, scales, st); \
+      case 256: return launch_qpanel<FE, 256>(x, rows, K, ld, ts, L, o, codes, scales, st); \
+    }                                                                                       \
   }
   PQ_INT_CASE(PQ_FMT_INT4, kInt4)
   PQ_INT_CASE(PQ_FMT_INT3, kInt3)
 #undef PQ_INT_CASE
   return fail(PQ_ERR_FORMAT, "unsupported (format, group) = (%d, %d)", (int)fmt, group);
-}
-
-int run_quantize_packed(pq_format fmt, int group, const void* x, int64_t rows, int64_t K, int64_t ld,
-                        const float* ts, void* operand, uint8_t* codes, void* scales, hipStream_t st) {
-  NormArgs na = {};
-  return dispatch_qpanel(kNormNone, fmt, group, x, rows, K, ld, ts, operand, codes, scales, na, st);
-}
-
-static NormArgs norm_args(const pq_norm_params& p) {
-  NormArgs na;
-  na.perm = p.perm;
-  na.gamma = (const uint16_t*)p.gamma;
-  na.mod_scale = (const uint16_t*)p.mod_scale;
-  na.mod_shift = (const uint16_t*)p.mod_shift;
-  na.rows_per_mod = p.rows_per_mod > 0 ? p.rows_per_mod : INT64_MAX;
-  na.eps = p.eps;
-  na.y = nullptr;
-  na.ldy = 0;
-  return na;
-}
-
-int run_norm_reorder(const pq_norm_params& p, const void* x, int64_t rows, int64_t K, int64_t ld, void* y,
-                     int64_t ldy, hipStream_t st) {
-  NormArgs na = norm_args(p);
-  na.y = (uint16_t*)y;
-  na.ldy = ldy;
-  OperandLayout L = {};
-  L.steps = (K + 63) / 64;
-  const int norm = p.kind == PQ_NORM_RMS ? kNormRms : kNormAdaLn;
-  if (norm == kNormRms)
-    return launch_qpanel_r<kFmtNone, 64, 8, kNormRms>(x, rows, K, ld, nullptr, L, nullptr, nullptr, nullptr, na, st);
-  return launch_qpanel_r<kFmtNone, 64, 8, kNormAdaLn>(x, rows, K, ld, nullptr, L, nullptr, nullptr, nullptr, na, st);
-}
-
-int run_norm_quantize_packed(const pq_norm_params& p, pq_format fmt, int group, const void* x, int64_t rows,
-                             int64_t K, int64_t ld, const float* ts, void* operand, void* y, int64_t ldy,
-                             hipStream_t st) {
-  NormArgs na = norm_args(p);
-  na.y = (uint16_t*)y;
-  na.ldy = ldy;
-  const int norm = p.kind == PQ_NORM_RMS ? kNormRms : kNormAdaLn;
-  return dispatch_qpanel(norm, fmt, group, x, rows, K, ld, ts, operand, nullptr, nullptr, na, st);
 }
 
 static OperandView panel_view(pq_format fmt, int group, const void* operand, int64_t rows, int64_t K,
