@@ -223,7 +223,28 @@ def main():
     t_floor_q = time_calls(lambda i: pq.pq_probe_stream(pool[i % n_rot], in_bytes, qout, qout.numel() - 16),
                            max(it, n_rot))
     t_floor_m = time_calls(lambda i: pq.pq_probe_stream(pool[i % n_rot], in_bytes, qout, 0), max(it, n_rot))
-    del pool
+    # the layer in front of the quantizer (RMSNorm / modulated LayerNorm) with the reorder absorbed
+    # into its row load: as a bf16 tensor and feeding the quantizer directly, on the same rotating inputs
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(synth.SEED_BASE + 77)
+    n_mod = 4
+    gamma = (1.0 + 0.3 * torch.randn(K, device=dev, generator=gen)).to(torch.bfloat16)
+    mod_s = (0.5 * torch.randn((n_mod, K), device=dev, generator=gen)).to(torch.bfloat16)
+    mod_b = (0.5 * torch.randn((n_mod, K), device=dev, generator=gen)).to(torch.bfloat16)
+    per_mod = -(-M // n_mod)
+    y_norm = torch.empty((M, K), dtype=torch.bfloat16, device=dev)
+    norm_op = torch.empty_like(a_op)
+    ts_n = torch.full((1,), 0.004, dtype=torch.float32, device=dev)     # a static tensor scale for |y| < ~10
+    nit = max(it, n_rot)
+    t_rms = time_calls(lambda i: pq.pq_norm_reorder(pq.NORM_RMS, pool[i % n_rot], 1e-6, perm, gamma, y=y_norm), nit)
+    t_aln = time_calls(lambda i: pq.pq_norm_reorder(pq.NORM_ADALN, pool[i % n_rot], 1e-6, perm, None, mod_s, mod_b,
+                                                    per_mod, y=y_norm), nit)
+    t_rms_q = time_calls(lambda i: pq.pq_norm_quantize_act_packed(pq.NORM_RMS, fmt, g, pool[i % n_rot], 1e-6, ts_n,
+                                                                  perm, gamma, operand=norm_op), nit)
+    t_aln_q = time_calls(lambda i: pq.pq_norm_quantize_act_packed(pq.NORM_ADALN, fmt, g, pool[i % n_rot], 1e-6, ts_n,
+                                                                  perm, None, mod_s, mod_b, per_mod, operand=norm_op), nit)
+    t_floor_n = time_calls(lambda i: pq.pq_probe_stream(pool[i % n_rot], in_bytes, y_norm, in_bytes), nit)
+    del pool, y_norm, norm_op
     # the calibration set as one buffer, rotating over enough copies to stay out of the caches
     xcats = [torch.cat([b.reshape(-1) for b in xs]) for _ in range(n_sets)]
     t_floor_mall = time_calls(lambda i: pq.pq_probe_stream(xcats[i % n_sets], xcats[0].numel() * 2, qout, 0),
@@ -264,7 +285,17 @@ def main():
         "calibrate_moments_plus_select": {"us": t_cal * 1e6},
         "select_perm": {"us": t_sel * 1e6,
                         "element_evaluations_per_s": 7.0 * (nb * M + N) * K / t_sel},
+        # the step in front of the path (normalisation with the reorder absorbed), cold inputs
+        "norm_reorder_rms_cold": {"us": t_rms * 1e6, "gbs": 2 * mbytes / t_rms / 1e9,
+                                  "frac_hbm_peak": 2 * mbytes / t_rms / 1e9 / HBM_PEAK_GBS},
+        "norm_reorder_adaln_cold": {"us": t_aln * 1e6, "gbs": 2 * mbytes / t_aln / 1e9,
+                                    "frac_hbm_peak": 2 * mbytes / t_aln / 1e9 / HBM_PEAK_GBS},
+        "norm_quantize_act_rms_cold": {"us": t_rms_q * 1e6, "gbs": qbytes / t_rms_q / 1e9,
+                                       "frac_hbm_peak": qbytes / t_rms_q / 1e9 / HBM_PEAK_GBS},
+        "norm_quantize_act_adaln_cold": {"us": t_aln_q * 1e6, "gbs": qbytes / t_aln_q / 1e9,
+                                         "frac_hbm_peak": qbytes / t_aln_q / 1e9 / HBM_PEAK_GBS},
         # same-run references (not part of the path)
+        "reference_stream_norm_footprint_cold": {"us": t_floor_n * 1e6, "gbs": 2 * mbytes / t_floor_n / 1e9},
         "reference_stream_quantizer_footprint_cold": {"us": t_floor_q * 1e6, "gbs": qbytes / t_floor_q / 1e9},
         "reference_stream_read_one_batch_cold": {"us": t_floor_m * 1e6, "gbs": mbytes / t_floor_m / 1e9},
         "reference_stream_read_all_batches_cold": {"us": t_floor_mall * 1e6, "gbs": nb * mbytes / t_floor_mall / 1e9},
