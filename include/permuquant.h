@@ -266,6 +266,12 @@ int pq_qgemm_packed(pq_format fmt, int group, const void* a_operand, const float
 int pq_qgemm_packed_f32(pq_format fmt, int group, const void* a_operand, const float* a_tensor_scale,
                         const void* w_operand, const float* w_tensor_scale, int64_t M, int64_t N,
                         int64_t K, float* y_f32, int64_t ldy, void* stream);
+/* The linear layer with its bias, y = Q(XP) Q(P^T W) + b (paper Eq. 8 covers the product; the layers
+ * it replaces are x W^T + b): bias_bf16 is bf16 [N] device memory, 16-byte aligned, added in fp32
+ * to the scaled accumulator before the single rounding to bf16.  Otherwise as pq_qgemm_packed.     */
+int pq_qgemm_packed_bias(pq_format fmt, int group, const void* a_operand, const float* a_tensor_scale,
+                         const void* w_operand, const float* w_tensor_scale, int64_t M, int64_t N, int64_t K,
+                         const void* bias_bf16, void* y_bf16, int64_t ldy, void* stream);
 
 /*
  * The normalisation layer in front of a quantized linear layer, with the channel reorder

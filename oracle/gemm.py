@@ -35,6 +35,11 @@ def dequant_product_from_packed(fmt: int, g: int, a_codes, a_scales, a_tensor_sc
                            build(w_codes, w_scales, w_tensor_scale), rows)
 
 
+def add_bias(y, bias) -> np.ndarray:
+    """The linear layer's bias, one value per output column: y[m, n] + b[n] (fp64)."""
+    return np.asarray(y, dtype=np.float64) + np.asarray(bias, dtype=np.float64)[None, :]
+
+
 def plain_product(x, w) -> np.ndarray:
     """Unquantized Y = X W^T in fp64 (left side of Eq. 8)."""
     return np.asarray(x, dtype=np.float64) @ np.asarray(w, dtype=np.float64).T

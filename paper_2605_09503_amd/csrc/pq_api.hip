@@ -349,7 +349,7 @@ int pq_norm_quantize_act_packed(const pq_norm_params* p, pq_format fmt, int grou
 
 static int qgemm_packed_common(pq_format fmt, int group, const void* a_operand, const float* a_ts,
                                const void* w_operand, const float* w_ts, int64_t M, int64_t N, int64_t K,
-                               void* y, int64_t ldy, bool out_f32, void* stream) {
+                               const void* bias, void* y, int64_t ldy, bool out_f32, void* stream) {
   if (!a_operand || !w_operand || !y) return fail(PQ_ERR_NULL, "pq_qgemm_packed: a required pointer is NULL");
   int rc = check_format(fmt, group, K);
   if (rc) return rc;
@@ -363,9 +363,9 @@ static int qgemm_packed_common(pq_format fmt, int group, const void* a_operand, 
   if (ldy < N || ldy % 8)
     return fail(PQ_ERR_SHAPE, "pq_qgemm_packed: ldy=%lld must be >= N=%lld and a multiple of 8",
                 (long long)ldy, (long long)N);
-  if (!aligned16(a_operand) || !aligned16(w_operand) || !aligned16(y))
+  if (!aligned16(a_operand) || !aligned16(w_operand) || !aligned16(y) || !aligned16(bias))
     return fail(PQ_ERR_SHAPE, "pq_qgemm_packed: buffers must be 16-byte aligned");
-  return run_qgemm_packed(fmt, group, a_operand, a_ts, w_operand, w_ts, M, N, K, y, ldy, out_f32,
+  return run_qgemm_packed(fmt, group, a_operand, a_ts, w_operand, w_ts, M, N, K, bias, y, ldy, out_f32,
                           as_stream(stream));
 }
 
@@ -373,14 +373,22 @@ int pq_qgemm_packed(pq_format fmt, int group, const void* a_operand, const float
                     const void* w_operand, const float* w_tensor_scale, int64_t M, int64_t N, int64_t K,
                     void* y_bf16, int64_t ldy, void* stream) {
   return qgemm_packed_common(fmt, group, a_operand, a_tensor_scale, w_operand, w_tensor_scale, M, N, K,
-                             y_bf16, ldy, false, stream);
+                             nullptr, y_bf16, ldy, false, stream);
+}
+
+int pq_qgemm_packed_bias(pq_format fmt, int group, const void* a_operand, const float* a_tensor_scale,
+                         const void* w_operand, const float* w_tensor_scale, int64_t M, int64_t N, int64_t K,
+                         const void* bias_bf16, void* y_bf16, int64_t ldy, void* stream) {
+  if (!bias_bf16) return fail(PQ_ERR_NULL, "pq_qgemm_packed_bias: bias is NULL");
+  return qgemm_packed_common(fmt, group, a_operand, a_tensor_scale, w_operand, w_tensor_scale, M, N, K,
+                             bias_bf16, y_bf16, ldy, false, stream);
 }
 
 int pq_qgemm_packed_f32(pq_format fmt, int group, const void* a_operand, const float* a_tensor_scale,
                         const void* w_operand, const float* w_tensor_scale, int64_t M, int64_t N,
                         int64_t K, float* y_f32, int64_t ldy, void* stream) {
   return qgemm_packed_common(fmt, group, a_operand, a_tensor_scale, w_operand, w_tensor_scale, M, N, K,
-                             y_f32, ldy, true, stream);
+                             nullptr, y_f32, ldy, true, stream);
 }
 
 int pq_probe_stream(const void* src, size_t read_bytes, void* dst, size_t write_bytes, void* stream) {

@@ -80,8 +80,8 @@ int run_norm_quantize_packed(const pq_norm_params& p, pq_format fmt, int group, 
                              int64_t K, int64_t ld, const float* ts, void* operand, void* y, int64_t ldy,
                              hipStream_t st);
 int run_qgemm_packed(pq_format fmt, int group, const void* a_operand, const float* a_ts,
-                     const void* w_operand, const float* w_ts, int64_t M, int64_t N, int64_t K, void* y,
-                     int64_t ldy, bool out_f32, hipStream_t st);
+                     const void* w_operand, const float* w_ts, int64_t M, int64_t N, int64_t K,
+                     const void* bias, void* y, int64_t ldy, bool out_f32, hipStream_t st);
 
 int launch_probe_stream(const void* src, size_t read_bytes, void* dst, size_t write_bytes, hipStream_t st);
 int launch_probe_mfma(int iters, float* sink, double* flops_out, hipStream_t st);

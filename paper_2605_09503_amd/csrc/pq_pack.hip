@@ -371,11 +371,12 @@ static OperandView panel_view(pq_format fmt, int group, const void* operand, int
 }
 
 int run_qgemm_packed(pq_format fmt, int group, const void* a_operand, const float* a_ts,
-                     const void* w_operand, const float* w_ts, int64_t M, int64_t N, int64_t K, void* y,
-                     int64_t ldy, bool out_f32, hipStream_t st) {
+                     const void* w_operand, const float* w_ts, int64_t M, int64_t N, int64_t K,
+                     const void* bias, void* y, int64_t ldy, bool out_f32, hipStream_t st) {
   if (M * 32 > 0x7FFFFFFF || N * 32 > 0x7FFFFFFF) return fail(PQ_ERR_SHAPE, "too many rows for the panel layout");
   const OperandView A = panel_view(fmt, group, a_operand, M, K, a_ts);
-  const OperandView W = panel_view(fmt, group, w_operand, N, K, w_ts);
+  OperandView W = panel_view(fmt, group, w_operand, N, K, w_ts);
+  W.bias = (const uint16_t*)bias;
   return launch_qgemm_views(fmt, group, A, W, M, N, K, y, ldy, out_f32, st);
 }
 

@@ -253,8 +253,10 @@ __global__ __launch_bounds__(WGM* WGN * 64) void qgemm_kernel(OperandView A, Ope
   // lane and contiguous along n; the fp32 variant (a checking aid) stores directly.
   constexpr int C_ROW_BYTES = BN * 2 + 16;
   static_assert(BM * C_ROW_BYTES <= 2 * STAGE_BYTES, "output tile fits in the operand stages");
-  // The column factors do not depend on the row block: loaded once (16 per MFMA tile column).
-  float wm[TN][16];
+  // The column factors (and the optional bias of the linear layer, y = x W^T + b) do not depend on
+  // the row block: loaded once (16 per MFMA tile column).
+  const uint16_t* __restrict__ bias = W.bias;               // uniform
+  float wm[TN][16], wb[TN][16];
 #pragma unroll
   for (int i = 0; i < TN; ++i)
 #pragma unroll
@@ -263,6 +265,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void qgemm_kernel(OperandView A, Ope
       for (int e = 0; e < 4; ++e) {
         const int n = n0 + wave_n * WTN + i * 32 + q * 8 + frag_half * 4 + e;
         wm[i][q * 4 + e] = w_mul[(int64_t)(min(n, N - 1) * w_mul_stride)];
+        wb[i][q * 4 + e] = bias ? bf16_to_f32(bias[min(n, N - 1)]) : 0.0f;
       }
 #pragma unroll
   for (int j = 0; j < TM; ++j) {
@@ -278,6 +281,10 @@ __global__ __launch_bounds__(WGM* WGN * 64) void qgemm_kernel(OperandView A, Ope
         float v[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) v[e] = acc[i][j][q * 4 + e] * (am * wm[i][q * 4 + e]);
+        if (bias) {                     // without a bias the product is stored as it is (a -0 stays -0)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] += wb[i][q * 4 + e];
+        }
         if constexpr (OUT_F32) {
           if (m < M && n < N) {
             float* yo = reinterpret_cast<float*>(y) + (int64_t)m * ldy + n;

@@ -35,6 +35,8 @@ struct Slice {
 //   panel (K-step-major, see pq_pack.hip):  code_row = 32, code_step = 32 * rows;
 //                                           sc_row = 2, sc_step = 2 * rows
 // mul: per-row epilogue factor (stride 1) or a single factor (stride 0).
+// bias: bf16 value per row of this operand added to the product in the epilogue (used for the
+// weight operand, whose rows are the output columns), or null.
 struct OperandView {
   const uint8_t* codes;
   int64_t code_row;
@@ -44,6 +46,7 @@ struct OperandView {
   int sc_step;
   const float* mul;
   int mul_stride;
+  const uint16_t* bias = nullptr;
 };
 
 // Branch-free load of one slice.  `codes_row` / `sc_row` point at a valid row (the caller

@@ -84,6 +84,7 @@ def load():
     packed_args = [i32, i32, vp, vp, vp, vp, i64, i64, i64, vp, i64, vp]
     lib.pq_qgemm_packed.argtypes = packed_args
     lib.pq_qgemm_packed_f32.argtypes = packed_args
+    lib.pq_qgemm_packed_bias.argtypes = [i32, i32, vp, vp, vp, vp, i64, i64, i64, vp, vp, i64, vp]
     lib.pq_norm_reorder.argtypes = [C.POINTER(NormParams), vp, i64, i64, i64, vp, i64, vp]
     lib.pq_norm_quantize_act_packed.argtypes = [C.POINTER(NormParams), i32, i32, vp, i64, i64, i64, vp, vp, sz,
                                                 vp, i64, vp]
@@ -338,6 +339,14 @@ def pq_qgemm_packed(fmt: int, group: int, a_operand, a_tensor_scale, w_operand, 
                     y: torch.Tensor, M: int, N: int, K: int, ldy=None) -> None:
     _gemm_packed(load().pq_qgemm_packed, fmt, group, a_operand, a_tensor_scale, w_operand, w_tensor_scale,
                  y, M, N, K, ldy)
+
+
+def pq_qgemm_packed_bias(fmt: int, group: int, a_operand, a_tensor_scale, w_operand, w_tensor_scale,
+                         bias: torch.Tensor, y: torch.Tensor, M: int, N: int, K: int, ldy=None) -> None:
+    """The packed product plus the layer's bias (bf16 [N]), added before the rounding to bf16."""
+    _check(load().pq_qgemm_packed_bias(fmt, group, _ptr(a_operand), _ptr(a_tensor_scale), _ptr(w_operand),
+                                       _ptr(w_tensor_scale), M, N, K, _ptr(bias), _ptr(y),
+                                       y.stride(0) if ldy is None else ldy, _stream()))
 
 
 def pq_qgemm_packed_f32(fmt: int, group: int, a_operand, a_tensor_scale, w_operand, w_tensor_scale,

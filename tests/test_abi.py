@@ -164,6 +164,9 @@ def test_packed_operand_validation(lib):
     assert g(1, 64, FAKE, None, FAKE, None, 8, 8, 64, FAKE, 4, None) == PQ_ERR_SHAPE   # ldy < N
     assert g(1, 64, FAKE, None, FAKE, None, 8, 8, 48, FAKE, 8, None) == PQ_ERR_SHAPE   # K % group
     assert g(2, 16, FAKE, None, FAKE, None, 8, 8, 64, FAKE, 8, None) == PQ_ERR_FORMAT
+    gb = lib.pq_qgemm_packed_bias
+    assert gb(1, 64, FAKE, None, FAKE, None, 8, 8, 64, None, FAKE, 8, None) == PQ_ERR_NULL          # no bias
+    assert gb(1, 64, FAKE, None, FAKE, None, 8, 8, 64, C.c_void_p(0x1002), FAKE, 8, None) == PQ_ERR_SHAPE
     assert lib.pq_probe_mfma(0, FAKE, None, None) == PQ_ERR_SHAPE
     assert lib.pq_probe_stream(None, 16, FAKE, 0, None) == PQ_ERR_NULL
     assert lib.pq_probe_stream(FAKE, 24, FAKE, 0, None) == PQ_ERR_SHAPE

@@ -515,6 +515,48 @@ def test_pack_operand_then_gemm_matches_oracle():
     T.gemm_f32_check(y32.cpu().numpy(), y_ref, T.abs_product(fmt, g, qa, qw), "packed int4 g64")
 
 
+@pytest.mark.parametrize("fmt,g", [(pq.FMT_NVFP4, 16), (pq.FMT_INT4, 64), (pq.FMT_INT3, 32)])
+@pytest.mark.parametrize("M,N,K", [(300, 264, 1088), (37, 520, 96)])
+def test_qgemm_packed_bias(fmt, g, M, N, K):
+    """y = Q(X) Q(W)^T + b: the bias is added in fp32 before the one rounding to bf16.  Against the
+    fp64 product plus bias: half a bf16 step (at most 2^-8 relative) for the rounding, plus the accumulation
+    bound of the product; and a zero bias reproduces the plain product except for the sign of zeros."""
+    if K % g:
+        pytest.skip("K is not a multiple of this group size")
+    _say("packed gemm with bias fmt=%d g=%d %dx%dx%d" % (fmt, g, M, N, K))
+    rng = np.random.default_rng(7700 + M + K + g)
+    xb = _rand_bits(rng, M, K)
+    wb = synth.f64_to_bf16_bits(0.02 * rng.standard_normal((N, K)))
+    bias_bits = synth.f64_to_bf16_bits(0.5 * rng.standard_normal(N))
+    x64, w64 = OF.bf16_bits_to_f64(xb), OF.bf16_bits_to_f64(wb)
+    ta = OQ.nvfp4_tensor_scale(OC.absmax(x64)) if fmt == pq.FMT_NVFP4 else None
+    tw = OQ.nvfp4_tensor_scale(OC.absmax(w64)) if fmt == pq.FMT_NVFP4 else None
+    qa, qw = OQ.quantize(fmt, g, x64, ta), OQ.quantize(fmt, g, w64, tw)
+    bias64 = OF.bf16_bits_to_f64(bias_bits)
+    y_ref = OG.add_bias(OG.dequant_product(fmt, g, qa, qw), bias64)
+    Ta = torch.full((1,), float(ta) if ta is not None else 1.0, dtype=torch.float32, device=DEV)
+    Tw = torch.ones(1, dtype=torch.float32, device=DEV)
+    w_codes, w_scales = pq.alloc_quantized(fmt, g, N, K, DEV)
+    pq.pq_quantize_weights(fmt, g, _to_dev(wb), None, w_codes, w_scales, Tw)
+    a_op = pq.pq_quantize_act_packed(fmt, g, _to_dev(xb), Ta)
+    w_op = pq.pq_pack_operand(fmt, g, w_codes, w_scales)
+    ldy = (N + 7) // 8 * 8
+    y = torch.full((M, ldy), 3.0, dtype=torch.bfloat16, device=DEV)
+    pq.pq_qgemm_packed_bias(fmt, g, a_op, Ta, w_op, Tw, _to_dev(bias_bits), y, M, N, K, ldy=ldy)
+    y0 = torch.full((M, ldy), 3.0, dtype=torch.bfloat16, device=DEV)
+    pq.pq_qgemm_packed_bias(fmt, g, a_op, Ta, w_op, Tw, torch.zeros(N, dtype=torch.bfloat16, device=DEV), y0, M, N, K, ldy=ldy)
+    y_plain = torch.full((M, ldy), 3.0, dtype=torch.bfloat16, device=DEV)
+    pq.pq_qgemm_packed(fmt, g, a_op, Ta, w_op, Tw, y_plain, M, N, K, ldy=ldy)
+    torch.cuda.synchronize()
+    got = y[:, :N].float().cpu().numpy().astype(np.float64)
+    mag = T.abs_product(fmt, g, qa, qw) + np.abs(bias64)[None, :]
+    tol = 2.0 ** -8 * np.abs(y_ref) + T.GEMM_ACC_UNITS * 2.0 ** -24 * mag
+    err = np.abs(got - y_ref)
+    assert np.all(err <= tol), "worst %g of tolerance" % float((err / tol).max())
+    assert torch.all(y[:, N:] == 3.0)
+    assert torch.equal(y0.float(), y_plain.float())          # -0 + 0 = +0: compare values, not bits
+
+
 @pytest.mark.parametrize("fmt,g", FMTS)
 @pytest.mark.parametrize("M,K,pad", [(300, 1056, 0), (7, 96, 0), (64, 2048, 16), (1, 256, 0), (515, 3072, 0)])
 def test_quantize_act_packed_equals_quantize_then_pack(fmt, g, M, K, pad):

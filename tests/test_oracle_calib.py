@@ -312,3 +312,9 @@ def test_bf16_round_of_product():
     # 1.00390625 = 1 + 2^-8 is a tie between 1.0 and 1.0078125 -> even mantissa (1.0)
     np.testing.assert_array_equal(back[:3], [1.0, 1.0, 1.015625])
     assert abs(back[3] + 3.0e-5) < 3.0e-5 * 2.0 ** -8
+
+
+def test_add_bias_is_a_per_column_offset():
+    y = np.arange(6.0).reshape(2, 3)
+    out = G.add_bias(y, [10.0, 20.0, 30.0])
+    assert out.tolist() == [[10.0, 21.0, 32.0], [13.0, 24.0, 35.0]]
