@@ -274,6 +274,18 @@ int pq_qgemm_packed_bias(pq_format fmt, int group, const void* a_operand, const 
                          const void* bias_bf16, void* y_bf16, int64_t ldy, void* stream);
 
 /*
+ * Dynamic per-tensor scale of the NVFP4 activation format (paper App. A.1: E4M3 block scales under an
+ * fp32 tensor scale; the paper does not say whether the activation tensor scale is static).  The
+ * default in this library is a static scale from the calibration absmax (pq_tensor_scale), which
+ * keeps activation quantization a single pass.  This call is the first pass of the two-pass
+ * alternative: T = max|x| / (448 * 6) of the live tensor x (bf16 [M, ld], first K columns), written to
+ * tensor_scale_out (device float) on `stream`; pass it to pq_quantize_act(_packed) and to the product
+ * that follows on the same stream -- nothing returns to the host.  K % 8 == 0, ld >= K, ld % 8 == 0.
+ */
+int pq_dynamic_tensor_scale(const void* x_bf16, int64_t M, int64_t K, int64_t ld, float* tensor_scale_out,
+                            void* stream);
+
+/*
  * The normalisation layer in front of a quantized linear layer, with the channel reorder
  * absorbed into its row load (paper App. C: RMSNorm and LayerNorm commute with a channel
  * permutation if the channel-wise vectors are permuted with it, so the layer can emit

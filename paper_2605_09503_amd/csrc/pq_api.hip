@@ -303,6 +303,19 @@ int pq_quantize_act_packed(pq_format fmt, int group, const void* x, int64_t M, i
   return run_quantize_packed(fmt, group, x, M, K, ld, tensor_scale, operand, codes, scales, as_stream(stream));
 }
 
+int pq_dynamic_tensor_scale(const void* x, int64_t M, int64_t K, int64_t ld, float* tensor_scale_out,
+                            void* stream) {
+  if (!x || !tensor_scale_out) return fail(PQ_ERR_NULL, "pq_dynamic_tensor_scale: a required pointer is NULL");
+  if (M <= 0 || K <= 0) return fail(PQ_ERR_SHAPE, "pq_dynamic_tensor_scale: M=%lld K=%lld must be positive",
+                                    (long long)M, (long long)K);
+  if (M > (1 << 24) || K > (1 << 24)) return fail(PQ_ERR_SHAPE, "pq_dynamic_tensor_scale: a dimension exceeds 2^24");
+  if (K % 8 || ld < K || ld % 8)
+    return fail(PQ_ERR_SHAPE, "pq_dynamic_tensor_scale: K=%lld must be a multiple of 8, ld=%lld >= K and a multiple of 8",
+                (long long)K, (long long)ld);
+  if (!aligned16(x)) return fail(PQ_ERR_SHAPE, "pq_dynamic_tensor_scale: x must be 16-byte aligned");
+  return launch_dynamic_tensor_scale(x, M, K, ld, tensor_scale_out, as_stream(stream));
+}
+
 static int check_norm(const char* who, const pq_norm_params* p, const void* x, int64_t M, int64_t K, int64_t ld,
                       const void* y, int64_t ldy, bool y_required) {
   if (!p || !x || (y_required && !y)) return fail(PQ_ERR_NULL, "%s: a required pointer is NULL", who);

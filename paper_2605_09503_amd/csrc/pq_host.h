@@ -32,6 +32,7 @@ int launch_moments(const void* const* xs, int n_batches, int64_t rows, int64_t K
 
 int launch_absmax_to_tensor_scale(const void* x, int64_t n_elems, float* tensor_scale_out,
                                   hipStream_t st);
+int launch_dynamic_tensor_scale(const void* x, int64_t rows, int64_t K, int64_t ld, float* out, hipStream_t st);
 int launch_fill_float(float* p, float v, hipStream_t st);
 int launch_tensor_scale(const float* absmax, float* out, hipStream_t st);
 int launch_quantize_rows(pq_format fmt, int group, const void* x, int64_t rows, int64_t K, int64_t ld,

@@ -203,6 +203,43 @@ int launch_fill_float(float* p, float v, hipStream_t st) {
   return check_hip(hipGetLastError(), "fill_float_kernel");
 }
 
+// absmax over the first K columns of every row of a tensor with row stride ld (the columns beyond
+// K are not read)
+__global__ __launch_bounds__(256) void absmax_rows_kernel(const uint16_t* __restrict__ x, int64_t rows, int k_chunks,
+                                                          int64_t ld, uint32_t* __restrict__ out_bits) {
+  uint32_t m = 0;
+  const int64_t n_chunks = rows * k_chunks;
+  for (int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x; c < n_chunks; c += (int64_t)gridDim.x * 256) {
+    const int64_t r = c / k_chunks;
+    const int col = (int)(c - r * k_chunks);
+    const uint4 p = *reinterpret_cast<const uint4*>(x + r * ld + (int64_t)col * 8);
+    const uint32_t w[4] = {p.x, p.y, p.z, p.w};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) m = max(m, max(w[j] & 0x7FFFu, (w[j] >> 16) & 0x7FFFu));
+  }
+  const float fm = wave_max(as_f32(m << 16));
+  if ((threadIdx.x & 63) == 0 && fm > 0.0f) atomicMax(out_bits, as_u32(fm));
+}
+
+// The per-tensor scale of a live activation tensor, T = max|x| / (448 * 6), left in device memory
+// for the quantizer and the GEMM that follow on the same stream (the first of the two passes of a
+// dynamic NVFP4 tensor scale).
+int launch_dynamic_tensor_scale(const void* x, int64_t rows, int64_t K, int64_t ld, float* out, hipStream_t st) {
+  const int64_t n_chunks = rows * (K / 8);
+  int64_t blocks = (n_chunks + 255) / 256;
+  if (blocks > 2048) blocks = 2048;
+  hipLaunchKernelGGL(zero_word_kernel, dim3(1), dim3(1), 0, st, (uint32_t*)out);
+  if (ld == K) {
+    hipLaunchKernelGGL(absmax_kernel, dim3((unsigned)blocks), dim3(256), 0, st, (const uint4*)x, n_chunks,
+                       (uint32_t*)out);
+  } else {
+    hipLaunchKernelGGL(absmax_rows_kernel, dim3((unsigned)blocks), dim3(256), 0, st, (const uint16_t*)x, rows,
+                       (int)(K / 8), ld, (uint32_t*)out);
+  }
+  hipLaunchKernelGGL(tensor_scale_kernel, dim3(1), dim3(1), 0, st, out);
+  return check_hip(hipGetLastError(), "absmax/tensor_scale kernels");
+}
+
 int launch_absmax_to_tensor_scale(const void* x, int64_t n_elems, float* out, hipStream_t st) {
   int64_t n_chunks = n_elems / 8;          // K is a multiple of 16, so no tail
   int64_t blocks = (n_chunks + 255) / 256;

@@ -85,6 +85,7 @@ def load():
     lib.pq_qgemm_packed.argtypes = packed_args
     lib.pq_qgemm_packed_f32.argtypes = packed_args
     lib.pq_qgemm_packed_bias.argtypes = [i32, i32, vp, vp, vp, vp, i64, i64, i64, vp, vp, i64, vp]
+    lib.pq_dynamic_tensor_scale.argtypes = [vp, i64, i64, i64, vp, vp]
     lib.pq_norm_reorder.argtypes = [C.POINTER(NormParams), vp, i64, i64, i64, vp, i64, vp]
     lib.pq_norm_quantize_act_packed.argtypes = [C.POINTER(NormParams), i32, i32, vp, i64, i64, i64, vp, vp, sz,
                                                 vp, i64, vp]
@@ -291,6 +292,16 @@ def pq_quantize_act_packed(fmt: int, group: int, x: torch.Tensor, tensor_scale: 
     _check(load().pq_quantize_act_packed(fmt, group, _ptr(x), M, K, x.stride(0), _ptr(tensor_scale),
                                          _ptr(operand), operand.numel(), _ptr(codes), _ptr(scales), _stream()))
     return operand
+
+
+def pq_dynamic_tensor_scale(x: torch.Tensor, tensor_scale_out: Optional[torch.Tensor] = None,
+                            K: Optional[int] = None) -> torch.Tensor:
+    """T = max|x| / 2688 of the live tensor, left on the device (first pass of a dynamic NVFP4 scale)."""
+    if tensor_scale_out is None:
+        tensor_scale_out = torch.empty(1, dtype=torch.float32, device=x.device)
+    _check(load().pq_dynamic_tensor_scale(_ptr(x), x.shape[0], x.shape[1] if K is None else K, x.stride(0),
+                                          _ptr(tensor_scale_out), _stream()))
+    return tensor_scale_out
 
 
 def _norm_params(kind, perm, gamma, mod_scale, mod_shift, rows_per_mod, eps) -> "NormParams":

@@ -187,6 +187,9 @@ def test_norm_validation(lib):
     assert f(C.byref(ok), FAKE, 8, 64, 64, FAKE, 60, None) == PQ_ERR_SHAPE          # ldy
     assert f(C.byref(params(eps=-1.0)), FAKE, 8, 64, 64, FAKE, 64, None) == PQ_ERR_SHAPE
     assert f(C.byref(params(perm=0x1004)), FAKE, 8, 64, 64, FAKE, 64, None) == PQ_ERR_SHAPE   # alignment
+    d = lib.pq_dynamic_tensor_scale
+    assert d(None, 8, 64, 64, FAKE, None) == PQ_ERR_NULL and d(FAKE, 8, 64, 64, None, None) == PQ_ERR_NULL
+    assert d(FAKE, 8, 60, 64, FAKE, None) == PQ_ERR_SHAPE and d(FAKE, 8, 64, 56, FAKE, None) == PQ_ERR_SHAPE
     g = lib.pq_norm_quantize_act_packed
     assert g(C.byref(ok), 1, 64, FAKE, 8, 64, 64, None, None, 1 << 20, None, 0, None) == PQ_ERR_NULL
     assert g(C.byref(ok), 0, 16, FAKE, 8, 64, 64, None, FAKE, 1 << 20, None, 0, None) == PQ_ERR_NULL   # NVFP4 scale

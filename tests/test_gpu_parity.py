@@ -515,6 +515,32 @@ def test_pack_operand_then_gemm_matches_oracle():
     T.gemm_f32_check(y32.cpu().numpy(), y_ref, T.abs_product(fmt, g, qa, qw), "packed int4 g64")
 
 
+@pytest.mark.parametrize("M,K,pad", [(300, 1056, 0), (37, 96, 40), (1, 16, 0), (2100, 3072, 8)])
+def test_dynamic_tensor_scale_two_pass(M, K, pad):
+    """The two-pass NVFP4 activation path: T from the live tensor on the device, then the quantizer.
+    T and the codes equal the oracle's for T = absmax / 2688; columns beyond K (here far larger than
+    the data) are not read."""
+    _say("dynamic tensor scale M=%d K=%d ld=%d" % (M, K, K + pad))
+    rng = np.random.default_rng(7800 + M + K)
+    bits = _rand_bits(rng, M, K + pad)
+    if pad:
+        bits[:, K:] = synth.f64_to_bf16_bits(np.full((M, pad), 3.0e4))
+    x = _to_dev(bits)[:, :K]
+    T_dev = torch.full((1,), 123.0, dtype=torch.float32, device=DEV)
+    pq.pq_dynamic_tensor_scale(x, T_dev, K=K)
+    codes, scales = pq.alloc_quantized(pq.FMT_NVFP4, 16, M, K, DEV)
+    pq.pq_quantize_act(pq.FMT_NVFP4, 16, x, None, T_dev, codes, scales)
+    torch.cuda.synchronize()
+    x64 = OF.bf16_bits_to_f64(bits[:, :K])
+    t_ref = OQ.nvfp4_tensor_scale(OC.absmax(x64))
+    assert np.float32(T_dev.item()) == t_ref
+    ref_codes, ref_scales, _ = T.oracle_quantize_bits(pq.FMT_NVFP4, 16, bits[:, :K], None, t_ref)
+    assert np.array_equal(codes.cpu().numpy(), ref_codes)
+    assert np.array_equal(scales.cpu().numpy(), ref_scales)
+    # with the tensor's own absmax no block scale saturates: the largest E4M3 byte is 448's
+    assert scales.max().item() == 0x7E
+
+
 @pytest.mark.parametrize("fmt,g", [(pq.FMT_NVFP4, 16), (pq.FMT_INT4, 64), (pq.FMT_INT3, 32)])
 @pytest.mark.parametrize("M,N,K", [(300, 264, 1088), (37, 520, 96)])
 def test_qgemm_packed_bias(fmt, g, M, N, K):
