@@ -111,12 +111,35 @@ def calibration_error(fmt: int, g: int, x_batches: Sequence[np.ndarray], w, perm
     return ex / sum_x2 + ew / sum_w2
 
 
+def output_error(fmt: int, g: int, x_batches: Sequence[np.ndarray], w, perm,
+                 act_tensor_scale=None, w_tensor_scale=None) -> float:
+    """The other reading of "quantization error on the calibration data" (Sec. 3.3): the relative
+    error of the layer's output,
+        E_out(pi) = sum_b ||X_b W^T - Q(X_b P) Q(P^T W)^T||^2 / sum_b ||X_b W^T||^2      (Eq. 8),
+    both operands quantized in the order pi; the unquantized product does not depend on pi."""
+    w = np.asarray(w, dtype=np.float64)
+    wp = w if perm is None else w[:, np.asarray(perm)]
+    w_hat = Qz.dequantize(fmt, g, Qz.quantize(fmt, g, wp, w_tensor_scale))
+    num = den = 0.0
+    for xb in x_batches:
+        xb = np.asarray(xb, dtype=np.float64)
+        xp = xb if perm is None else xb[:, np.asarray(perm)]
+        x_hat = Qz.dequantize(fmt, g, Qz.quantize(fmt, g, xp, act_tensor_scale))
+        y = xb @ w.T
+        d = y - x_hat @ w_hat.T
+        num += float(np.sum(d * d))
+        den += float(np.sum(y * y))
+    return num / den
+
+
 def select_permutation(fmt: int, g: int, x_batches: Sequence[np.ndarray], w,
                        alphas: Sequence[float] = DEFAULT_ALPHAS, tau: float = 0.0,
-                       act_tensor_scale=None) -> SelectResult:
+                       act_tensor_scale=None, metric: str = "tensor") -> SelectResult:
     """Joint second-moment reordering with calibration-based acceptance (Sec. 3.3).
 
     x_batches: calibration activations, each [M, K] fp64 (bf16 values); w: [N, K].
+    metric: "tensor" -- E of the module docstring (the two tensors' relative errors);
+            "output" -- output_error above (the layer-output reading).
     """
     w = np.asarray(w, dtype=np.float64)
     K = w.shape[1]
@@ -132,16 +155,24 @@ def select_permutation(fmt: int, g: int, x_batches: Sequence[np.ndarray], w,
     sum_x2 = float(np.sum(sa))
     sum_w2 = float(np.sum(sw))
 
+    if metric == "tensor":
+        def err(p):
+            return calibration_error(fmt, g, x_batches, w, p, act_tensor_scale, w_ts, sum_x2, sum_w2)
+    elif metric == "output":
+        def err(p):
+            return output_error(fmt, g, x_batches, w, p, act_tensor_scale, w_ts)
+    else:
+        raise ValueError("metric must be 'tensor' or 'output'")
+
     ident = np.arange(K, dtype=np.int32)
-    e_orig = calibration_error(fmt, g, x_batches, w, None, act_tensor_scale, w_ts, sum_x2, sum_w2)
+    e_orig = err(None)
     cands, errs, gaps = [], [], []
     for a in alphas:
         key = joint_key(sa, sw, float(a))
         p = sort_descending(key)
         cands.append(p)
         gaps.append(min_relative_key_gap(key, p))
-        errs.append(calibration_error(fmt, g, x_batches, w, p, act_tensor_scale, w_ts,
-                                      sum_x2, sum_w2))
+        errs.append(err(p))
     j = int(np.argmin(np.asarray(errs)))          # first minimum = smallest alpha
     best = cands[j]
     accepted = (not np.array_equal(best, ident)) and e_orig > 0.0 and \

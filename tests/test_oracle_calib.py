@@ -318,3 +318,59 @@ def test_add_bias_is_a_per_column_offset():
     y = np.arange(6.0).reshape(2, 3)
     out = G.add_bias(y, [10.0, 20.0, 30.0])
     assert out.tolist() == [[10.0, 21.0, 32.0], [13.0, 24.0, 35.0]]
+
+
+def test_output_error_brute_force_and_invariances():
+    """E_out from explicit loops on a tiny layer; zero when nothing is lost; the unquantized product
+    does not depend on the order, so a permutation inside one group changes nothing."""
+    rng = np.random.default_rng(11)
+    K, g, M, N = 8, 4, 3, 2
+    x = _bf16(rng.normal(size=(M, K)) * np.array([9, 1, 1, 1, 9, 1, 1, 1.0]))
+    w = _bf16(rng.normal(size=(N, K)))
+    perm = np.array([0, 4, 1, 2, 3, 5, 6, 7])
+    xq = Qz.dequantize(1, g, Qz.quantize(1, g, x[:, perm]))
+    wq = Qz.dequantize(1, g, Qz.quantize(1, g, w[:, perm]))
+    num = den = 0.0
+    for m in range(M):
+        for n in range(N):
+            y = sum(x[m, k] * w[n, k] for k in range(K))
+            yq = sum(xq[m, k] * wq[n, k] for k in range(K))
+            num += (y - yq) ** 2
+            den += y ** 2
+    got = C.output_error(1, g, [x], w, perm)
+    assert abs(got - num / den) <= 1e-13 * (num / den)
+    # two batches: numerators and denominators add before the division
+    x2 = _bf16(rng.normal(size=(M, K)))
+    both = C.output_error(1, g, [x, x2], w, perm)
+    a = C.output_error(1, g, [x], w, perm)
+    b = C.output_error(1, g, [x2], w, perm)
+    da = float(np.sum((x @ w.T) ** 2))
+    db = float(np.sum((x2 @ w.T) ** 2))
+    assert abs(both - (a * da + b * db) / (da + db)) <= 1e-13
+    # codes that are exact (integers up to 7 with the group maximum 7) lose nothing
+    xi = np.array([[7.0, -3, 2, 0, 7, 1, -1, 5]])
+    wi = np.array([[7.0, 7, -7, 1, 7, 0, 2, -4]])
+    assert C.output_error(1, g, [xi], wi, None) == 0.0
+    # reordering inside a group leaves every group's content, hence the error, unchanged
+    inside = np.array([1, 0, 3, 2, 4, 5, 7, 6])
+    assert abs(C.output_error(1, g, [x], w, inside) - C.output_error(1, g, [x], w, None)) <= 1e-15
+
+
+def test_select_permutation_by_output_error():
+    """With the layer-output metric the selection follows output_error: argmin over the grid,
+    acceptance against the original order; the candidate orders are those of the tensor metric."""
+    rng = np.random.default_rng(12)
+    K, g = 64, 16
+    chan = np.exp(1.5 * rng.normal(size=K))
+    xs = [_bf16(rng.normal(size=(24, K)) * chan) for _ in range(2)]
+    w = _bf16(0.05 * rng.normal(size=(20, K)) / np.sqrt(chan))
+    a = C.select_permutation(1, g, xs, w, metric="tensor")
+    b = C.select_permutation(1, g, xs, w, metric="output")
+    assert all(np.array_equal(p, q) for p, q in zip(a.cand_perms, b.cand_perms))
+    errs = [C.output_error(1, g, xs, w, p) for p in b.cand_perms]
+    assert b.e_cand == errs and b.alpha_index == int(np.argmin(errs))
+    assert b.e_orig == C.output_error(1, g, xs, w, None)
+    assert b.accepted == (errs[b.alpha_index] < b.e_orig)
+    assert np.array_equal(b.perm, b.cand_perms[b.alpha_index] if b.accepted else np.arange(K))
+    with pytest.raises(ValueError):
+        C.select_permutation(1, g, xs, w, metric="other")
