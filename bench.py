@@ -212,6 +212,14 @@ def main():
     tw_h = ts_w.item() if fmt == pq.FMT_NVFP4 else 1.0
     t_sel = time_calls(lambda i: pq.pq_select_perm(fmt, g, sa, sw, xs, w, ta_h, tw_h, perm, workspace=ws_sel), 3,
                        graph=False)
+    # the selection under the other metric (relative error of the layer's output): the forward path run
+    # once per candidate and batch, plus the unquantized products; not part of the timed step
+    ws_out = torch.empty(pq.pq_workspace_bytes(pq.OP_SELECT_PERM_OUTPUT, fmt, g, M, N, K, nb), dtype=torch.uint8,
+                         device=dev)
+    perm_o = torch.empty_like(perm)
+    t_sel_out = time_calls(lambda i: pq.pq_select_perm_output_error(fmt, g, sa, sw, xs, w, ta_h, tw_h, perm_o,
+                                                                    workspace=ws_out), 2, graph=False)
+    del ws_out, perm_o
 
     # references measured in the same run: a plain streaming kernel with the footprint of the
     # quantizer (reads the bf16 tensor, writes codes + scales) and of the moments pass (reads
@@ -285,6 +293,7 @@ def main():
         "calibrate_moments_plus_select": {"us": t_cal * 1e6},
         "select_perm": {"us": t_sel * 1e6,
                         "element_evaluations_per_s": 7.0 * (nb * M + N) * K / t_sel},
+        "select_perm_output_error": {"us": t_sel_out * 1e6},
         # the step in front of the path (normalisation with the reorder absorbed), cold inputs
         "norm_reorder_rms_cold": {"us": t_rms * 1e6, "gbs": 2 * mbytes / t_rms / 1e9,
                                   "frac_hbm_peak": 2 * mbytes / t_rms / 1e9 / HBM_PEAK_GBS},

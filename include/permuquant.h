@@ -56,7 +56,8 @@ typedef enum {
   PQ_OP_QUANTIZE_WEIGHTS = 2,
   PQ_OP_QUANTIZE_ACT = 3,
   PQ_OP_QGEMM = 4,
-  PQ_OP_QUANT_ERROR = 5
+  PQ_OP_QUANT_ERROR = 5,
+  PQ_OP_SELECT_PERM_OUTPUT = 6
 } pq_op;
 
 #define PQ_OK 0
@@ -157,6 +158,24 @@ int pq_select_perm(pq_format fmt, int group, const double* act_sumsq, const doub
                    const double* alphas, int n_alpha, double tau, int32_t* perm_out,
                    pq_select_report* report, void* workspace, size_t workspace_bytes,
                    void* stream);
+
+/*
+ * The same selection with the layer-output error as the metric -- the other reading of "smallest
+ * quantization error on the calibration data" (paper Sec. 3.3), in terms of Eq. 8:
+ *     E_out(pi) = sum_b ||X_b W^T - Q(X_b P) Q(P^T W)^T||^2 / sum_b ||X_b W^T||^2.
+ * Candidates, argmin, tie rule, acceptance rule and arguments as for pq_select_perm; K must also be a
+ * multiple of 32 (the quantized product runs through the packed forward path, the unquantized one
+ * through a plain bf16 MFMA kernel, both with fp32 accumulation: E_out carries a relative error of
+ * about 1e-5 against exact arithmetic).  report->sum_x2 holds sum_b ||X_b W^T||^2, sum_w2 is 0.
+ * workspace: pq_workspace_bytes(PQ_OP_SELECT_PERM_OUTPUT, fmt, group, M, N, K, n_batches) bytes -- it
+ * holds the fp32 reference products of all batches (4 n_batches M N bytes).
+ */
+int pq_select_perm_output_error(pq_format fmt, int group, const double* act_sumsq, const double* w_sumsq,
+                                int64_t K, const void* const* x_calib, int n_batches, int64_t M,
+                                const void* w_bf16, int64_t N, float act_tensor_scale, float w_tensor_scale,
+                                const double* alphas, int n_alpha, double tau, int32_t* perm_out,
+                                pq_select_report* report, void* workspace, size_t workspace_bytes,
+                                void* stream);
 
 /*
  * Squared quantization error of one tensor in a given channel order (paper Eq. 3 on a finite

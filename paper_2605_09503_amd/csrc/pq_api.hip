@@ -57,6 +57,9 @@ size_t pq_workspace_bytes(pq_op op, pq_format fmt, int group, int64_t M, int64_t
     case PQ_OP_QUANT_ERROR:
       if (M <= 0) return 0;
       return quant_error_workspace_bytes(M);
+    case PQ_OP_SELECT_PERM_OUTPUT:
+      if (M <= 0 || N <= 0 || K <= 0 || n_batches <= 0 || check_format(fmt, group, K) || K % 32) return 0;
+      return select_output_workspace_bytes(fmt, group, M, N, K, n_batches);
     case PQ_OP_QGEMM:
       if (M <= 0 || N <= 0 || K <= 0 || group <= 0) return 0;
       return qgemm_workspace_bytes(fmt, group, M, N, K);
@@ -105,38 +108,65 @@ int pq_tensor_scale(const float* absmax, float* tensor_scale_out, void* stream) 
   return launch_tensor_scale(absmax, tensor_scale_out, as_stream(stream));
 }
 
+static int select_common(bool output_metric, pq_format fmt, int group, const double* act_sumsq,
+                         const double* w_sumsq, int64_t K, const void* const* x_calib, int n_batches, int64_t M,
+                         const void* w_bf16, int64_t N, float act_tensor_scale, float w_tensor_scale,
+                         const double* alphas, int n_alpha, double tau, int32_t* perm_out,
+                         pq_select_report* report, void* workspace, size_t workspace_bytes, void* stream) {
+  const char* who = output_metric ? "pq_select_perm_output_error" : "pq_select_perm";
+  if (!act_sumsq || !w_sumsq || !x_calib || !w_bf16 || !alphas || !perm_out || !report)
+    return fail(PQ_ERR_NULL, "%s: a required pointer is NULL", who);
+  int rc = check_format(fmt, group, K);
+  if (rc) return rc;
+  if (M <= 0 || N <= 0) return fail(PQ_ERR_SHAPE, "%s: M=%lld N=%lld must be positive", who, (long long)M, (long long)N);
+  if (n_batches <= 0) return fail(PQ_ERR_SHAPE, "%s: n_batches=%d must be positive", who, n_batches);
+  if (n_alpha <= 0 || n_alpha > PQ_MAX_ALPHAS)
+    return fail(PQ_ERR_SHAPE, "%s: n_alpha=%d outside 1..%d", who, n_alpha, PQ_MAX_ALPHAS);
+  if (K > 65536) return fail(PQ_ERR_SHAPE, "%s: K=%lld above the supported 65536", who, (long long)K);
+  if (output_metric && K % 32) return fail(PQ_ERR_SHAPE, "%s: K=%lld must be a multiple of 32", who, (long long)K);
+  if (output_metric && (M > (1 << 24) || N > (1 << 24))) return fail(PQ_ERR_SHAPE, "%s: a dimension exceeds 2^24", who);
+  for (int j = 0; j < n_alpha; ++j)
+    if (!(alphas[j] >= 0.0 && alphas[j] <= 1.0))
+      return fail(PQ_ERR_SHAPE, "%s: alphas[%d]=%g outside [0, 1]", who, j, alphas[j]);
+  if (!(tau == tau)) return fail(PQ_ERR_SHAPE, "%s: tau is NaN", who);
+  for (int b = 0; b < n_batches; ++b) {
+    if (!x_calib[b]) return fail(PQ_ERR_NULL, "%s: x_calib[%d] is NULL", who, b);
+    if (!aligned16(x_calib[b])) return fail(PQ_ERR_SHAPE, "%s: x_calib[%d] must be 16-byte aligned", who, b);
+  }
+  if (!aligned16(w_bf16)) return fail(PQ_ERR_SHAPE, "%s: w must be 16-byte aligned", who);
+  const size_t need = output_metric ? select_output_workspace_bytes(fmt, group, M, N, K, n_batches)
+                                    : select_workspace_bytes(M, N, K, n_batches);
+  if (!workspace || workspace_bytes < need)
+    return fail(PQ_ERR_WORKSPACE, "%s: workspace of %zu bytes needed, %zu given", who, need,
+                workspace ? workspace_bytes : (size_t)0);
+  if (output_metric)
+    return run_select_output(fmt, group, act_sumsq, w_sumsq, K, x_calib, n_batches, M, w_bf16, N, act_tensor_scale,
+                             w_tensor_scale, alphas, n_alpha, tau, perm_out, report, workspace, as_stream(stream));
+  return run_select(fmt, group, act_sumsq, w_sumsq, K, x_calib, n_batches, M, w_bf16, N,
+                    act_tensor_scale, w_tensor_scale, alphas, n_alpha, tau, perm_out, report,
+                    workspace, as_stream(stream));
+}
+
 int pq_select_perm(pq_format fmt, int group, const double* act_sumsq, const double* w_sumsq,
                    int64_t K, const void* const* x_calib, int n_batches, int64_t M,
                    const void* w_bf16, int64_t N, float act_tensor_scale, float w_tensor_scale,
                    const double* alphas, int n_alpha, double tau, int32_t* perm_out,
                    pq_select_report* report, void* workspace, size_t workspace_bytes,
                    void* stream) {
-  if (!act_sumsq || !w_sumsq || !x_calib || !w_bf16 || !alphas || !perm_out || !report)
-    return fail(PQ_ERR_NULL, "pq_select_perm: a required pointer is NULL");
-  int rc = check_format(fmt, group, K);
-  if (rc) return rc;
-  if (M <= 0 || N <= 0) return fail(PQ_ERR_SHAPE, "pq_select_perm: M=%lld N=%lld must be positive",
-                                    (long long)M, (long long)N);
-  if (n_batches <= 0) return fail(PQ_ERR_SHAPE, "pq_select_perm: n_batches=%d must be positive", n_batches);
-  if (n_alpha <= 0 || n_alpha > PQ_MAX_ALPHAS)
-    return fail(PQ_ERR_SHAPE, "pq_select_perm: n_alpha=%d outside 1..%d", n_alpha, PQ_MAX_ALPHAS);
-  if (K > 65536) return fail(PQ_ERR_SHAPE, "pq_select_perm: K=%lld above the supported 65536", (long long)K);
-  for (int j = 0; j < n_alpha; ++j)
-    if (!(alphas[j] >= 0.0 && alphas[j] <= 1.0))
-      return fail(PQ_ERR_SHAPE, "pq_select_perm: alphas[%d]=%g outside [0, 1]", j, alphas[j]);
-  if (!(tau == tau)) return fail(PQ_ERR_SHAPE, "pq_select_perm: tau is NaN");
-  for (int b = 0; b < n_batches; ++b) {
-    if (!x_calib[b]) return fail(PQ_ERR_NULL, "pq_select_perm: x_calib[%d] is NULL", b);
-    if (!aligned16(x_calib[b])) return fail(PQ_ERR_SHAPE, "pq_select_perm: x_calib[%d] must be 16-byte aligned", b);
-  }
-  if (!aligned16(w_bf16)) return fail(PQ_ERR_SHAPE, "pq_select_perm: w must be 16-byte aligned");
-  size_t need = select_workspace_bytes(M, N, K, n_batches);
-  if (!workspace || workspace_bytes < need)
-    return fail(PQ_ERR_WORKSPACE, "pq_select_perm: workspace of %zu bytes needed, %zu given", need,
-                workspace ? workspace_bytes : (size_t)0);
-  return run_select(fmt, group, act_sumsq, w_sumsq, K, x_calib, n_batches, M, w_bf16, N,
-                    act_tensor_scale, w_tensor_scale, alphas, n_alpha, tau, perm_out, report,
-                    workspace, as_stream(stream));
+  return select_common(false, fmt, group, act_sumsq, w_sumsq, K, x_calib, n_batches, M, w_bf16, N,
+                       act_tensor_scale, w_tensor_scale, alphas, n_alpha, tau, perm_out, report, workspace,
+                       workspace_bytes, stream);
+}
+
+int pq_select_perm_output_error(pq_format fmt, int group, const double* act_sumsq, const double* w_sumsq,
+                                int64_t K, const void* const* x_calib, int n_batches, int64_t M,
+                                const void* w_bf16, int64_t N, float act_tensor_scale, float w_tensor_scale,
+                                const double* alphas, int n_alpha, double tau, int32_t* perm_out,
+                                pq_select_report* report, void* workspace, size_t workspace_bytes,
+                                void* stream) {
+  return select_common(true, fmt, group, act_sumsq, w_sumsq, K, x_calib, n_batches, M, w_bf16, N,
+                       act_tensor_scale, w_tensor_scale, alphas, n_alpha, tau, perm_out, report, workspace,
+                       workspace_bytes, stream);
 }
 
 int pq_quant_error(pq_format fmt, int group, const void* x, int64_t rows, int64_t K,

@@ -45,6 +45,14 @@ int run_select(pq_format fmt, int group, const double* act_sumsq, const double* 
                const void* const* x_calib, int n_batches, int64_t M, const void* w, int64_t N,
                float act_ts, float w_ts, const double* alphas, int n_alpha, double tau,
                int32_t* perm_out, pq_select_report* report, void* ws, hipStream_t st);
+int launch_candidate_orders(const double* act_sumsq, const double* w_sumsq, int64_t K, const double* alphas,
+                            int n_alpha, double* keys, int32_t* rank, int32_t* cands, hipStream_t st);
+int launch_identity_order(int32_t* perm, int64_t K, hipStream_t st);
+size_t select_output_workspace_bytes(pq_format fmt, int group, int64_t M, int64_t N, int64_t K, int n_batches);
+int run_select_output(pq_format fmt, int group, const double* act_sumsq, const double* w_sumsq, int64_t K,
+                      const void* const* x_calib, int n_batches, int64_t M, const void* w, int64_t N,
+                      float act_ts, float w_ts, const double* alphas, int n_alpha, double tau,
+                      int32_t* perm_out, pq_select_report* report, void* ws, hipStream_t st);
 int run_quant_error(pq_format fmt, int group, const void* x, int64_t rows, int64_t K,
                     const int32_t* perm, float ts, double* err_out, void* ws, hipStream_t st);
 

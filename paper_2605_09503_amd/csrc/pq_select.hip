@@ -462,6 +462,25 @@ int run_quant_error(pq_format fmt, int group, const void* x, int64_t rows, int64
   return check_hip(hipGetLastError(), "reduce_rows_kernel");
 }
 
+// The candidate orders of the alpha grid (joint score, descending stable sort) into
+// cands[n_alpha][K]; keys [PQ_MAX_ALPHAS][K] doubles and rank [PQ_MAX_ALPHAS][K] ints are scratch.
+int launch_candidate_orders(const double* act_sumsq, const double* w_sumsq, int64_t K, const double* alphas,
+                            int n_alpha, double* keys, int32_t* rank, int32_t* cands, hipStream_t st) {
+  const unsigned kb = (unsigned)((K + 255) / 256);
+  const int chunks = rank_chunks(K);
+  AlphaList al;
+  for (int j = 0; j < PQ_MAX_ALPHAS; ++j) al.a[j] = j < n_alpha ? alphas[j] : 0.0;
+  hipLaunchKernelGGL(key_kernel, dim3(kb, n_alpha), dim3(256), 0, st, act_sumsq, w_sumsq, K, al, keys, rank);
+  hipLaunchKernelGGL(rank_count_kernel, dim3(kb, chunks, n_alpha), dim3(256), 0, st, keys, (int)K, rank);
+  hipLaunchKernelGGL(rank_scatter_kernel, dim3(kb, n_alpha), dim3(256), 0, st, rank, (int)K, cands);
+  return check_hip(hipGetLastError(), "key/rank kernels");
+}
+
+int launch_identity_order(int32_t* perm, int64_t K, hipStream_t st) {
+  hipLaunchKernelGGL(iota_kernel, dim3((unsigned)((K + 255) / 256)), dim3(256), 0, st, perm, (int)K);
+  return check_hip(hipGetLastError(), "iota_kernel");
+}
+
 int run_select(pq_format fmt, int group, const double* act_sumsq, const double* w_sumsq, int64_t K,
                const void* const* x_calib, int n_batches, int64_t M, const void* w, int64_t N,
                float act_ts, float w_ts, const double* alphas, int n_alpha, double tau,
@@ -469,16 +488,8 @@ int run_select(pq_format fmt, int group, const double* act_sumsq, const double* 
   SelectWs W;
   carve_select(ws, M, N, K, n_batches, &W);
   const int n_cand = n_alpha + 1;            // candidate 0 is the original order
-  const unsigned kb = (unsigned)((K + 255) / 256);
-  const int chunks = rank_chunks(K);
   int rc;
-  AlphaList al;
-  for (int j = 0; j < PQ_MAX_ALPHAS; ++j) al.a[j] = j < n_alpha ? alphas[j] : 0.0;
-  hipLaunchKernelGGL(key_kernel, dim3(kb, n_alpha), dim3(256), 0, st, act_sumsq, w_sumsq, K, al, W.keys,
-                     W.rank);
-  hipLaunchKernelGGL(rank_count_kernel, dim3(kb, chunks, n_alpha), dim3(256), 0, st, W.keys, (int)K, W.rank);
-  hipLaunchKernelGGL(rank_scatter_kernel, dim3(kb, n_alpha), dim3(256), 0, st, W.rank, (int)K, W.cands);
-  if ((rc = check_hip(hipGetLastError(), "key/rank kernels"))) return rc;
+  if ((rc = launch_candidate_orders(act_sumsq, w_sumsq, K, alphas, n_alpha, W.keys, W.rank, W.cands, st))) return rc;
   double* sums = W.sums;
   // activations: all batches of a launch share one grid (up to kMaxMomentBatches per launch)
   const QeShape qa = qe_shape(M, K, n_batches < kMaxMomentBatches ? n_batches : kMaxMomentBatches);
@@ -533,8 +544,7 @@ int run_select(pq_format fmt, int group, const double* act_sumsq, const double* 
     rc = check_hip(hipMemcpyAsync(perm_out, W.cands + (int64_t)best * K, (size_t)K * 4,
                                   hipMemcpyDeviceToDevice, st), "copy permutation");
   } else {
-    hipLaunchKernelGGL(iota_kernel, dim3(kb), dim3(256), 0, st, perm_out, (int)K);
-    rc = check_hip(hipGetLastError(), "iota_kernel");
+    rc = launch_identity_order(perm_out, K, st);
   }
   return rc;
 }

@@ -15,7 +15,8 @@ from typing import List, Optional, Sequence
 import torch
 
 FMT_NVFP4, FMT_INT4, FMT_INT3 = 0, 1, 2
-OP_CALIB_MOMENTS, OP_SELECT_PERM, OP_QUANTIZE_WEIGHTS, OP_QUANTIZE_ACT, OP_QGEMM, OP_QUANT_ERROR = range(6)
+OP_CALIB_MOMENTS, OP_SELECT_PERM, OP_QUANTIZE_WEIGHTS, OP_QUANTIZE_ACT, OP_QGEMM, OP_QUANT_ERROR, \
+    OP_SELECT_PERM_OUTPUT = range(7)
 MAX_ALPHAS = 15
 DEFAULT_ALPHAS = (0.0, 0.2, 0.4, 0.6, 0.8, 1.0)
 
@@ -69,6 +70,7 @@ def load():
     lib.pq_select_perm.argtypes = [i32, i32, vp, vp, i64, C.POINTER(vp), i32, i64, vp, i64,
                                    C.c_float, C.c_float, C.POINTER(C.c_double), i32, C.c_double,
                                    vp, C.POINTER(_Report), vp, sz, vp]
+    lib.pq_select_perm_output_error.argtypes = lib.pq_select_perm.argtypes
     lib.pq_quant_error.argtypes = [i32, i32, vp, i64, i64, vp, C.c_float, vp, vp, sz, vp]
     lib.pq_quantize_weights.argtypes = [i32, i32, vp, i64, i64, vp, vp, vp, vp, vp]
     lib.pq_quantize_act.argtypes = [i32, i32, vp, i64, i64, i64, vp, vp, vp, vp, vp]
@@ -174,25 +176,41 @@ class SelectReport:
     sum_w2: float
 
 
+def _select(entry: str, op: int, fmt, group, act_sumsq, w_sumsq, x_calib, w, act_tensor_scale, w_tensor_scale,
+            perm_out, alphas, tau, workspace) -> SelectReport:
+    M, K = x_calib[0].shape
+    N = w.shape[0]
+    nb = len(x_calib)
+    if workspace is None:
+        workspace = _workspace(pq_workspace_bytes(op, fmt, group, M, N, K, nb), w.device)
+    ptrs = (C.c_void_p * nb)(*[xb.data_ptr() for xb in x_calib])
+    al = (C.c_double * len(alphas))(*[float(a) for a in alphas])
+    rep = _Report()
+    _check(getattr(load(), entry)(fmt, group, _ptr(act_sumsq), _ptr(w_sumsq), K, ptrs, nb, M, _ptr(w), N,
+                                  float(act_tensor_scale), float(w_tensor_scale), al, len(alphas),
+                                  float(tau), _ptr(perm_out), C.byref(rep), _ptr(workspace),
+                                  0 if workspace is None else workspace.numel(), _stream()))
+    return SelectReport(bool(rep.accepted), rep.alpha_index, rep.e_orig, rep.e_best,
+                        [rep.e_cand[j] for j in range(len(alphas))], rep.sum_x2, rep.sum_w2)
+
+
 def pq_select_perm(fmt: int, group: int, act_sumsq: torch.Tensor, w_sumsq: torch.Tensor,
                    x_calib: Sequence[torch.Tensor], w: torch.Tensor, act_tensor_scale: float,
                    w_tensor_scale: float, perm_out: torch.Tensor,
                    alphas: Sequence[float] = DEFAULT_ALPHAS, tau: float = 0.0,
                    workspace: Optional[torch.Tensor] = None) -> SelectReport:
-    M, K = x_calib[0].shape
-    N = w.shape[0]
-    nb = len(x_calib)
-    if workspace is None:
-        workspace = _workspace(pq_workspace_bytes(OP_SELECT_PERM, fmt, group, M, N, K, nb), w.device)
-    ptrs = (C.c_void_p * nb)(*[xb.data_ptr() for xb in x_calib])
-    al = (C.c_double * len(alphas))(*[float(a) for a in alphas])
-    rep = _Report()
-    _check(load().pq_select_perm(fmt, group, _ptr(act_sumsq), _ptr(w_sumsq), K, ptrs, nb, M, _ptr(w), N,
-                                 float(act_tensor_scale), float(w_tensor_scale), al, len(alphas),
-                                 float(tau), _ptr(perm_out), C.byref(rep), _ptr(workspace),
-                                 0 if workspace is None else workspace.numel(), _stream()))
-    return SelectReport(bool(rep.accepted), rep.alpha_index, rep.e_orig, rep.e_best,
-                        [rep.e_cand[j] for j in range(len(alphas))], rep.sum_x2, rep.sum_w2)
+    return _select("pq_select_perm", OP_SELECT_PERM, fmt, group, act_sumsq, w_sumsq, x_calib, w,
+                   act_tensor_scale, w_tensor_scale, perm_out, alphas, tau, workspace)
+
+
+def pq_select_perm_output_error(fmt: int, group: int, act_sumsq: torch.Tensor, w_sumsq: torch.Tensor,
+                                x_calib: Sequence[torch.Tensor], w: torch.Tensor, act_tensor_scale: float,
+                                w_tensor_scale: float, perm_out: torch.Tensor,
+                                alphas: Sequence[float] = DEFAULT_ALPHAS, tau: float = 0.0,
+                                workspace: Optional[torch.Tensor] = None) -> SelectReport:
+    """The selection with the relative error of the layer's output as the metric."""
+    return _select("pq_select_perm_output_error", OP_SELECT_PERM_OUTPUT, fmt, group, act_sumsq, w_sumsq, x_calib, w,
+                   act_tensor_scale, w_tensor_scale, perm_out, alphas, tau, workspace)
 
 
 def pq_quant_error(fmt: int, group: int, x: torch.Tensor, perm: Optional[torch.Tensor],

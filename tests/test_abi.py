@@ -172,6 +172,27 @@ def test_packed_operand_validation(lib):
     assert lib.pq_probe_stream(FAKE, 24, FAKE, 0, None) == PQ_ERR_SHAPE
 
 
+def test_select_output_error_validation(lib):
+    w = lib.pq_workspace_bytes
+    # the workspace holds the fp32 reference products of all batches
+    assert w(pq.OP_SELECT_PERM_OUTPUT, pq.FMT_INT4, 64, 4608, 3072, 3072, 8) > 8 * 4608 * 3072 * 4
+    assert w(pq.OP_SELECT_PERM_OUTPUT, pq.FMT_INT4, 64, 64, 64, 96, 1) == 0          # K % group
+    assert w(pq.OP_SELECT_PERM_OUTPUT, pq.FMT_NVFP4, 16, 64, 64, 48, 1) == 0         # K % 32
+    f = lib.pq_select_perm_output_error
+    al = (C.c_double * 2)(0.0, 1.0)
+    rep = pq._Report()
+    xs = (C.c_void_p * 1)(0x1000)
+    args = lambda K=64, ws=FAKE, size=1 << 30: (1, 32, FAKE, FAKE, K, xs, 1, 8, FAKE, 8, 1.0, 1.0, al, 2, 0.0, FAKE,
+                                                C.byref(rep), ws, size, None)
+    assert f(*args(K=48)) == PQ_ERR_SHAPE              # K % group
+    assert f(1, 16, FAKE, FAKE, 48, xs, 1, 8, FAKE, 8, 1.0, 1.0, al, 2, 0.0, FAKE, C.byref(rep), FAKE, 1 << 30,
+             None) == PQ_ERR_FORMAT                    # INT4 with group 16 is not offered
+    assert f(0, 16, FAKE, FAKE, 48, xs, 1, 8, FAKE, 8, 1.0, 1.0, al, 2, 0.0, FAKE, C.byref(rep), FAKE, 1 << 30,
+             None) == PQ_ERR_SHAPE                     # NVFP4, K = 48: not a multiple of 32
+    assert f(*args(ws=None)) == PQ_ERR_WORKSPACE
+    assert f(*args(size=16)) == PQ_ERR_WORKSPACE
+
+
 def test_norm_validation(lib):
     def params(kind=0, perm=None, gamma=None, eps=1e-6):
         return pq.NormParams(kind, perm, gamma, None, None, 0, eps)

@@ -242,6 +242,51 @@ def test_select_perm_matches_oracle(name, fmt, g, M, N, K, nb):
     np.testing.assert_array_equal(perm_out.cpu().numpy(), np.arange(K))
 
 
+@pytest.mark.parametrize("name,fmt,g,M,N,K,nb", [
+    ("c0", pq.FMT_NVFP4, 16, 256, 512, 512, 4),
+    ("c1", pq.FMT_INT4, 64, 160, 192, 768, 3),
+    ("c4", pq.FMT_INT3, 32, 200, 150, 640, 2),      # N not a multiple of 8: padded fp32 rows
+])
+def test_select_perm_output_error_matches_oracle(name, fmt, g, M, N, K, nb):
+    """The selection with the layer-output metric.  Both products accumulate in fp32 on the GPU, the
+    oracle in fp64: the error ratios agree to 1e-4 (their difference of nearly equal numbers amplifies
+    the 1e-7 of the accumulation), and argmin / acceptance are compared only where the oracle's margins
+    are far above that."""
+    _say("select_perm_output_error %s fmt=%d g=%d M=%d N=%d K=%d" % (name, fmt, g, M, N, K))
+    base = synth.CONFIGS[name]
+    cfg = synth.scaled(base, M=M, N=N, K=K, n_calib=nb, n_outlier=min(base.n_outlier, K // 64))
+    st, calib, test, xs, w = _layer_on_gpu(cfg)
+    sa, sw, amax_a, amax_w = _gpu_moments(xs, w, K)
+    xs64 = [OF.bf16_bits_to_f64(b) for b in calib]
+    w64 = OF.bf16_bits_to_f64(st.w_bits)
+    ts_a = ts_w = 1.0
+    if fmt == pq.FMT_NVFP4:
+        ts_a = float(OQ.nvfp4_tensor_scale(max(OC.absmax(x) for x in xs64)))
+        ts_w = float(OQ.nvfp4_tensor_scale(OC.absmax(w64)))
+    ref = OC.select_permutation(fmt, g, xs64, w64, act_tensor_scale=np.float32(ts_a) if fmt == pq.FMT_NVFP4 else None,
+                                metric="output")
+    assert ref.min_key_gap > 1e-11
+    perm_out = torch.empty(K, dtype=torch.int32, device=DEV)
+    rep = pq.pq_select_perm_output_error(fmt, g, sa, sw, xs, w, ts_a, ts_w, perm_out)
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(rep.e_orig, ref.e_orig, rtol=1e-4)
+    np.testing.assert_allclose(rep.e_cand, ref.e_cand, rtol=1e-4)
+    np.testing.assert_allclose(rep.sum_x2, sum(float(np.sum((x @ w64.T) ** 2)) for x in xs64), rtol=1e-6)
+    e = np.sort(np.asarray(ref.e_cand))
+    assert (e[1] - e[0]) / e[0] > 1e-3 and abs(ref.e_orig - ref.e_best) / ref.e_orig > 1e-3, \
+        "margins too small for comparing the decisions: reseed"
+    assert rep.alpha_index == ref.alpha_index and rep.accepted == ref.accepted
+    np.testing.assert_array_equal(perm_out.cpu().numpy(), ref.perm)
+    # determinism: a second run gives the same numbers bit for bit
+    rep_b = pq.pq_select_perm_output_error(fmt, g, sa, sw, xs, w, ts_a, ts_w, perm_out)
+    assert rep_b.e_cand == rep.e_cand and rep_b.e_orig == rep.e_orig
+    # a threshold above any gain rejects
+    rep2 = pq.pq_select_perm_output_error(fmt, g, sa, sw, xs, w, ts_a, ts_w, perm_out, tau=0.999)
+    torch.cuda.synchronize()
+    assert not rep2.accepted
+    np.testing.assert_array_equal(perm_out.cpu().numpy(), np.arange(K))
+
+
 def test_select_perm_candidates_and_ties():
     # equal second moments: the sort must keep ascending channel index (stable)
     K, M, N = 256, 32, 32
