@@ -351,6 +351,27 @@ int pq_norm_quantize_act_packed(const pq_norm_params* p, pq_format fmt, int grou
                                 size_t operand_size, void* y_bf16, int64_t ldy, void* stream);
 
 /*
+ * PermuQuant-H (paper App. D): the Hadamard rotation with the reorder applied after it, x H P -- the
+ * permutation is the order in which the fast transform's output is consumed, no pass of its own.
+ *     y_P[m, j] = (x[m, :] H)[pi(j)],   H H^T = I, entries +-1 / sqrt(K),
+ * H = S_{2^k} (x) P_m / sqrt(K): the Sylvester matrix in natural order times, for K = 12 * 2^k or
+ * 20 * 2^k, the Paley (type I) Hadamard matrix of order 12 or 20 (channel i = a * m + b); other widths
+ * return PQ_ERR_SHAPE.  Computed in fp32 from the bf16 input, rounded once to bf16.  The same call on the
+ * weight matrix (rows = output channels) gives the rotated weights to quantize offline, and on the
+ * calibration batches the tensors whose moments drive the selection; (xH)(WH)^T = x W^T.
+ * pq_hadamard_quantize_act_packed feeds the rounded values to the activation quantizer:
+ *     == pq_quantize_act_packed(pq_hadamard_reorder(x))   bit for bit.
+ * perm: int32 [K] device or NULL (identity).  x, y, ld, ldy, operand, tensor_scale as for pq_norm_reorder /
+ * pq_norm_quantize_act_packed.  One fp32 row per wave is held in LDS: K <= 39000.
+ */
+int pq_hadamard_reorder(const int32_t* perm, const void* x_bf16, int64_t M, int64_t K, int64_t ld,
+                        void* y_bf16, int64_t ldy, void* stream);
+int pq_hadamard_quantize_act_packed(const int32_t* perm, pq_format fmt, int group, const void* x_bf16,
+                                    int64_t M, int64_t K, int64_t ld, const float* tensor_scale,
+                                    void* operand, size_t operand_size, void* y_bf16, int64_t ldy,
+                                    void* stream);
+
+/*
  * Measurement aids (no part of the method; they give the timings of the kernels above a
  * reference measured on the same device in the same run).
  *

@@ -390,6 +390,49 @@ int pq_norm_quantize_act_packed(const pq_norm_params* p, pq_format fmt, int grou
   return run_norm_quantize_packed(*p, fmt, group, x, M, K, ld, tensor_scale, operand, y, ldy, as_stream(stream));
 }
 
+static int check_hadamard(const char* who, const int32_t* perm, const void* x, int64_t M, int64_t K, int64_t ld,
+                          const void* y, int64_t ldy, bool y_required) {
+  if (!x || (y_required && !y)) return fail(PQ_ERR_NULL, "%s: a required pointer is NULL", who);
+  if (M <= 0 || K <= 0) return fail(PQ_ERR_SHAPE, "%s: M=%lld K=%lld must be positive", who, (long long)M, (long long)K);
+  if (M > (1 << 24) || K > (1 << 24)) return fail(PQ_ERR_SHAPE, "%s: a dimension exceeds 2^24", who);
+  if (K % 8 || ld < K || ld % 8)
+    return fail(PQ_ERR_SHAPE, "%s: K=%lld must be a multiple of 8, ld=%lld >= K and a multiple of 8", who,
+                (long long)K, (long long)ld);
+  if (!hadamard_width_ok(K))
+    return fail(PQ_ERR_SHAPE, "%s: K=%lld is not 2^k, 12 * 2^k or 20 * 2^k: no Hadamard construction offered", who,
+                (long long)K);
+  if (y && (ldy < K || ldy % 8))
+    return fail(PQ_ERR_SHAPE, "%s: ldy=%lld must be >= K=%lld and a multiple of 8", who, (long long)ldy, (long long)K);
+  if (!aligned16(x) || !aligned16(y) || !aligned16(perm))
+    return fail(PQ_ERR_SHAPE, "%s: buffers must be 16-byte aligned", who);
+  return PQ_OK;
+}
+
+int pq_hadamard_reorder(const int32_t* perm, const void* x, int64_t M, int64_t K, int64_t ld, void* y, int64_t ldy,
+                        void* stream) {
+  int rc = check_hadamard("pq_hadamard_reorder", perm, x, M, K, ld, y, ldy, true);
+  if (rc) return rc;
+  return run_hadamard_reorder(perm, x, M, K, ld, y, ldy, as_stream(stream));
+}
+
+int pq_hadamard_quantize_act_packed(const int32_t* perm, pq_format fmt, int group, const void* x, int64_t M,
+                                    int64_t K, int64_t ld, const float* tensor_scale, void* operand,
+                                    size_t operand_size, void* y, int64_t ldy, void* stream) {
+  const char* who = "pq_hadamard_quantize_act_packed";
+  int rc = check_hadamard(who, perm, x, M, K, ld, y, ldy, false);
+  if (rc) return rc;
+  if (!operand) return fail(PQ_ERR_NULL, "%s: operand is NULL", who);
+  rc = check_format(fmt, group, K);
+  if (rc) return rc;
+  if (fmt == PQ_FMT_NVFP4 && !tensor_scale) return fail(PQ_ERR_NULL, "%s: NVFP4 needs the per-tensor scale", who);
+  if (K % 32) return fail(PQ_ERR_SHAPE, "%s: K=%lld must be a multiple of 32", who, (long long)K);
+  if (!aligned16(operand)) return fail(PQ_ERR_SHAPE, "%s: buffers must be 16-byte aligned", who);
+  const size_t need = operand_bytes(fmt, group, M, K);
+  if (operand_size < need)
+    return fail(PQ_ERR_WORKSPACE, "%s: operand buffer of %zu bytes needed, %zu given", who, need, operand_size);
+  return run_hadamard_quantize_packed(perm, fmt, group, x, M, K, ld, tensor_scale, operand, y, ldy, as_stream(stream));
+}
+
 static int qgemm_packed_common(pq_format fmt, int group, const void* a_operand, const float* a_ts,
                                const void* w_operand, const float* w_ts, int64_t M, int64_t N, int64_t K,
                                const void* bias, void* y, int64_t ldy, bool out_f32, void* stream) {

@@ -88,6 +88,12 @@ int run_norm_reorder(const pq_norm_params& p, const void* x, int64_t rows, int64
 int run_norm_quantize_packed(const pq_norm_params& p, pq_format fmt, int group, const void* x, int64_t rows,
                              int64_t K, int64_t ld, const float* ts, void* operand, void* y, int64_t ldy,
                              hipStream_t st);
+bool hadamard_width_ok(int64_t K);
+int run_hadamard_reorder(const int32_t* perm, const void* x, int64_t rows, int64_t K, int64_t ld, void* y,
+                         int64_t ldy, hipStream_t st);
+int run_hadamard_quantize_packed(const int32_t* perm, pq_format fmt, int group, const void* x, int64_t rows,
+                                 int64_t K, int64_t ld, const float* ts, void* operand, void* y, int64_t ldy,
+                                 hipStream_t st);
 int run_qgemm_packed(pq_format fmt, int group, const void* a_operand, const float* a_ts,
                      const void* w_operand, const float* w_ts, int64_t M, int64_t N, int64_t K,
                      const void* bias, void* y, int64_t ldy, bool out_f32, hipStream_t st);

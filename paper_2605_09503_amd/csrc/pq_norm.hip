@@ -17,6 +17,12 @@
 // The channel-wise vectors are shared by the rows of a workgroup: they are staged in LDS already
 // reordered (position j holds the value of channel pi(j)) once per workgroup, which is the only
 // step all waves wait for.
+//
+// The same skeleton runs the Hadamard variant (paper App. D, x H P): step 1 becomes a fast
+// Hadamard transform of the row in the wave's slab (fp32), steps 2 and 3 read the transformed
+// row at pi(j) -- the reorder is the order in which the transform's output is consumed.
+#include <math.h>
+
 #include <algorithm>
 
 #include "pq_qgemm_common.h"
@@ -25,7 +31,7 @@ namespace pq {
 
 namespace {
 
-enum Norm : int { kNormRms = 0, kNormAdaLn = 1 };
+enum Norm : int { kNormRms = 0, kNormAdaLn = 1, kHadamard = 2 };
 constexpr int kFmtNone = -1;                  // normalise and reorder only, no quantization
 constexpr int kNormMaxWaves = 8;
 
@@ -38,6 +44,8 @@ struct NormArgs {
   float eps;
   uint16_t* y;                  // bf16 [rows][ldy] normalised, reordered output, or null
   int64_t ldy;
+  int had_pow2, had_m;          // Hadamard: K = had_pow2 * had_m, had_m in {1, 12, 20}
+  float had_scale;              // 1 / sqrt(K)
 };
 
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
@@ -56,6 +64,100 @@ __device__ __forceinline__ uint32_t pack_bf16_rne(float lo, float hi) {
 struct Idx8 {
   int4 lo, hi;
 };
+
+
+// ---- fast Hadamard transform of one row held in LDS as fp32, by one wave -------------------
+// H = S_{2^k} (x) P_m / sqrt(K), channel i = a * m + b (a: Sylvester index, natural order; b: Paley
+// index).  Kronecker factors act on separate index digits, so the transform is a sequence of
+// passes, each applying a small matrix along one digit: every lane takes whole fibres (all elements
+// that differ only in that digit), transforms them in registers and writes them back.
+
+// between passes: the wave's LDS writes are complete and visible to its other lanes
+__device__ __forceinline__ void wave_lds_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// Sylvester matrix of order R along a digit of weight `inner` elements; n_fibres = K / R
+template <int R>
+__device__ __forceinline__ void sylvester_pass(float* slab, int inner, int n_fibres, int lane) {
+  for (int f = lane; f < n_fibres; f += 64) {
+    const int hi = f / inner, lo = f - hi * inner;
+    float* base = slab + hi * (R * inner) + lo;
+    float v[R];
+#pragma unroll
+    for (int t = 0; t < R; ++t) v[t] = base[t * inner];
+#pragma unroll
+    for (int h = 1; h < R; h <<= 1)
+#pragma unroll
+      for (int i = 0; i < R; i += 2 * h)
+#pragma unroll
+        for (int j = i; j < i + h; ++j) {
+          const float a = v[j], b = v[j + h];
+          v[j] = a + b;
+          v[j + h] = a - b;
+        }
+#pragma unroll
+    for (int t = 0; t < R; ++t) base[t * inner] = v[t];
+  }
+  wave_lds_sync();
+}
+
+// quadratic character mod Q (Q prime): +1 for a non-zero square, -1 otherwise, 0 for 0
+template <int Q>
+__host__ __device__ constexpr int legendre(int r) {
+  r = ((r % Q) + Q) % Q;
+  if (r == 0) return 0;
+  for (int t = 1; t < Q; ++t)
+    if ((t * t) % Q == r) return 1;
+  return -1;
+}
+
+// entry (b, b2) of the Paley type I Hadamard matrix of order M = Q + 1:  I + [[0, 1^T], [-1, chi(i - j)]]
+template <int M>
+__host__ __device__ constexpr int paley_entry(int b, int b2) {
+  if (b == b2) return 1;
+  if (b == 0) return 1;
+  if (b2 == 0) return -1;
+  return legendre<M - 1>((b - 1) - (b2 - 1));
+}
+
+// y[b2] = sum_b x[b] P[b][b2] along the last digit (M contiguous elements per fibre)
+template <int M>
+__device__ __forceinline__ void paley_pass(float* slab, int n_fibres, int lane) {
+  for (int f = lane; f < n_fibres; f += 64) {
+    float* base = slab + f * M;
+    float v[M], o[M];
+#pragma unroll
+    for (int b = 0; b < M; ++b) v[b] = base[b];
+#pragma unroll
+    for (int b2 = 0; b2 < M; ++b2) {
+      float acc = 0.0f;
+#pragma unroll
+      for (int b = 0; b < M; ++b) acc = paley_entry<M>(b, b2) > 0 ? acc + v[b] : acc - v[b];
+      o[b2] = acc;
+    }
+#pragma unroll
+    for (int b = 0; b < M; ++b) base[b] = o[b];
+  }
+  wave_lds_sync();
+}
+
+__device__ __forceinline__ void hadamard_row(float* slab, int K, int pow2, int m, int lane) {
+  if (m == 12) paley_pass<12>(slab, pow2, lane);
+  if (m == 20) paley_pass<20>(slab, pow2, lane);
+  int inner = m;                       // weight of the current Sylvester digit, in elements
+  int rem = pow2;
+  while (rem >= 16) {
+    sylvester_pass<16>(slab, inner, K / 16, lane);
+    inner *= 16;
+    rem /= 16;
+  }
+  if (rem == 8) sylvester_pass<8>(slab, inner, K / 8, lane);
+  if (rem == 4) sylvester_pass<4>(slab, inner, K / 4, lane);
+  if (rem == 2) sylvester_pass<2>(slab, inner, K / 2, lane);
+}
 
 template <int FMT, int G, int NORM>
 __global__ __launch_bounds__(64 * kNormMaxWaves) void norm_rows_kernel(
@@ -82,9 +184,11 @@ __global__ __launch_bounds__(64 * kNormMaxWaves) void norm_rows_kernel(
 
   uint16_t* vec_g = reinterpret_cast<uint16_t*>(lds_raw);
   uint32_t* vec_sb = reinterpret_cast<uint32_t*>(lds_raw);
-  const size_t vec_bytes = (size_t)Ki * (NORM == kNormRms ? 2 : 4);
+  constexpr int kSlabElem = NORM == kHadamard ? 4 : 2;       // Hadamard rows are held as fp32
+  const size_t vec_bytes = NORM == kHadamard ? 0 : (size_t)Ki * (NORM == kNormRms ? 2 : 4);
   uint16_t* slab = reinterpret_cast<uint16_t*>(lds_raw + vec_bytes) + (size_t)wave * Ki;
-  float* h_lds = reinterpret_cast<float*>(lds_raw + vec_bytes + (size_t)n_waves * Ki * 2) + (size_t)wave * n_units;
+  float* slab_f = reinterpret_cast<float*>(lds_raw + vec_bytes) + (size_t)wave * Ki;
+  float* h_lds = reinterpret_cast<float*>(lds_raw + vec_bytes + (size_t)n_waves * Ki * kSlabElem) + (size_t)wave * n_units;
 
   // ---- the vectors of the first row's sample, reordered, into LDS (all threads).  Scattered
   // 2-byte loads from memory cost the texture addresser a cycle per lane, so the vectors are first
@@ -93,7 +197,7 @@ __global__ __launch_bounds__(64 * kNormMaxWaves) void norm_rows_kernel(
   // they are gathered from memory instead.)
   int64_t mod0 = 0;
   if constexpr (NORM == kNormAdaLn) mod0 = row0 / na.rows_per_mod;
-  {
+  if constexpr (NORM != kHadamard) {
     const uint16_t* v0 = NORM == kNormRms ? na.gamma : (na.mod_scale ? na.mod_scale + mod0 * K : nullptr);
     const uint16_t* v1 = NORM == kNormRms ? nullptr : (na.mod_shift ? na.mod_shift + mod0 * K : nullptr);
     constexpr uint32_t kDefault0 = NORM == kNormRms ? 0x3F80u : 0u;      // gamma = 1, s = 0
@@ -179,8 +283,33 @@ __global__ __launch_bounds__(64 * kNormMaxWaves) void norm_rows_kernel(
 #pragma unroll
   for (int q = 0; q < kBatch; ++q) ix_cur[q] = load_idx(lane + 64 * q);
 
-  // ---- 1. the row: statistics, and a copy in the wave's slab
   const uint16_t* xr = x + row * ld;
+  float rstd = 0.0f, nmr = 0.0f;                             // LN(x) = x * rstd + nmr
+  if constexpr (NORM == kHadamard) {
+    // ---- 1. the row as fp32 in the wave's slab, transformed in place
+    constexpr int kInFlight = 8;
+    for (int c0 = 0; c0 < k_chunks; c0 += kInFlight * 64) {
+      uint4 lines[kInFlight];
+#pragma unroll
+      for (int t = 0; t < kInFlight; ++t) {
+        const int c = min(c0 + t * 64 + lane, k_chunks - 1);
+        lines[t] = *reinterpret_cast<const uint4*>(xr + (size_t)c * 8);
+      }
+#pragma unroll
+      for (int t = 0; t < kInFlight; ++t) {
+        const int c = c0 + t * 64 + lane;
+        if (c < k_chunks) {
+          const uint4 p = lines[t];
+          *reinterpret_cast<float4*>(slab_f + c * 8) = make_float4(bf16_lo(p.x), bf16_hi(p.x), bf16_lo(p.y), bf16_hi(p.y));
+          *reinterpret_cast<float4*>(slab_f + c * 8 + 4) = make_float4(bf16_lo(p.z), bf16_hi(p.z), bf16_lo(p.w), bf16_hi(p.w));
+        }
+      }
+    }
+    wave_lds_sync();
+    hadamard_row(slab_f, Ki, na.had_pow2, na.had_m, lane);
+    rstd = na.had_scale;
+  } else {
+  // ---- 1. the row: statistics, and a copy in the wave's slab
   float s1 = 0.0f, s2 = 0.0f;
   {
     const bf16x2_t ones = __builtin_bit_cast(bf16x2_t, 0x3F803F80u);
@@ -232,8 +361,9 @@ __global__ __launch_bounds__(64 * kNormMaxWaves) void norm_rows_kernel(
       s2 = var * k_f;
     }
   }
-  const float rstd = 1.0f / sqrtf(s2 / k_f + na.eps);
-  const float nmr = -mean * rstd;                            // LN(x) = x * rstd + nmr
+  rstd = 1.0f / sqrtf(s2 / k_f + na.eps);
+  nmr = -mean * rstd;
+  }
 
   // AdaLN: a row of another sample than the staged one reads its vectors from memory
   bool own_mod = false;
@@ -262,7 +392,7 @@ __global__ __launch_bounds__(64 * kNormMaxWaves) void norm_rows_kernel(
       const int idx[8] = {ix_cur[q].lo.x, ix_cur[q].lo.y, ix_cur[q].lo.z, ix_cur[q].lo.w,
                           ix_cur[q].hi.x, ix_cur[q].hi.y, ix_cur[q].hi.z, ix_cur[q].hi.w};
 #pragma unroll
-      for (int e = 0; e < 8; ++e) xv[q][e] = bf16_to_f32(slab[idx[e]]);
+      for (int e = 0; e < 8; ++e) xv[q][e] = NORM == kHadamard ? slab_f[idx[e]] : bf16_to_f32(slab[idx[e]]);
     }
 #pragma unroll
     for (int q = 0; q < kBatch; ++q) {
@@ -271,7 +401,10 @@ __global__ __launch_bounds__(64 * kNormMaxWaves) void norm_rows_kernel(
       const bool in_row = c < k_chunks;
       const int cc = min(c, k_chunks - 1);
       float yv[8];
-      if constexpr (NORM == kNormRms) {
+      if constexpr (NORM == kHadamard) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) yv[e] = xv[q][e] * rstd;             // 1 / sqrt(K)
+      } else if constexpr (NORM == kNormRms) {
         const uint4 gq = *reinterpret_cast<const uint4*>(vec_g + cc * 8);
         const uint32_t gw[4] = {gq.x, gq.y, gq.z, gq.w};
 #pragma unroll
@@ -361,7 +494,9 @@ __global__ __launch_bounds__(64 * kNormMaxWaves) void norm_rows_kernel(
 constexpr size_t kNormLdsLimit = 160 * 1024 - 1024;      // dynamic LDS a workgroup may ask for
 
 size_t norm_lds_bytes(int norm, bool is_int, int n_waves, int64_t K, int64_t units) {
-  return (size_t)K * (norm == kNormRms ? 2 : 4) + (size_t)n_waves * K * 2 + (is_int ? (size_t)n_waves * units * 4 : 0);
+  const size_t per_wave_int = is_int ? (size_t)n_waves * units * 4 : 0;
+  if (norm == kHadamard) return (size_t)n_waves * K * 4 + per_wave_int;
+  return (size_t)K * (norm == kNormRms ? 2 : 4) + (size_t)n_waves * K * 2 + per_wave_int;
 }
 
 // Waves (= rows) per workgroup: as many as still let the launch run in one round of resident
@@ -420,6 +555,7 @@ template <int FMT, int G>
 int launch_norm(int norm, const void* x, int64_t rows, int64_t K, int64_t ld, const float* ts,
                 const OperandLayout& L, uint8_t* operand, const NormArgs& na, hipStream_t st) {
   if (norm == kNormRms) return launch_norm_rows<FMT, G, kNormRms>(x, rows, K, ld, ts, L, operand, na, st);
+  if (norm == kHadamard) return launch_norm_rows<FMT, G, kHadamard>(x, rows, K, ld, ts, L, operand, na, st);
   return launch_norm_rows<FMT, G, kNormAdaLn>(x, rows, K, ld, ts, L, operand, na, st);
 }
 
@@ -433,6 +569,35 @@ NormArgs norm_args(const pq_norm_params& p, void* y, int64_t ldy) {
   na.eps = p.eps;
   na.y = (uint16_t*)y;
   na.ldy = ldy;
+  na.had_pow2 = na.had_m = 0;
+  na.had_scale = 0.0f;
+  return na;
+}
+
+// K = 2^k * m with m in {1, 12, 20} (the smallest such m): false if there is none
+bool hadamard_factor(int64_t K, int* pow2, int* m) {
+  const int ms[3] = {1, 12, 20};
+  for (int i = 0; i < 3; ++i) {
+    if (K % ms[i]) continue;
+    const int64_t p = K / ms[i];
+    if (p >= 1 && (p & (p - 1)) == 0) {
+      *pow2 = (int)p;
+      *m = ms[i];
+      return true;
+    }
+  }
+  return false;
+}
+
+NormArgs hadamard_args(const int32_t* perm, int64_t K, void* y, int64_t ldy, int pow2, int m) {
+  NormArgs na = {};
+  na.perm = perm;
+  na.rows_per_mod = INT64_MAX;
+  na.y = (uint16_t*)y;
+  na.ldy = ldy;
+  na.had_pow2 = pow2;
+  na.had_m = m;
+  na.had_scale = (float)(1.0 / sqrt((double)K));
   return na;
 }
 
@@ -462,6 +627,44 @@ int run_norm_quantize_packed(const pq_norm_params& p, pq_format fmt, int group, 
       case 128: return launch_norm<FE, 128>(norm, x, rows, K, ld, ts, L, o, na, st); \
       case 256: return launch_norm<FE, 256>(norm, x, rows, K, ld, ts, L, o, na, st); \
     }                                                                           \
+  }
+  PQ_INT_CASE(PQ_FMT_INT4, kInt4)
+  PQ_INT_CASE(PQ_FMT_INT3, kInt3)
+#undef PQ_INT_CASE
+  return fail(PQ_ERR_FORMAT, "unsupported (format, group) = (%d, %d)", (int)fmt, group);
+}
+
+bool hadamard_width_ok(int64_t K) {
+  int p, m;
+  return hadamard_factor(K, &p, &m);
+}
+
+int run_hadamard_reorder(const int32_t* perm, const void* x, int64_t rows, int64_t K, int64_t ld, void* y,
+                         int64_t ldy, hipStream_t st) {
+  int p, m;
+  if (!hadamard_factor(K, &p, &m)) return fail(PQ_ERR_SHAPE, "no Hadamard construction for K=%lld", (long long)K);
+  OperandLayout L = {};
+  L.steps = (K + 63) / 64;
+  return launch_norm<kFmtNone, 64>(kHadamard, x, rows, K, ld, nullptr, L, nullptr, hadamard_args(perm, K, y, ldy, p, m), st);
+}
+
+int run_hadamard_quantize_packed(const int32_t* perm, pq_format fmt, int group, const void* x, int64_t rows,
+                                 int64_t K, int64_t ld, const float* ts, void* operand, void* y, int64_t ldy,
+                                 hipStream_t st) {
+  int p, m;
+  if (!hadamard_factor(K, &p, &m)) return fail(PQ_ERR_SHAPE, "no Hadamard construction for K=%lld", (long long)K);
+  const OperandLayout L = operand_layout(fmt, group, rows, K);
+  const NormArgs na = hadamard_args(perm, K, y, ldy, p, m);
+  uint8_t* o = (uint8_t*)operand;
+  if (fmt == PQ_FMT_NVFP4) return launch_norm<kNvfp4, 16>(kHadamard, x, rows, K, ld, ts, L, o, na, st);
+#define PQ_INT_CASE(F, FE)                                                           \
+  if (fmt == F) {                                                                    \
+    switch (group) {                                                                 \
+      case 32: return launch_norm<FE, 32>(kHadamard, x, rows, K, ld, ts, L, o, na, st);   \
+      case 64: return launch_norm<FE, 64>(kHadamard, x, rows, K, ld, ts, L, o, na, st);   \
+      case 128: return launch_norm<FE, 128>(kHadamard, x, rows, K, ld, ts, L, o, na, st); \
+      case 256: return launch_norm<FE, 256>(kHadamard, x, rows, K, ld, ts, L, o, na, st); \
+    }                                                                                \
   }
   PQ_INT_CASE(PQ_FMT_INT4, kInt4)
   PQ_INT_CASE(PQ_FMT_INT3, kInt3)

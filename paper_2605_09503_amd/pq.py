@@ -87,6 +87,8 @@ def load():
     lib.pq_qgemm_packed.argtypes = packed_args
     lib.pq_qgemm_packed_f32.argtypes = packed_args
     lib.pq_qgemm_packed_bias.argtypes = [i32, i32, vp, vp, vp, vp, i64, i64, i64, vp, vp, i64, vp]
+    lib.pq_hadamard_reorder.argtypes = [vp, vp, i64, i64, i64, vp, i64, vp]
+    lib.pq_hadamard_quantize_act_packed.argtypes = [vp, i32, i32, vp, i64, i64, i64, vp, vp, sz, vp, i64, vp]
     lib.pq_dynamic_tensor_scale.argtypes = [vp, i64, i64, i64, vp, vp]
     lib.pq_norm_reorder.argtypes = [C.POINTER(NormParams), vp, i64, i64, i64, vp, i64, vp]
     lib.pq_norm_quantize_act_packed.argtypes = [C.POINTER(NormParams), i32, i32, vp, i64, i64, i64, vp, vp, sz,
@@ -356,6 +358,31 @@ def pq_norm_quantize_act_packed(kind: int, fmt: int, group: int, x: torch.Tensor
     _check(load().pq_norm_quantize_act_packed(C.byref(p), fmt, group, _ptr(x), M, K, x.stride(0),
                                               _ptr(tensor_scale), _ptr(operand), operand.numel(), _ptr(y),
                                               0 if y is None else y.stride(0), _stream()))
+    return operand
+
+
+def pq_hadamard_reorder(x: torch.Tensor, perm: Optional[torch.Tensor] = None, y: Optional[torch.Tensor] = None,
+                        K: Optional[int] = None) -> torch.Tensor:
+    """x H with the columns of the result in the order `perm` (bf16 [M, K])."""
+    M = x.shape[0]
+    K = x.shape[1] if K is None else K
+    if y is None:
+        y = torch.empty((M, K), dtype=torch.bfloat16, device=x.device)
+    _check(load().pq_hadamard_reorder(_ptr(perm), _ptr(x), M, K, x.stride(0), _ptr(y), y.stride(0), _stream()))
+    return y
+
+
+def pq_hadamard_quantize_act_packed(fmt: int, group: int, x: torch.Tensor, tensor_scale: Optional[torch.Tensor],
+                                    perm: Optional[torch.Tensor] = None, operand: Optional[torch.Tensor] = None,
+                                    y: Optional[torch.Tensor] = None, K: Optional[int] = None) -> torch.Tensor:
+    """The rotation feeding the activation quantizer directly: returns the GEMM operand."""
+    M = x.shape[0]
+    K = x.shape[1] if K is None else K
+    if operand is None:
+        operand = torch.empty(max(pq_operand_bytes(fmt, group, M, K), 16), dtype=torch.uint8, device=x.device)
+    _check(load().pq_hadamard_quantize_act_packed(_ptr(perm), fmt, group, _ptr(x), M, K, x.stride(0),
+                                                  _ptr(tensor_scale), _ptr(operand), operand.numel(), _ptr(y),
+                                                  0 if y is None else y.stride(0), _stream()))
     return operand
 
 

@@ -193,6 +193,21 @@ def test_select_output_error_validation(lib):
     assert f(*args(size=16)) == PQ_ERR_WORKSPACE
 
 
+def test_hadamard_validation(lib):
+    f = lib.pq_hadamard_reorder
+    assert f(None, None, 8, 64, 64, FAKE, 64, None) == PQ_ERR_NULL
+    assert f(None, FAKE, 8, 64, 64, None, 64, None) == PQ_ERR_NULL
+    assert f(None, FAKE, 8, 1152, 1152, FAKE, 1152, None) == PQ_ERR_SHAPE        # 9 * 2^7: no construction
+    assert b"Hadamard" in lib.pq_last_error()
+    assert f(None, FAKE, 8, 64, 56, FAKE, 64, None) == PQ_ERR_SHAPE
+    assert f(C.c_void_p(0x1004), FAKE, 8, 64, 64, FAKE, 64, None) == PQ_ERR_SHAPE
+    g = lib.pq_hadamard_quantize_act_packed
+    assert g(None, 1, 64, FAKE, 8, 64, 64, None, None, 1 << 20, None, 0, None) == PQ_ERR_NULL
+    assert g(None, 0, 16, FAKE, 8, 64, 64, None, FAKE, 1 << 20, None, 0, None) == PQ_ERR_NULL
+    assert g(None, 1, 64, FAKE, 8, 24, 24, None, FAKE, 1 << 20, None, 0, None) == PQ_ERR_SHAPE    # K % group
+    assert g(None, 1, 64, FAKE, 8, 64, 64, None, FAKE, 16, None, 0, None) == PQ_ERR_WORKSPACE
+
+
 def test_norm_validation(lib):
     def params(kind=0, perm=None, gamma=None, eps=1e-6):
         return pq.NormParams(kind, perm, gamma, None, None, 0, eps)
