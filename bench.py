@@ -251,6 +251,12 @@ def main():
                                                                   perm, gamma, operand=norm_op), nit)
     t_aln_q = time_calls(lambda i: pq.pq_norm_quantize_act_packed(pq.NORM_ADALN, fmt, g, pool[i % n_rot], 1e-6, ts_n,
                                                                   perm, None, mod_s, mod_b, per_mod, operand=norm_op), nit)
+    # the Hadamard variant (x H P) where the width has a construction
+    t_had = t_had_q = float("nan")
+    if K in (2 ** (K.bit_length() - 1), 12 * 2 ** max(0, (K // 12).bit_length() - 1), 20 * 2 ** max(0, (K // 20).bit_length() - 1)):
+        t_had = time_calls(lambda i: pq.pq_hadamard_reorder(pool[i % n_rot], perm, y=y_norm), nit)
+        t_had_q = time_calls(lambda i: pq.pq_hadamard_quantize_act_packed(fmt, g, pool[i % n_rot], ts_n, perm,
+                                                                          operand=norm_op), nit)
     t_floor_n = time_calls(lambda i: pq.pq_probe_stream(pool[i % n_rot], in_bytes, y_norm, in_bytes), nit)
     del pool, y_norm, norm_op
     # the calibration set as one buffer, rotating over enough copies to stay out of the caches
@@ -303,6 +309,10 @@ def main():
                                        "frac_hbm_peak": qbytes / t_rms_q / 1e9 / HBM_PEAK_GBS},
         "norm_quantize_act_adaln_cold": {"us": t_aln_q * 1e6, "gbs": qbytes / t_aln_q / 1e9,
                                          "frac_hbm_peak": qbytes / t_aln_q / 1e9 / HBM_PEAK_GBS},
+        "hadamard_reorder_cold": {"us": t_had * 1e6, "gbs": 2 * mbytes / t_had / 1e9,
+                                  "frac_hbm_peak": 2 * mbytes / t_had / 1e9 / HBM_PEAK_GBS},
+        "hadamard_quantize_act_cold": {"us": t_had_q * 1e6, "gbs": qbytes / t_had_q / 1e9,
+                                       "frac_hbm_peak": qbytes / t_had_q / 1e9 / HBM_PEAK_GBS},
         # same-run references (not part of the path)
         "reference_stream_norm_footprint_cold": {"us": t_floor_n * 1e6, "gbs": 2 * mbytes / t_floor_n / 1e9},
         "reference_stream_quantizer_footprint_cold": {"us": t_floor_q * 1e6, "gbs": qbytes / t_floor_q / 1e9},

@@ -82,8 +82,11 @@ __device__ __forceinline__ void wave_lds_sync() {
 // Sylvester matrix of order R along a digit of weight `inner` elements; n_fibres = K / R
 template <int R>
 __device__ __forceinline__ void sylvester_pass(float* slab, int inner, int n_fibres, int lane) {
+  // f / inner through a float reciprocal: f < 2^13 and the quotient's fractional part is at least
+  // 1 / (2 inner) away from an integer, far more than the rounding error of the product
+  const float inv_inner = 1.0f / (float)inner;
   for (int f = lane; f < n_fibres; f += 64) {
-    const int hi = f / inner, lo = f - hi * inner;
+    const int hi = (int)(((float)f + 0.5f) * inv_inner), lo = f - hi * inner;
     float* base = slab + hi * (R * inner) + lo;
     float v[R];
 #pragma unroll
@@ -131,11 +134,23 @@ __device__ __forceinline__ void paley_pass(float* slab, int n_fibres, int lane) 
     float v[M], o[M];
 #pragma unroll
     for (int b = 0; b < M; ++b) v[b] = base[b];
+    // a pair of inputs enters every output as +-(v0 + v1) or +-(v0 - v1): form both once, then each
+    // output is a signed sum of M / 2 terms instead of M
+    float sum[M / 2], dif[M / 2];
+#pragma unroll
+    for (int j = 0; j < M / 2; ++j) {
+      sum[j] = v[2 * j] + v[2 * j + 1];
+      dif[j] = v[2 * j] - v[2 * j + 1];
+    }
 #pragma unroll
     for (int b2 = 0; b2 < M; ++b2) {
       float acc = 0.0f;
 #pragma unroll
-      for (int b = 0; b < M; ++b) acc = paley_entry<M>(b, b2) > 0 ? acc + v[b] : acc - v[b];
+      for (int j = 0; j < M / 2; ++j) {
+        const int s0 = paley_entry<M>(2 * j, b2), s1 = paley_entry<M>(2 * j + 1, b2);
+        const float term = s0 == s1 ? sum[j] : dif[j];
+        acc = s0 > 0 ? acc + term : acc - term;
+      }
       o[b2] = acc;
     }
 #pragma unroll
