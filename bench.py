@@ -60,7 +60,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         log("bench.py: this build runs on one GPU only (every step of the path shards over token "
-            "rows without communication; see DESIGN.md). Run with --gpus 1.")
+            "rows without communication). Run with --gpus 1.")
         sys.exit(2)
 
     import torch

@@ -231,8 +231,8 @@ __global__ __launch_bounds__(512) void quant_error_kernel(TensorList xs, int row
             for (int j = 0; j < 8; ++j) {
               // The clip of the quantizer cannot act here: amax is the true maximum of the group, so
               // |x * inv| <= Q (1 + 3 * 2^-24) < Q + 1/2 and the rounding already lands on +-Q
-              // (inv = 0 gives 0).  Adding and subtracting 1.5 * 2^23 rounds to the nearest integer.
-              const float t = (v[rr][j] * s[rr].inv + 12582912.0f) - 12582912.0f;
+              // (inv = 0 gives 0).  v_rndne_f32 rounds to the nearest integer, ties to even.
+              const float t = __builtin_rintf(v[rr][j] * s[rr].inv);
               // v - s t is exact in binary32: for t != 0 both terms are multiples of the last place
               // of s and the difference is at most about s / 2, so it needs no more than 24 bits;
               // the fused multiply-add returns it unrounded
