@@ -57,7 +57,9 @@ typedef enum {
   PQ_OP_QUANTIZE_ACT = 3,
   PQ_OP_QGEMM = 4,
   PQ_OP_QUANT_ERROR = 5,
-  PQ_OP_SELECT_PERM_OUTPUT = 6
+  PQ_OP_SELECT_PERM_OUTPUT = 6,
+  PQ_OP_CHANNEL_STATS = 7,       /* M = rows, K                                   */
+  PQ_OP_ORDER = 8                /* K: pq_order_by_score, pq_order_random         */
 } pq_op;
 
 #define PQ_OK 0
@@ -291,6 +293,37 @@ int pq_qgemm_packed_f32(pq_format fmt, int group, const void* a_operand, const f
 int pq_qgemm_packed_bias(pq_format fmt, int group, const void* a_operand, const float* a_tensor_scale,
                          const void* w_operand, const float* w_tensor_scale, int64_t M, int64_t N, int64_t K,
                          const void* bias_bf16, void* y_bf16, int64_t ldy, void* stream);
+
+/*
+ * The other reorder criteria of the ablation (paper Tab. 2a: variance, absmax, round-robin, random; the
+ * paper names them without formulas, the readings are the library's).  A criterion supplies one
+ * non-negative statistic per channel and side that takes the place of the second moment in the joint
+ * score of Eq. 9: pq_select_perm accepts any such pair of arrays as act_sumsq / w_sumsq.
+ *
+ * pq_calib_channel_stats: per channel the sum (fp64, accumulated into sum[K]) and the largest magnitude
+ *   (fp32, folded into absmax[K] by max) of x, bf16 [rows, ld]; either output may be NULL.  Call once per
+ *   batch; workspace: pq_workspace_bytes(PQ_OP_CHANNEL_STATS, ., ., rows, 0, K, 0).
+ * pq_channel_statistic: the statistic of a criterion from those sums, out[K] fp64:
+ *   PQ_CRIT_VARIANCE  out = max(sumsq - sum^2 / n_rows, 0)   (n_rows times the biased variance)
+ *   PQ_CRIT_ABSMAX    out = absmax^2
+ * pq_order_by_score: the order of one alpha (Eq. 9, descending, ties in ascending channel order) without
+ *   the error evaluation.  workspace: pq_workspace_bytes(PQ_OP_ORDER, ., ., 0, 0, K, 0).
+ * pq_order_round_robin: deals the channels of `order` (best first) to the K / group groups in turn: rank r
+ *   goes to position (r mod (K/group)) * group + r / (K/group).  K % group == 0; order != perm_out.
+ * pq_order_random: a seeded permutation: channels sorted by splitmix64(seed + channel) >> 11, ascending,
+ *   equal hashes in ascending channel order.  workspace as for pq_order_by_score.
+ * All arrays are device memory; everything runs on `stream`.  Evaluate any order with pq_quant_error.
+ */
+typedef enum { PQ_CRIT_VARIANCE = 0, PQ_CRIT_ABSMAX = 1 } pq_criterion;
+int pq_calib_channel_stats(const void* x_bf16, int64_t rows, int64_t K, int64_t ld, double* sum, float* absmax,
+                           void* workspace, size_t workspace_bytes, void* stream);
+int pq_channel_statistic(pq_criterion kind, const double* sum, const double* sumsq, const float* absmax,
+                         int64_t n_rows, int64_t K, double* out, void* stream);
+int pq_order_by_score(const double* act_stat, const double* w_stat, int64_t K, double alpha, int32_t* perm_out,
+                      void* workspace, size_t workspace_bytes, void* stream);
+int pq_order_round_robin(const int32_t* order, int64_t K, int group, int32_t* perm_out, void* stream);
+int pq_order_random(uint64_t seed, int64_t K, int32_t* perm_out, void* workspace, size_t workspace_bytes,
+                    void* stream);
 
 /*
  * Dynamic per-tensor scale of the NVFP4 activation format (paper App. A.1: E4M3 block scales under an

@@ -57,6 +57,12 @@ size_t pq_workspace_bytes(pq_op op, pq_format fmt, int group, int64_t M, int64_t
     case PQ_OP_QUANT_ERROR:
       if (M <= 0) return 0;
       return quant_error_workspace_bytes(M);
+    case PQ_OP_CHANNEL_STATS:
+      if (M <= 0 || K <= 0) return 0;
+      return channel_stats_workspace_bytes(M, K);
+    case PQ_OP_ORDER:
+      if (K <= 0) return 0;
+      return random_order_workspace_bytes(K);
     case PQ_OP_SELECT_PERM_OUTPUT:
       if (M <= 0 || N <= 0 || K <= 0 || n_batches <= 0 || check_format(fmt, group, K) || K % 32) return 0;
       return select_output_workspace_bytes(fmt, group, M, N, K, n_batches);
@@ -331,6 +337,77 @@ int pq_quantize_act_packed(pq_format fmt, int group, const void* x, int64_t M, i
     return fail(PQ_ERR_WORKSPACE, "pq_quantize_act_packed: operand buffer of %zu bytes needed, %zu given", need,
                 operand_size);
   return run_quantize_packed(fmt, group, x, M, K, ld, tensor_scale, operand, codes, scales, as_stream(stream));
+}
+
+int pq_calib_channel_stats(const void* x, int64_t rows, int64_t K, int64_t ld, double* sum, float* absmax,
+                           void* workspace, size_t workspace_bytes, void* stream) {
+  if (!x || (!sum && !absmax)) return fail(PQ_ERR_NULL, "pq_calib_channel_stats: x and one of sum, absmax are required");
+  if (rows <= 0 || K <= 0) return fail(PQ_ERR_SHAPE, "pq_calib_channel_stats: rows=%lld K=%lld must be positive",
+                                        (long long)rows, (long long)K);
+  if (rows > (1 << 24) || K > (1 << 24)) return fail(PQ_ERR_SHAPE, "pq_calib_channel_stats: a dimension exceeds 2^24");
+  if (K % 8 || ld < K || ld % 8)
+    return fail(PQ_ERR_SHAPE, "pq_calib_channel_stats: K=%lld must be a multiple of 8, ld=%lld >= K and a multiple of 8",
+                (long long)K, (long long)ld);
+  if (!aligned16(x)) return fail(PQ_ERR_SHAPE, "pq_calib_channel_stats: x must be 16-byte aligned");
+  const size_t need = channel_stats_workspace_bytes(rows, K);
+  if (!workspace || workspace_bytes < need)
+    return fail(PQ_ERR_WORKSPACE, "pq_calib_channel_stats: workspace of %zu bytes needed, %zu given", need,
+                workspace ? workspace_bytes : (size_t)0);
+  return launch_channel_stats(x, rows, K, ld, sum, absmax, workspace, as_stream(stream));
+}
+
+int pq_channel_statistic(pq_criterion kind, const double* sum, const double* sumsq, const float* absmax,
+                         int64_t n_rows, int64_t K, double* out, void* stream) {
+  if (!out) return fail(PQ_ERR_NULL, "pq_channel_statistic: out is NULL");
+  if (K <= 0) return fail(PQ_ERR_SHAPE, "pq_channel_statistic: K=%lld must be positive", (long long)K);
+  if (kind == PQ_CRIT_VARIANCE) {
+    if (!sum || !sumsq) return fail(PQ_ERR_NULL, "pq_channel_statistic: the variance needs sum and sumsq");
+    if (n_rows <= 0) return fail(PQ_ERR_SHAPE, "pq_channel_statistic: n_rows=%lld must be positive", (long long)n_rows);
+    return launch_channel_variance(sum, sumsq, n_rows, K, out, as_stream(stream));
+  }
+  if (kind == PQ_CRIT_ABSMAX) {
+    if (!absmax) return fail(PQ_ERR_NULL, "pq_channel_statistic: the absmax criterion needs absmax");
+    return launch_channel_absmax_sq(absmax, K, out, as_stream(stream));
+  }
+  return fail(PQ_ERR_FORMAT, "pq_channel_statistic: unknown criterion %d", (int)kind);
+}
+
+static int check_order_ws(const char* who, int64_t K, const int32_t* perm_out, const void* workspace,
+                          size_t workspace_bytes) {
+  if (!perm_out) return fail(PQ_ERR_NULL, "%s: perm_out is NULL", who);
+  if (K <= 0 || K > 65536) return fail(PQ_ERR_SHAPE, "%s: K=%lld outside 1..65536", who, (long long)K);
+  const size_t need = random_order_workspace_bytes(K);
+  if (!workspace || workspace_bytes < need)
+    return fail(PQ_ERR_WORKSPACE, "%s: workspace of %zu bytes needed, %zu given", who, need,
+                workspace ? workspace_bytes : (size_t)0);
+  return PQ_OK;
+}
+
+int pq_order_by_score(const double* act_stat, const double* w_stat, int64_t K, double alpha, int32_t* perm_out,
+                      void* workspace, size_t workspace_bytes, void* stream) {
+  if (!act_stat || !w_stat) return fail(PQ_ERR_NULL, "pq_order_by_score: a statistic array is NULL");
+  int rc = check_order_ws("pq_order_by_score", K, perm_out, workspace, workspace_bytes);
+  if (rc) return rc;
+  if (!(alpha >= 0.0 && alpha <= 1.0)) return fail(PQ_ERR_SHAPE, "pq_order_by_score: alpha=%g outside [0, 1]", alpha);
+  double* keys = (double*)workspace;
+  int32_t* rank = (int32_t*)((char*)workspace + align_up((size_t)K * 8, 256));
+  return launch_candidate_orders(act_stat, w_stat, K, &alpha, 1, keys, rank, perm_out, as_stream(stream));
+}
+
+int pq_order_round_robin(const int32_t* order, int64_t K, int group, int32_t* perm_out, void* stream) {
+  if (!order || !perm_out) return fail(PQ_ERR_NULL, "pq_order_round_robin: a required pointer is NULL");
+  if (order == perm_out) return fail(PQ_ERR_SHAPE, "pq_order_round_robin: order and perm_out must differ");
+  if (K <= 0 || group <= 0 || K % group)
+    return fail(PQ_ERR_SHAPE, "pq_order_round_robin: K=%lld must be a positive multiple of group=%d", (long long)K, group);
+  if (K > (1 << 24)) return fail(PQ_ERR_SHAPE, "pq_order_round_robin: K exceeds 2^24");
+  return launch_round_robin(order, K, group, perm_out, as_stream(stream));
+}
+
+int pq_order_random(uint64_t seed, int64_t K, int32_t* perm_out, void* workspace, size_t workspace_bytes,
+                    void* stream) {
+  int rc = check_order_ws("pq_order_random", K, perm_out, workspace, workspace_bytes);
+  if (rc) return rc;
+  return launch_random_order(seed, K, perm_out, workspace, as_stream(stream));
 }
 
 int pq_dynamic_tensor_scale(const void* x, int64_t M, int64_t K, int64_t ld, float* tensor_scale_out,

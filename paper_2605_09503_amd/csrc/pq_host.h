@@ -48,6 +48,15 @@ int run_select(pq_format fmt, int group, const double* act_sumsq, const double* 
 int launch_candidate_orders(const double* act_sumsq, const double* w_sumsq, int64_t K, const double* alphas,
                             int n_alpha, double* keys, int32_t* rank, int32_t* cands, hipStream_t st);
 int launch_identity_order(int32_t* perm, int64_t K, hipStream_t st);
+int launch_round_robin(const int32_t* order, int64_t K, int group, int32_t* perm, hipStream_t st);
+size_t random_order_workspace_bytes(int64_t K);      // also enough for one candidate order (keys + ranks)
+int launch_random_order(uint64_t seed, int64_t K, int32_t* perm, void* ws, hipStream_t st);
+size_t channel_stats_workspace_bytes(int64_t rows, int64_t K);
+int launch_channel_stats(const void* x, int64_t rows, int64_t K, int64_t ld, double* sum, float* absmax, void* ws,
+                         hipStream_t st);
+int launch_channel_variance(const double* sum, const double* sumsq, int64_t n_rows, int64_t K, double* out,
+                            hipStream_t st);
+int launch_channel_absmax_sq(const float* absmax, int64_t K, double* out, hipStream_t st);
 size_t select_output_workspace_bytes(pq_format fmt, int group, int64_t M, int64_t N, int64_t K, int n_batches);
 int run_select_output(pq_format fmt, int group, const double* act_sumsq, const double* w_sumsq, int64_t K,
                       const void* const* x_calib, int n_batches, int64_t M, const void* w, int64_t N,

@@ -192,4 +192,120 @@ int launch_moments(const void* const* xs, int n_batches, int64_t rows, int64_t K
   return PQ_OK;
 }
 
+// ---------------------------------------------------------------- per-channel sum and absmax
+// Statistics of the alternative reorder criteria (paper Tab. 2a: variance, absmax): per column the
+// sum (fp64) and the largest magnitude.  Same decomposition as above: partials per row slab, then a
+// second kernel that folds them in slab order.
+__global__ __launch_bounds__(64 * kTy) void channel_stats_partial_kernel(const uint16_t* __restrict__ x, int64_t rows,
+                                                                        int64_t K, int64_t ld, int rows_per_slab,
+                                                                        double* __restrict__ psum,
+                                                                        float* __restrict__ pmax) {
+  __shared__ double red[kTy][64][kColsPerLane + 1];
+  __shared__ uint32_t redm[kTy][64][kColsPerLane + 1];
+  const int lane = threadIdx.x, ty = threadIdx.y;
+  const int64_t col = (int64_t)blockIdx.x * kColsPerBlock + lane * kColsPerLane;
+  const int64_t r0 = (int64_t)blockIdx.y * rows_per_slab;
+  const int64_t r1 = r0 + rows_per_slab < rows ? r0 + rows_per_slab : rows;
+  double acc[kColsPerLane];
+  uint32_t amax[kColsPerLane];           // |bf16| bit patterns order like the magnitudes
+#pragma unroll
+  for (int c = 0; c < kColsPerLane; ++c) acc[c] = 0.0, amax[c] = 0u;
+  if (col < K) {
+    const uint16_t* p = x + col;
+    for (int64_t r = r0 + ty; r < r1; r += kTy) {
+      const uint4 v = *reinterpret_cast<const uint4*>(p + r * ld);
+      const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        acc[2 * j] += (double)bf16_lo(w[j]);
+        acc[2 * j + 1] += (double)bf16_hi(w[j]);
+        amax[2 * j] = max(amax[2 * j], w[j] & 0x7FFFu);
+        amax[2 * j + 1] = max(amax[2 * j + 1], (w[j] >> 16) & 0x7FFFu);
+      }
+    }
+  }
+#pragma unroll
+  for (int c = 0; c < kColsPerLane; ++c) red[ty][lane][c] = acc[c], redm[ty][lane][c] = amax[c];
+  __syncthreads();
+  if (ty < kColsPerLane && col < K) {
+    double s = 0.0;
+    uint32_t m = 0u;
+#pragma unroll
+    for (int w = 0; w < kTy; ++w) s += red[w][lane][ty], m = max(m, redm[w][lane][ty]);
+    psum[(int64_t)blockIdx.y * K + col + ty] = s;
+    pmax[(int64_t)blockIdx.y * K + col + ty] = as_f32(m << 16);
+  }
+}
+
+__global__ __launch_bounds__(256) void channel_stats_finish_kernel(const double* __restrict__ psum,
+                                                                  const float* __restrict__ pmax, int slabs,
+                                                                  int64_t K, double* __restrict__ sum,
+                                                                  float* __restrict__ absmax) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= K) return;
+  double s = 0.0;
+  float m = 0.0f;
+  for (int r = 0; r < slabs; ++r) {
+    s += psum[(int64_t)r * K + i];
+    m = fmaxf(m, pmax[(int64_t)r * K + i]);
+  }
+  if (sum) sum[i] += s;
+  if (absmax) absmax[i] = fmaxf(absmax[i], m);
+}
+
+static int channel_stats_slabs(int64_t rows, int64_t K) {
+  const int64_t col_blocks = (K + kColsPerBlock - 1) / kColsPerBlock;
+  int64_t want = (1024 + col_blocks - 1) / col_blocks;
+  const int64_t max_slabs = (rows + 4 * kTy - 1) / (4 * kTy);
+  if (want > max_slabs) want = max_slabs;
+  if (want < 1) want = 1;
+  if (want > 256) want = 256;
+  return (int)want;
+}
+
+size_t channel_stats_workspace_bytes(int64_t rows, int64_t K) {
+  const int slabs = channel_stats_slabs(rows, K);
+  return align_up((size_t)slabs * K * sizeof(double), 256) + align_up((size_t)slabs * K * sizeof(float), 256);
+}
+
+int launch_channel_stats(const void* x, int64_t rows, int64_t K, int64_t ld, double* sum, float* absmax, void* ws,
+                         hipStream_t st) {
+  const int slabs = channel_stats_slabs(rows, K);
+  const int rows_per_slab = (int)((rows + slabs - 1) / slabs);
+  double* psum = (double*)ws;
+  float* pmax = (float*)((char*)ws + align_up((size_t)slabs * K * sizeof(double), 256));
+  hipLaunchKernelGGL(channel_stats_partial_kernel, dim3((unsigned)((K + kColsPerBlock - 1) / kColsPerBlock), (unsigned)slabs),
+                     dim3(64, kTy), 0, st, (const uint16_t*)x, rows, K, ld, rows_per_slab, psum, pmax);
+  hipLaunchKernelGGL(channel_stats_finish_kernel, dim3((unsigned)((K + 255) / 256)), dim3(256), 0, st,
+                     (const double*)psum, (const float*)pmax, slabs, K, sum, absmax);
+  return check_hip(hipGetLastError(), "channel_stats kernels");
+}
+
+// out[i] = max(sumsq[i] - sum[i]^2 / n, 0): n times the biased variance of channel i
+__global__ __launch_bounds__(256) void channel_variance_kernel(const double* __restrict__ sum,
+                                                              const double* __restrict__ sumsq, double n, int64_t K,
+                                                              double* __restrict__ out) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < K) out[i] = fmax(sumsq[i] - sum[i] * sum[i] / n, 0.0);
+}
+
+// out[i] = absmax[i]^2 as a double (the statistic of the absmax criterion, in the units of a second moment)
+__global__ __launch_bounds__(256) void channel_absmax_sq_kernel(const float* __restrict__ absmax, int64_t K,
+                                                               double* __restrict__ out) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < K) out[i] = (double)absmax[i] * (double)absmax[i];
+}
+
+int launch_channel_variance(const double* sum, const double* sumsq, int64_t n_rows, int64_t K, double* out,
+                            hipStream_t st) {
+  hipLaunchKernelGGL(channel_variance_kernel, dim3((unsigned)((K + 255) / 256)), dim3(256), 0, st, sum, sumsq,
+                     (double)n_rows, K, out);
+  return check_hip(hipGetLastError(), "channel_variance_kernel");
+}
+
+int launch_channel_absmax_sq(const float* absmax, int64_t K, double* out, hipStream_t st) {
+  hipLaunchKernelGGL(channel_absmax_sq_kernel, dim3((unsigned)((K + 255) / 256)), dim3(256), 0, st, absmax, K, out);
+  return check_hip(hipGetLastError(), "channel_absmax_sq_kernel");
+}
+
 }  // namespace pq

@@ -476,6 +476,47 @@ int launch_candidate_orders(const double* act_sumsq, const double* w_sumsq, int6
   return check_hip(hipGetLastError(), "key/rank kernels");
 }
 
+// ---- orders of the ablation (paper Tab. 2a) that are not a sort by a statistic
+// round-robin: rank r of `order` goes to group r mod (K / g), slot r div (K / g)
+__global__ __launch_bounds__(256) void round_robin_kernel(const int32_t* __restrict__ order, int K, int g,
+                                                         int32_t* __restrict__ perm) {
+  const int r = blockIdx.x * 256 + threadIdx.x;
+  if (r >= K) return;
+  const int n_groups = K / g;
+  perm[(r % n_groups) * g + r / n_groups] = order[r];
+}
+
+// random: key[i] = -(splitmix64(seed + i) >> 11) as a double (53 bits: exact), so that the descending
+// stable sort used for the scores gives ascending hashes with ties in ascending channel order
+__global__ __launch_bounds__(256) void random_key_kernel(uint64_t seed, int K, double* __restrict__ keys,
+                                                        int32_t* __restrict__ rank) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= K) return;
+  uint64_t z = seed + (uint64_t)i + 0x9E3779B97F4A7C15ull;
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+  z = z ^ (z >> 31);
+  keys[i] = -(double)(z >> 11);
+  rank[i] = 0;
+}
+
+int launch_round_robin(const int32_t* order, int64_t K, int group, int32_t* perm, hipStream_t st) {
+  hipLaunchKernelGGL(round_robin_kernel, dim3((unsigned)((K + 255) / 256)), dim3(256), 0, st, order, (int)K, group, perm);
+  return check_hip(hipGetLastError(), "round_robin_kernel");
+}
+
+size_t random_order_workspace_bytes(int64_t K) { return align_up((size_t)K * 8, 256) + align_up((size_t)K * 4, 256); }
+
+int launch_random_order(uint64_t seed, int64_t K, int32_t* perm, void* ws, hipStream_t st) {
+  double* keys = (double*)ws;
+  int32_t* rank = (int32_t*)((char*)ws + align_up((size_t)K * 8, 256));
+  const unsigned kb = (unsigned)((K + 255) / 256);
+  hipLaunchKernelGGL(random_key_kernel, dim3(kb), dim3(256), 0, st, seed, (int)K, keys, rank);
+  hipLaunchKernelGGL(rank_count_kernel, dim3(kb, rank_chunks(K), 1), dim3(256), 0, st, keys, (int)K, rank);
+  hipLaunchKernelGGL(rank_scatter_kernel, dim3(kb, 1), dim3(256), 0, st, rank, (int)K, perm);
+  return check_hip(hipGetLastError(), "random order kernels");
+}
+
 int launch_identity_order(int32_t* perm, int64_t K, hipStream_t st) {
   hipLaunchKernelGGL(iota_kernel, dim3((unsigned)((K + 255) / 256)), dim3(256), 0, st, perm, (int)K);
   return check_hip(hipGetLastError(), "iota_kernel");

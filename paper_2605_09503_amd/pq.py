@@ -16,7 +16,8 @@ import torch
 
 FMT_NVFP4, FMT_INT4, FMT_INT3 = 0, 1, 2
 OP_CALIB_MOMENTS, OP_SELECT_PERM, OP_QUANTIZE_WEIGHTS, OP_QUANTIZE_ACT, OP_QGEMM, OP_QUANT_ERROR, \
-    OP_SELECT_PERM_OUTPUT = range(7)
+    OP_SELECT_PERM_OUTPUT, OP_CHANNEL_STATS, OP_ORDER = range(9)
+CRIT_VARIANCE, CRIT_ABSMAX = 0, 1
 MAX_ALPHAS = 15
 DEFAULT_ALPHAS = (0.0, 0.2, 0.4, 0.6, 0.8, 1.0)
 
@@ -87,6 +88,11 @@ def load():
     lib.pq_qgemm_packed.argtypes = packed_args
     lib.pq_qgemm_packed_f32.argtypes = packed_args
     lib.pq_qgemm_packed_bias.argtypes = [i32, i32, vp, vp, vp, vp, i64, i64, i64, vp, vp, i64, vp]
+    lib.pq_calib_channel_stats.argtypes = [vp, i64, i64, i64, vp, vp, vp, sz, vp]
+    lib.pq_channel_statistic.argtypes = [i32, vp, vp, vp, i64, i64, vp, vp]
+    lib.pq_order_by_score.argtypes = [vp, vp, i64, C.c_double, vp, vp, sz, vp]
+    lib.pq_order_round_robin.argtypes = [vp, i64, i32, vp, vp]
+    lib.pq_order_random.argtypes = [C.c_uint64, i64, vp, vp, sz, vp]
     lib.pq_hadamard_reorder.argtypes = [vp, vp, i64, i64, i64, vp, i64, vp]
     lib.pq_hadamard_quantize_act_packed.argtypes = [vp, i32, i32, vp, i64, i64, i64, vp, vp, sz, vp, i64, vp]
     lib.pq_dynamic_tensor_scale.argtypes = [vp, i64, i64, i64, vp, vp]
@@ -312,6 +318,48 @@ def pq_quantize_act_packed(fmt: int, group: int, x: torch.Tensor, tensor_scale: 
     _check(load().pq_quantize_act_packed(fmt, group, _ptr(x), M, K, x.stride(0), _ptr(tensor_scale),
                                          _ptr(operand), operand.numel(), _ptr(codes), _ptr(scales), _stream()))
     return operand
+
+
+def pq_calib_channel_stats(x: torch.Tensor, total: Optional[torch.Tensor], absmax: Optional[torch.Tensor],
+                           K: Optional[int] = None, workspace: Optional[torch.Tensor] = None) -> None:
+    """Per channel: sum (fp64, accumulated into `total`) and largest magnitude (fp32, max into `absmax`)."""
+    rows = x.shape[0]
+    K = x.shape[1] if K is None else K
+    if workspace is None:
+        workspace = _workspace(pq_workspace_bytes(OP_CHANNEL_STATS, 0, 0, rows, 0, K), x.device)
+    _check(load().pq_calib_channel_stats(_ptr(x), rows, K, x.stride(0), _ptr(total), _ptr(absmax), _ptr(workspace),
+                                         workspace.numel(), _stream()))
+
+
+def pq_channel_statistic(kind: int, total, sumsq, absmax, n_rows: int, out: torch.Tensor) -> torch.Tensor:
+    _check(load().pq_channel_statistic(kind, _ptr(total), _ptr(sumsq), _ptr(absmax), n_rows, out.numel(), _ptr(out),
+                                       _stream()))
+    return out
+
+
+def _order_ws(K: int, device, workspace):
+    return workspace if workspace is not None else _workspace(pq_workspace_bytes(OP_ORDER, 0, 0, 0, 0, K), device)
+
+
+def pq_order_by_score(act_stat: torch.Tensor, w_stat: torch.Tensor, alpha: float, perm_out: torch.Tensor,
+                      workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    K = act_stat.numel()
+    ws = _order_ws(K, act_stat.device, workspace)
+    _check(load().pq_order_by_score(_ptr(act_stat), _ptr(w_stat), K, float(alpha), _ptr(perm_out), _ptr(ws),
+                                    ws.numel(), _stream()))
+    return perm_out
+
+
+def pq_order_round_robin(order: torch.Tensor, group: int, perm_out: torch.Tensor) -> torch.Tensor:
+    _check(load().pq_order_round_robin(_ptr(order), order.numel(), group, _ptr(perm_out), _stream()))
+    return perm_out
+
+
+def pq_order_random(seed: int, perm_out: torch.Tensor, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    K = perm_out.numel()
+    ws = _order_ws(K, perm_out.device, workspace)
+    _check(load().pq_order_random(int(seed), K, _ptr(perm_out), _ptr(ws), ws.numel(), _stream()))
+    return perm_out
 
 
 def pq_dynamic_tensor_scale(x: torch.Tensor, tensor_scale_out: Optional[torch.Tensor] = None,

@@ -193,6 +193,31 @@ def test_select_output_error_validation(lib):
     assert f(*args(size=16)) == PQ_ERR_WORKSPACE
 
 
+def test_criteria_validation(lib):
+    w = lib.pq_workspace_bytes
+    assert w(pq.OP_CHANNEL_STATS, 0, 0, 4608, 0, 3072, 0) >= 3072 * 12 and w(pq.OP_CHANNEL_STATS, 0, 0, 0, 0, 64, 0) == 0
+    assert w(pq.OP_ORDER, 0, 0, 0, 0, 3072, 0) >= 3072 * 12
+    f = lib.pq_calib_channel_stats
+    assert f(None, 8, 64, 64, FAKE, FAKE, FAKE, 1 << 20, None) == PQ_ERR_NULL
+    assert f(FAKE, 8, 64, 64, None, None, FAKE, 1 << 20, None) == PQ_ERR_NULL
+    assert f(FAKE, 8, 60, 64, FAKE, None, FAKE, 1 << 20, None) == PQ_ERR_SHAPE
+    assert f(FAKE, 8, 64, 64, FAKE, None, FAKE, 8, None) == PQ_ERR_WORKSPACE
+    s = lib.pq_channel_statistic
+    assert s(0, None, FAKE, None, 8, 64, FAKE, None) == PQ_ERR_NULL          # variance needs the sums
+    assert s(1, None, None, None, 8, 64, FAKE, None) == PQ_ERR_NULL          # absmax criterion needs absmax
+    assert s(0, FAKE, FAKE, None, 0, 64, FAKE, None) == PQ_ERR_SHAPE
+    assert s(7, FAKE, FAKE, FAKE, 8, 64, FAKE, None) == PQ_ERR_FORMAT
+    o = lib.pq_order_by_score
+    assert o(None, FAKE, 64, 0.5, FAKE, FAKE, 1 << 20, None) == PQ_ERR_NULL
+    assert o(FAKE, FAKE, 64, 1.5, FAKE, FAKE, 1 << 20, None) == PQ_ERR_SHAPE
+    assert o(FAKE, FAKE, 64, 0.5, FAKE, FAKE, 8, None) == PQ_ERR_WORKSPACE
+    r = lib.pq_order_round_robin
+    assert r(FAKE, 96, 64, C.c_void_p(0x2000), None) == PQ_ERR_SHAPE         # K % group
+    assert r(FAKE, 64, 16, FAKE, None) == PQ_ERR_SHAPE                       # in place
+    assert lib.pq_order_random(1, 64, None, FAKE, 1 << 20, None) == PQ_ERR_NULL
+    assert lib.pq_order_random(1, 1 << 20, FAKE, FAKE, 1 << 30, None) == PQ_ERR_SHAPE
+
+
 def test_hadamard_validation(lib):
     f = lib.pq_hadamard_reorder
     assert f(None, None, 8, 64, 64, FAKE, 64, None) == PQ_ERR_NULL
