@@ -138,3 +138,39 @@ def test_hadamard_then_reorder_layer_lowers_the_output_error():
     got = OF.bf16_bits_to_f64(_host_bits(y))
     scale = np.sqrt(np.mean(y_ref ** 2))
     assert np.abs(got - y_ref).max() <= 0.03 * scale + 2.0 ** -8 * np.abs(y_ref).max()
+
+
+def test_forward_path_replays_from_a_captured_graph():
+    """The forward entry points allocate nothing and never synchronise, so a caller can capture them in a
+    graph: three replays on refreshed inputs, with eager work and synchronisations in between, each equal
+    to the eager result bit for bit."""
+    M, N, K, fmt, g = 200, 136, 1024, pq.FMT_INT4, 64
+    rng = np.random.default_rng(9996)
+    perm_d = torch.from_numpy(rng.permutation(K).astype(np.int32)).to(DEV)
+    gamma = _dev(_bits(1.0 + 0.2 * rng.standard_normal(K)))
+    bias = _dev(_bits(0.5 * rng.standard_normal(N)))
+    w_op, Tw = _weights_operand(fmt, g, _bits(0.03 * rng.standard_normal((N, K))), perm_d)
+    one = torch.ones(1, dtype=torch.float32, device=DEV)
+    x = torch.empty((M, K), dtype=torch.bfloat16, device=DEV)
+    a_op = torch.zeros(pq.pq_operand_bytes(fmt, g, M, K), dtype=torch.uint8, device=DEV)
+    y = torch.empty((M, N), dtype=torch.bfloat16, device=DEV)
+
+    def forward(out):
+        pq.pq_norm_quantize_act_packed(pq.NORM_RMS, fmt, g, x, 1e-6, one, perm_d, gamma, operand=a_op)
+        pq.pq_qgemm_packed_bias(fmt, g, a_op, one, w_op, Tw, bias, out, M, N, K)
+
+    x.copy_(_dev(_bits(rng.standard_normal((M, K)))))
+    forward(y)                                   # warm-up outside the capture (first-use set-up of the kernels)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        forward(y)
+    for i in range(3):
+        x.copy_(_dev(_bits(rng.standard_normal((M, K)) * (1.0 + i))))
+        y_eager = torch.empty_like(y)
+        forward(y_eager)
+        torch.cuda.synchronize()
+        y.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y.view(torch.int16), y_eager.view(torch.int16)), "replay %d differs" % i
