@@ -4,7 +4,11 @@
  * The library implements the data-parallel hot path of PermuQuant: calibration statistics
  * and permutation selection (paper Sec. 3.2-3.3), offline weight quantization in the
  * selected channel order, dynamic per-group activation quantization, and the low-bit GEMM
- * of the reordered quantized linear layer (paper Eq. 8).
+ * of the reordered quantized linear layer (paper Eq. 8).  Around that path it offers the steps
+ * the paper describes next to it: the normalisation layer that absorbs the activation reorder
+ * (App. C), the Hadamard variant PermuQuant-H (App. D), the layer-output reading of the
+ * calibration metric, a dynamic NVFP4 tensor scale, the layer's bias in the GEMM epilogue and
+ * the alternative reorder criteria of the ablation (Tab. 2a).
  *
  * Conventions
  *   - X is [M, K] row-major (tokens x input channels), W is [N, K] row-major (output x input
