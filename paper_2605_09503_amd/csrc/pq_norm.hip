@@ -44,6 +44,7 @@ struct NormArgs {
   float eps;
   uint16_t* y;                  // bf16 [rows][ldy] normalised, reordered output, or null
   int64_t ldy;
+  int rows_seq;                 // rows a team of waves takes one after the other (wide rows)
   int had_pow2, had_m;          // Hadamard: K = had_pow2 * had_m, had_m in {1, 12, 20}
   float had_scale;              // 1 / sqrt(K)
 };
@@ -79,13 +80,21 @@ __device__ __forceinline__ void wave_lds_sync() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+// A row is worked on by a team of TEAM waves: one wave, which only has to order its own LDS
+// traffic, or (wide rows) all waves of the workgroup, which meet at a workgroup barrier.
+template <int TEAM>
+__device__ __forceinline__ void team_sync() {
+  if constexpr (TEAM == 1) wave_lds_sync();
+  else __syncthreads();
+}
+
 // Sylvester matrix of order R along a digit of weight `inner` elements; n_fibres = K / R
-template <int R>
+template <int R, int TEAM>
 __device__ __forceinline__ void sylvester_pass(float* slab, int inner, int n_fibres, int lane) {
   // f / inner through a float reciprocal: f < 2^13 and the quotient's fractional part is at least
   // 1 / (2 inner) away from an integer, far more than the rounding error of the product
   const float inv_inner = 1.0f / (float)inner;
-  for (int f = lane; f < n_fibres; f += 64) {
+  for (int f = lane; f < n_fibres; f += 64 * TEAM) {
     const int hi = (int)(((float)f + 0.5f) * inv_inner), lo = f - hi * inner;
     float* base = slab + hi * (R * inner) + lo;
     float v[R];
@@ -104,7 +113,7 @@ __device__ __forceinline__ void sylvester_pass(float* slab, int inner, int n_fib
 #pragma unroll
     for (int t = 0; t < R; ++t) base[t * inner] = v[t];
   }
-  wave_lds_sync();
+  team_sync<TEAM>();
 }
 
 // quadratic character mod Q (Q prime): +1 for a non-zero square, -1 otherwise, 0 for 0
@@ -127,9 +136,9 @@ __host__ __device__ constexpr int paley_entry(int b, int b2) {
 }
 
 // y[b2] = sum_b x[b] P[b][b2] along the last digit (M contiguous elements per fibre)
-template <int M>
+template <int M, int TEAM>
 __device__ __forceinline__ void paley_pass(float* slab, int n_fibres, int lane) {
-  for (int f = lane; f < n_fibres; f += 64) {
+  for (int f = lane; f < n_fibres; f += 64 * TEAM) {
     float* base = slab + f * M;
     float v[M], o[M];
 #pragma unroll
@@ -156,25 +165,27 @@ __device__ __forceinline__ void paley_pass(float* slab, int n_fibres, int lane) 
 #pragma unroll
     for (int b = 0; b < M; ++b) base[b] = o[b];
   }
-  wave_lds_sync();
+  team_sync<TEAM>();
 }
 
+// `lane` is the thread's index inside its team (0 .. 64 TEAM - 1)
+template <int TEAM>
 __device__ __forceinline__ void hadamard_row(float* slab, int K, int pow2, int m, int lane) {
-  if (m == 12) paley_pass<12>(slab, pow2, lane);
-  if (m == 20) paley_pass<20>(slab, pow2, lane);
+  if (m == 12) paley_pass<12, TEAM>(slab, pow2, lane);
+  if (m == 20) paley_pass<20, TEAM>(slab, pow2, lane);
   int inner = m;                       // weight of the current Sylvester digit, in elements
   int rem = pow2;
   while (rem >= 16) {
-    sylvester_pass<16>(slab, inner, K / 16, lane);
+    sylvester_pass<16, TEAM>(slab, inner, K / 16, lane);
     inner *= 16;
     rem /= 16;
   }
-  if (rem == 8) sylvester_pass<8>(slab, inner, K / 8, lane);
-  if (rem == 4) sylvester_pass<4>(slab, inner, K / 4, lane);
-  if (rem == 2) sylvester_pass<2>(slab, inner, K / 2, lane);
+  if (rem == 8) sylvester_pass<8, TEAM>(slab, inner, K / 8, lane);
+  if (rem == 4) sylvester_pass<4, TEAM>(slab, inner, K / 4, lane);
+  if (rem == 2) sylvester_pass<2, TEAM>(slab, inner, K / 2, lane);
 }
 
-template <int FMT, int G, int NORM>
+template <int FMT, int G, int NORM, int TEAM>
 __global__ __launch_bounds__(64 * kNormMaxWaves) void norm_rows_kernel(
     const uint16_t* __restrict__ x, int64_t rows, int64_t K, int64_t ld, const float* __restrict__ tensor_scale,
     int64_t steps, int64_t units, uint8_t* __restrict__ p_codes, uint16_t* __restrict__ p_scales,
@@ -185,92 +196,127 @@ __global__ __launch_bounds__(64 * kNormMaxWaves) void norm_rows_kernel(
   // chunks a lane works on at a time (AdaLN holds more per chunk: two keep it at five waves per SIMD)
   constexpr int kBatch = NORM == kNormAdaLn ? 2 : 3;
   static_assert(LPG >= 1 && LPG <= 64, "a group lies inside one wave-wide run of chunks");
-  // dynamic LDS: [vectors: K bf16 (RMSNorm) or K words (AdaLN)] [per wave: K bf16 row slab]
-  //              [per wave, INT: `units` fp32 group maxima]
+  // dynamic LDS: [vectors: K bf16 (RMSNorm) or K words (AdaLN)] [per row: K bf16 (Hadamard: fp32) slab]
+  //              [per row, INT: `units` fp32 group maxima] [per wave: 4 floats for team reductions]
+  // TEAM == 1: every wave owns a row.  TEAM > 1: the workgroup is one team of TEAM waves and owns one row.
+  constexpr int TL = 64 * TEAM;                              // threads of a team
   extern __shared__ __align__(16) unsigned char lds_raw[];
   const int tid = threadIdx.x, lane = tid & 63, n_waves = blockDim.x >> 6;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int tl = TEAM == 1 ? lane : tid;                     // index inside the team
+  const int slot = TEAM == 1 ? wave : 0;                     // row slot inside the workgroup
+  const int rows_per_wg = TEAM == 1 ? n_waves : 1;
   const int Ki = (int)K;
   const int k_chunks = Ki / 8;                               // chunks that exist
   const int n_chunks = (int)steps * 8;                       // chunks the panel holds (a half step past K included)
   const int n_units = (int)units;
-  const int64_t row0 = (int64_t)blockIdx.x * n_waves;
-  const int64_t row = row0 + wave;
+  // TEAM > 1: the workgroup takes na.rows_seq consecutive rows one after the other, so that the vectors
+  // are staged once for all of them
+  const int rows_seq = TEAM == 1 ? 1 : na.rows_seq;
+  const int64_t row0 = (int64_t)blockIdx.x * (TEAM == 1 ? rows_per_wg : rows_seq);
 
   uint16_t* vec_g = reinterpret_cast<uint16_t*>(lds_raw);
   uint32_t* vec_sb = reinterpret_cast<uint32_t*>(lds_raw);
   constexpr int kSlabElem = NORM == kHadamard ? 4 : 2;       // Hadamard rows are held as fp32
   const size_t vec_bytes = NORM == kHadamard ? 0 : (size_t)Ki * (NORM == kNormRms ? 2 : 4);
-  uint16_t* slab = reinterpret_cast<uint16_t*>(lds_raw + vec_bytes) + (size_t)wave * Ki;
-  float* slab_f = reinterpret_cast<float*>(lds_raw + vec_bytes) + (size_t)wave * Ki;
-  float* h_lds = reinterpret_cast<float*>(lds_raw + vec_bytes + (size_t)n_waves * Ki * kSlabElem) + (size_t)wave * n_units;
+  uint16_t* slab = reinterpret_cast<uint16_t*>(lds_raw + vec_bytes) + (size_t)slot * Ki;
+  float* slab_f = reinterpret_cast<float*>(lds_raw + vec_bytes) + (size_t)slot * Ki;
+  const size_t slab_bytes = (size_t)rows_per_wg * Ki * kSlabElem;
+  float* h_lds = reinterpret_cast<float*>(lds_raw + vec_bytes + slab_bytes) + (size_t)slot * n_units;
+  float* team_red = reinterpret_cast<float*>(lds_raw + vec_bytes + slab_bytes) + (size_t)(IS_INT ? rows_per_wg * n_units : 0);
+  // sum / maximum over the team, the same value in every thread (fixed order of the waves)
+  auto team_sum = [&](float v) -> float {
+    v = wave_sum_f32(v);
+    if constexpr (TEAM > 1) {
+      if (lane == 0) team_red[wave] = v;
+      __syncthreads();
+      float t = 0.0f;
+#pragma unroll
+      for (int w = 0; w < TEAM; ++w) t += team_red[w];
+      __syncthreads();
+      v = t;
+    }
+    return v;
+  };
+  auto team_max = [&](float v) -> float {
+    v = wave_max(v);
+    if constexpr (TEAM > 1) {
+      if (lane == 0) team_red[wave] = v;
+      __syncthreads();
+      float t = 0.0f;
+#pragma unroll
+      for (int w = 0; w < TEAM; ++w) t = fmaxf(t, team_red[w]);
+      __syncthreads();
+      v = t;
+    }
+    return v;
+  };
 
   // ---- the vectors of the first row's sample, reordered, into LDS (all threads).  Scattered
   // 2-byte loads from memory cost the texture addresser a cycle per lane, so the vectors are first
   // copied as they lie (whole lines) into the space of the row slabs, which is still free, and
-  // reordered from there with LDS reads.  (If a single slab is smaller than the two AdaLN vectors,
-  // they are gathered from memory instead.)
+  // reordered from there with LDS reads, one vector at a time.
   int64_t mod0 = 0;
   if constexpr (NORM == kNormAdaLn) mod0 = row0 / na.rows_per_mod;
   if constexpr (NORM != kHadamard) {
     const uint16_t* v0 = NORM == kNormRms ? na.gamma : (na.mod_scale ? na.mod_scale + mod0 * K : nullptr);
     const uint16_t* v1 = NORM == kNormRms ? nullptr : (na.mod_shift ? na.mod_shift + mod0 * K : nullptr);
     constexpr uint32_t kDefault0 = NORM == kNormRms ? 0x3F80u : 0u;      // gamma = 1, s = 0
-    uint16_t* tmp0 = reinterpret_cast<uint16_t*>(lds_raw + vec_bytes);
-    uint16_t* tmp1 = tmp0 + Ki;
-    const bool via_lds = (size_t)n_waves * Ki * 2 >= vec_bytes;          // uniform over the workgroup
-    if (via_lds) {
-      for (int c = tid; c < k_chunks; c += blockDim.x) {
-        if (v0) *reinterpret_cast<uint4*>(tmp0 + c * 8) = *reinterpret_cast<const uint4*>(v0 + (size_t)c * 8);
-        if (v1) *reinterpret_cast<uint4*>(tmp1 + c * 8) = *reinterpret_cast<const uint4*>(v1 + (size_t)c * 8);
+    uint16_t* tmp = reinterpret_cast<uint16_t*>(lds_raw + vec_bytes);    // the slab space: at least 2 K bytes
+    // one vector at a time: copy as it lies, barrier, permuted read
+    auto permuted = [&](const uint16_t* v, int c, uint32_t dflt, uint32_t (&out)[8]) {
+      if (!v) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) out[e] = dflt;
+        return;
       }
-      __syncthreads();
-    }
-    for (int c = tid; c < k_chunks; c += blockDim.x) {
-      int idx[8];
       if (na.perm) {
         const int4 i0 = *reinterpret_cast<const int4*>(na.perm + (size_t)c * 8);
         const int4 i1 = *reinterpret_cast<const int4*>(na.perm + (size_t)c * 8 + 4);
-        idx[0] = i0.x; idx[1] = i0.y; idx[2] = i0.z; idx[3] = i0.w;
-        idx[4] = i1.x; idx[5] = i1.y; idx[6] = i1.z; idx[7] = i1.w;
+        const int idx[8] = {i0.x, i0.y, i0.z, i0.w, i1.x, i1.y, i1.z, i1.w};
+#pragma unroll
+        for (int e = 0; e < 8; ++e) out[e] = tmp[idx[e]];
       } else {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) idx[e] = c * 8 + e;
+        for (int e = 0; e < 8; ++e) out[e] = tmp[c * 8 + e];
       }
-      uint32_t a0[8], a1[8];
-#pragma unroll
-      for (int e = 0; e < 8; ++e) a0[e] = kDefault0, a1[e] = 0u;
-      if (v0) {
-        if (via_lds) {
-#pragma unroll
-          for (int e = 0; e < 8; ++e) a0[e] = tmp0[idx[e]];
-        } else {
-#pragma unroll
-          for (int e = 0; e < 8; ++e) a0[e] = v0[idx[e]];
-        }
-      }
-      if (v1) {
-        if (via_lds) {
-#pragma unroll
-          for (int e = 0; e < 8; ++e) a1[e] = tmp1[idx[e]];
-        } else {
-#pragma unroll
-          for (int e = 0; e < 8; ++e) a1[e] = v1[idx[e]];
-        }
-      }
+    };
+    if (v0) {
+      for (int c = tid; c < k_chunks; c += blockDim.x)
+        *reinterpret_cast<uint4*>(tmp + c * 8) = *reinterpret_cast<const uint4*>(v0 + (size_t)c * 8);
+    }
+    __syncthreads();
+    for (int c = tid; c < k_chunks; c += blockDim.x) {
+      uint32_t a0[8];
+      permuted(v0, c, kDefault0, a0);
       if constexpr (NORM == kNormRms) {
         *reinterpret_cast<uint4*>(vec_g + c * 8) = make_uint4(a0[0] | (a0[1] << 16), a0[2] | (a0[3] << 16),
                                                                a0[4] | (a0[5] << 16), a0[6] | (a0[7] << 16));
       } else {
-        *reinterpret_cast<uint4*>(vec_sb + c * 8) = make_uint4(a0[0] | (a1[0] << 16), a0[1] | (a1[1] << 16),
-                                                                a0[2] | (a1[2] << 16), a0[3] | (a1[3] << 16));
-        *reinterpret_cast<uint4*>(vec_sb + c * 8 + 4) = make_uint4(a0[4] | (a1[4] << 16), a0[5] | (a1[5] << 16),
-                                                                    a0[6] | (a1[6] << 16), a0[7] | (a1[7] << 16));
+        *reinterpret_cast<uint4*>(vec_sb + c * 8) = make_uint4(a0[0], a0[1], a0[2], a0[3]);
+        *reinterpret_cast<uint4*>(vec_sb + c * 8 + 4) = make_uint4(a0[4], a0[5], a0[6], a0[7]);
+      }
+    }
+    if constexpr (NORM == kNormAdaLn) {
+      if (v1) {                              // uniform over the workgroup
+        __syncthreads();
+        for (int c = tid; c < k_chunks; c += blockDim.x)
+          *reinterpret_cast<uint4*>(tmp + c * 8) = *reinterpret_cast<const uint4*>(v1 + (size_t)c * 8);
+        __syncthreads();
+        for (int c = tid; c < k_chunks; c += blockDim.x) {      // the chunks this thread wrote above
+          uint32_t a1[8];
+          permuted(v1, c, 0u, a1);
+          uint4 q0 = *reinterpret_cast<uint4*>(vec_sb + c * 8), q1 = *reinterpret_cast<uint4*>(vec_sb + c * 8 + 4);
+          q0.x |= a1[0] << 16; q0.y |= a1[1] << 16; q0.z |= a1[2] << 16; q0.w |= a1[3] << 16;
+          q1.x |= a1[4] << 16; q1.y |= a1[5] << 16; q1.z |= a1[6] << 16; q1.w |= a1[7] << 16;
+          *reinterpret_cast<uint4*>(vec_sb + c * 8) = q0;
+          *reinterpret_cast<uint4*>(vec_sb + c * 8 + 4) = q1;
+        }
       }
     }
   }
   __syncthreads();                       // the last barrier; every wave reaches it (the slabs are free again)
-  if (row >= rows) return;               // wave-uniform
+  if (TEAM == 1 && row0 + slot >= rows) return;      // wave-uniform; a team stays together to the end
 
   // indices pi(j) of chunk c (clamped to an existing chunk: the address is always valid)
   auto load_idx = [&](int c) -> Idx8 {
@@ -291,28 +337,32 @@ __global__ __launch_bounds__(64 * kNormMaxWaves) void norm_rows_kernel(
     T = *tensor_scale;
     encT = nv4_enc_scale(T);
   }
-  const int n_iter = (n_chunks + 63) / 64;
+  const int n_iter = (n_chunks + TL - 1) / TL;
 
+  for (int ri = 0; ri < rows_seq; ++ri) {
+  const int64_t row_u = TEAM == 1 ? row0 + slot : row0 + ri;
+  const bool active = row_u < rows;                          // a team runs past the last row without storing
+  const int64_t row = active ? row_u : rows - 1;
   // the first batch of indices does not depend on the row's values
   Idx8 ix_cur[kBatch];
 #pragma unroll
-  for (int q = 0; q < kBatch; ++q) ix_cur[q] = load_idx(lane + 64 * q);
+  for (int q = 0; q < kBatch; ++q) ix_cur[q] = load_idx(tl + TL * q);
 
   const uint16_t* xr = x + row * ld;
   float rstd = 0.0f, nmr = 0.0f;                             // LN(x) = x * rstd + nmr
   if constexpr (NORM == kHadamard) {
     // ---- 1. the row as fp32 in the wave's slab, transformed in place
     constexpr int kInFlight = 8;
-    for (int c0 = 0; c0 < k_chunks; c0 += kInFlight * 64) {
+    for (int c0 = 0; c0 < k_chunks; c0 += kInFlight * TL) {
       uint4 lines[kInFlight];
 #pragma unroll
       for (int t = 0; t < kInFlight; ++t) {
-        const int c = min(c0 + t * 64 + lane, k_chunks - 1);
+        const int c = min(c0 + t * TL + tl, k_chunks - 1);
         lines[t] = *reinterpret_cast<const uint4*>(xr + (size_t)c * 8);
       }
 #pragma unroll
       for (int t = 0; t < kInFlight; ++t) {
-        const int c = c0 + t * 64 + lane;
+        const int c = c0 + t * TL + tl;
         if (c < k_chunks) {
           const uint4 p = lines[t];
           *reinterpret_cast<float4*>(slab_f + c * 8) = make_float4(bf16_lo(p.x), bf16_hi(p.x), bf16_lo(p.y), bf16_hi(p.y));
@@ -320,8 +370,8 @@ __global__ __launch_bounds__(64 * kNormMaxWaves) void norm_rows_kernel(
         }
       }
     }
-    wave_lds_sync();
-    hadamard_row(slab_f, Ki, na.had_pow2, na.had_m, lane);
+    team_sync<TEAM>();
+    hadamard_row<TEAM>(slab_f, Ki, na.had_pow2, na.had_m, tl);
     rstd = na.had_scale;
   } else {
   // ---- 1. the row: statistics, and a copy in the wave's slab
@@ -329,16 +379,16 @@ __global__ __launch_bounds__(64 * kNormMaxWaves) void norm_rows_kernel(
   {
     const bf16x2_t ones = __builtin_bit_cast(bf16x2_t, 0x3F803F80u);
     constexpr int kInFlight = 8;                            // lines per lane requested together
-    for (int c0 = 0; c0 < k_chunks; c0 += kInFlight * 64) {
+    for (int c0 = 0; c0 < k_chunks; c0 += kInFlight * TL) {
       uint4 lines[kInFlight];
 #pragma unroll
       for (int t = 0; t < kInFlight; ++t) {
-        const int c = min(c0 + t * 64 + lane, k_chunks - 1);
+        const int c = min(c0 + t * TL + tl, k_chunks - 1);
         lines[t] = *reinterpret_cast<const uint4*>(xr + (size_t)c * 8);
       }
 #pragma unroll
       for (int t = 0; t < kInFlight; ++t) {
-        const int c = c0 + t * 64 + lane;
+        const int c = c0 + t * TL + tl;
         if (c < k_chunks) {
           *reinterpret_cast<uint4*>(slab + c * 8) = lines[t];
           const uint32_t d[4] = {lines[t].x, lines[t].y, lines[t].z, lines[t].w};
@@ -352,17 +402,17 @@ __global__ __launch_bounds__(64 * kNormMaxWaves) void norm_rows_kernel(
       }
     }
   }
-  s2 = wave_sum_f32(s2);
+  s2 = team_sum(s2);                     // (with TEAM > 1 also the barrier after the slab writes)
   float mean = 0.0f;
   if constexpr (NORM == kNormAdaLn) {
-    mean = wave_sum_f32(s1) / k_f;
+    mean = team_sum(s1) / k_f;
     // variance = mean square - mean^2 loses accuracy when the mean dominates; then (rare, uniform
     // over the wave) it is recomputed from the deviations, on the lane's own chunks in LDS
     const float mean_sq = s2 / k_f;
     const float var = mean_sq - mean * mean;
     if (mean_sq > 16.0f * var) {
       float s3 = 0.0f;
-      for (int c = lane; c < k_chunks; c += 64) {
+      for (int c = tl; c < k_chunks; c += TL) {
         const uint4 p = *reinterpret_cast<const uint4*>(slab + c * 8);
         const uint32_t d[4] = {p.x, p.y, p.z, p.w};
 #pragma unroll
@@ -371,7 +421,7 @@ __global__ __launch_bounds__(64 * kNormMaxWaves) void norm_rows_kernel(
           s3 = fmaf(hi, hi, fmaf(lo, lo, s3));
         }
       }
-      s2 = wave_sum_f32(s3);
+      s2 = team_sum(s3);
     } else {
       s2 = var * k_f;
     }
@@ -399,7 +449,7 @@ __global__ __launch_bounds__(64 * kNormMaxWaves) void norm_rows_kernel(
     // next batch's indices while this one is worked on
     Idx8 ix_next[kBatch];
 #pragma unroll
-    for (int q = 0; q < kBatch; ++q) ix_next[q] = load_idx(lane + 64 * (it0 + kBatch + q));
+    for (int q = 0; q < kBatch; ++q) ix_next[q] = load_idx(tl + TL * (it0 + kBatch + q));
     // gathers of the whole batch in flight together
     float xv[kBatch][8];
 #pragma unroll
@@ -411,7 +461,7 @@ __global__ __launch_bounds__(64 * kNormMaxWaves) void norm_rows_kernel(
     }
 #pragma unroll
     for (int q = 0; q < kBatch; ++q) {
-      const int c = lane + 64 * (it0 + q);
+      const int c = tl + TL * (it0 + q);
       if (it0 + q >= n_iter) break;                          // wave-uniform
       const bool in_row = c < k_chunks;
       const int cc = min(c, k_chunks - 1);
@@ -450,7 +500,7 @@ __global__ __launch_bounds__(64 * kNormMaxWaves) void norm_rows_kernel(
       uint4 yb = make_uint4(pack_bf16_rne(yv[0], yv[1]), pack_bf16_rne(yv[2], yv[3]),
                             pack_bf16_rne(yv[4], yv[5]), pack_bf16_rne(yv[6], yv[7]));
       if (!in_row) yb = make_uint4(0u, 0u, 0u, 0u);          // the half step past K holds zeros
-      if (y_row && in_row) *reinterpret_cast<uint4*>(y_row + (size_t)c * 8) = yb;
+      if (y_row && in_row && active) *reinterpret_cast<uint4*>(y_row + (size_t)c * 8) = yb;
 
       if constexpr (QUANT) {
         // the quantizer of pq_quantize.hip on the rounded values
@@ -472,7 +522,7 @@ __global__ __launch_bounds__(64 * kNormMaxWaves) void norm_rows_kernel(
           // collects the byte of the second pair
           const uint32_t other = dpp_u32<0x4E>(sc.byte);         // lane ^ 2
           const int u = c >> 2;
-          if ((lane & 3) == 0 && u < n_units) p_scales[(int64_t)u * rows + row] = (uint16_t)(sc.byte | (other << 8));
+          if ((lane & 3) == 0 && u < n_units && active) p_scales[(int64_t)u * rows + row] = (uint16_t)(sc.byte | (other << 8));
         } else {
           constexpr int FI = IS_INT ? FMT : kInt4;
           const IntScale sc = int_scale<FI>(a);
@@ -481,7 +531,7 @@ __global__ __launch_bounds__(64 * kNormMaxWaves) void norm_rows_kernel(
           const int g = c / LPG;
           if (lane % LPG == 0 && g < n_units) h_lds[g] = a;
         }
-        if (c < n_chunks) *reinterpret_cast<uint32_t*>(p_codes + ((int64_t)(c >> 3) * rows + row) * 32 + (c & 7) * 4) = codes;
+        if (c < n_chunks && active) *reinterpret_cast<uint32_t*>(p_codes + ((int64_t)(c >> 3) * rows + row) * 32 + (c & 7) * 4) = codes;
       }
     }
 #pragma unroll
@@ -493,25 +543,28 @@ __global__ __launch_bounds__(64 * kNormMaxWaves) void norm_rows_kernel(
     // largest group maximum in [2^10, 2^11) (see pack_operand_kernel); scale units are the fp16
     // group maxima times 2^-E, the row factor 2^E / Q
     constexpr float Q = qmax_of(FMT);
-    const float mx = wave_max(row_max);
+    const float mx = team_max(row_max);    // (with TEAM > 1 also the barrier after the h_lds writes)
     int e = (int)((as_u32(mx) >> 23) & 0xFF) - 127;
     if (mx == 0.0f) e = 0;
     const int E = max(-120, min(120, e - 10));
     const float down = as_f32((uint32_t)(127 - E) << 23);
-    if (lane == 0) p_mul[row] = as_f32((uint32_t)(127 + E) << 23) / Q;
-    for (int u = lane; u < n_units; u += 64) {       // the wave's own LDS writes, in order
+    if (tl == 0 && active) p_mul[row] = as_f32((uint32_t)(127 + E) << 23) / Q;
+    for (int u = tl; u < n_units; u += TL) {         // the team's own LDS writes, ordered above
       const _Float16 hn = (_Float16)(h_lds[u] * down);
-      p_scales[(int64_t)u * rows + row] = __builtin_bit_cast(uint16_t, hn);
+      if (active) p_scales[(int64_t)u * rows + row] = __builtin_bit_cast(uint16_t, hn);
     }
   }
+  if constexpr (TEAM > 1) __syncthreads();     // the slab and the group maxima are free for the next row
+  }  // rows of the workgroup
 }
 
 constexpr size_t kNormLdsLimit = 160 * 1024 - 1024;      // dynamic LDS a workgroup may ask for
 
-size_t norm_lds_bytes(int norm, bool is_int, int n_waves, int64_t K, int64_t units) {
-  const size_t per_wave_int = is_int ? (size_t)n_waves * units * 4 : 0;
-  if (norm == kHadamard) return (size_t)n_waves * K * 4 + per_wave_int;
-  return (size_t)K * (norm == kNormRms ? 2 : 4) + (size_t)n_waves * K * 2 + per_wave_int;
+// rows: row slabs of the workgroup (= waves when every wave owns a row, 1 for a team of waves)
+size_t norm_lds_bytes(int norm, bool is_int, int rows_per_wg, int n_waves, int64_t K, int64_t units) {
+  const size_t tail = (is_int ? (size_t)rows_per_wg * units * 4 : 0) + (size_t)n_waves * 16;
+  if (norm == kHadamard) return (size_t)rows_per_wg * K * 4 + tail;
+  return (size_t)K * (norm == kNormRms ? 2 : 4) + (size_t)rows_per_wg * K * 2 + tail;
 }
 
 // Waves (= rows) per workgroup: as many as still let the launch run in one round of resident
@@ -523,7 +576,7 @@ int norm_waves_per_group(Kern kern, int norm, bool is_int, int64_t rows, int64_t
   int best = 1;
   double best_cost = 1e30;
   for (int w = 1; w <= kNormMaxWaves; ++w) {
-    const size_t lds = norm_lds_bytes(norm, is_int, w, K, units);
+    const size_t lds = norm_lds_bytes(norm, is_int, w, w, K, units);
     if (lds > kNormLdsLimit) break;
     int per_cu = 0;
     if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, 64 * w, lds) != hipSuccess || per_cu < 1)
@@ -538,32 +591,52 @@ int norm_waves_per_group(Kern kern, int norm, bool is_int, int64_t rows, int64_t
   return best;
 }
 
-template <int FMT, int G, int NORM>
-int launch_norm_rows(const void* x, int64_t rows, int64_t K, int64_t ld, const float* ts, const OperandLayout& L,
+constexpr int kWideTeam = 4;             // waves that share a row wider than kWideRow channels
+constexpr int64_t kWideRow = 4096;
+
+template <int FMT, int G, int NORM, int TEAM>
+int launch_norm_team(const void* x, int64_t rows, int64_t K, int64_t ld, const float* ts, const OperandLayout& L,
                      uint8_t* operand, const NormArgs& na, hipStream_t st) {
   constexpr bool is_int = FMT == kInt4 || FMT == kInt3;
-  if (norm_lds_bytes(NORM, is_int, 1, K, L.units) > kNormLdsLimit)
+  const size_t least = norm_lds_bytes(NORM, is_int, 1, TEAM, K, L.units);
+  if (least > kNormLdsLimit)
     return fail(PQ_ERR_SHAPE, "K=%lld needs %zu bytes of LDS for one row and the vectors, more than the %zu available",
-                (long long)K, norm_lds_bytes(NORM, is_int, 1, K, L.units), kNormLdsLimit);
-  auto kern = norm_rows_kernel<FMT, G, NORM>;
+                (long long)K, least, kNormLdsLimit);
+  auto kern = norm_rows_kernel<FMT, G, NORM, TEAM>;
   // the choice depends on the shape only: remembered from the previous launch of this kernel
   static thread_local struct { int64_t rows, K; int n_waves; } memo = {0, 0, 0};
   if (memo.rows != rows || memo.K != K) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)kNormLdsLimit);
     if (e != hipSuccess) return check_hip(e, "hipFuncSetAttribute(norm_rows_kernel)");
-    memo.n_waves = norm_waves_per_group(kern, NORM, is_int, rows, K, L.units);
+    memo.n_waves = TEAM == 1 ? norm_waves_per_group(kern, NORM, is_int, rows, K, L.units) : TEAM;
     memo.rows = rows;
     memo.K = K;
   }
   const int n_waves = memo.n_waves;
-  const size_t shmem = norm_lds_bytes(NORM, is_int, n_waves, K, L.units);
-  const int64_t groups = (rows + n_waves - 1) / n_waves;
+  const int rows_per_wg = TEAM == 1 ? n_waves : 1;
+  const size_t shmem = norm_lds_bytes(NORM, is_int, rows_per_wg, n_waves, K, L.units);
+  NormArgs args = na;
+  // a team takes several rows in sequence where that still leaves about three workgroups per compute
+  // unit: the staging of the vectors is then shared by those rows
+  args.rows_seq = 1;
+  if (TEAM > 1 && NORM != kHadamard) args.rows_seq = (int)std::max<int64_t>(1, std::min<int64_t>(8, rows / 768));
+  const int64_t per_group = TEAM == 1 ? rows_per_wg : args.rows_seq;
+  const int64_t groups = (rows + per_group - 1) / per_group;
   hipLaunchKernelGGL(kern, dim3((unsigned)groups), dim3(64 * n_waves), shmem, st, (const uint16_t*)x, rows, K, ld, ts,
                      L.steps, L.units, operand ? operand + L.codes : nullptr,
                      (uint16_t*)(operand ? operand + L.scales : nullptr),
-                     (float*)(operand ? operand + L.mul : nullptr), na);
+                     (float*)(operand ? operand + L.mul : nullptr), args);
   return check_hip(hipGetLastError(), "norm_rows_kernel");
+}
+
+// One wave per row up to kWideRow channels; wider rows are shared by the kWideTeam waves of a workgroup
+// (a wave alone would leave a compute unit with two or three rows in flight).
+template <int FMT, int G, int NORM>
+int launch_norm_rows(const void* x, int64_t rows, int64_t K, int64_t ld, const float* ts, const OperandLayout& L,
+                     uint8_t* operand, const NormArgs& na, hipStream_t st) {
+  if (K > kWideRow) return launch_norm_team<FMT, G, NORM, kWideTeam>(x, rows, K, ld, ts, L, operand, na, st);
+  return launch_norm_team<FMT, G, NORM, 1>(x, rows, K, ld, ts, L, operand, na, st);
 }
 
 template <int FMT, int G>
@@ -584,6 +657,7 @@ NormArgs norm_args(const pq_norm_params& p, void* y, int64_t ldy) {
   na.eps = p.eps;
   na.y = (uint16_t*)y;
   na.ldy = ldy;
+  na.rows_seq = 1;
   na.had_pow2 = na.had_m = 0;
   na.had_scale = 0.0f;
   return na;

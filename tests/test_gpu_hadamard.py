@@ -62,7 +62,8 @@ def _check_close(got_bits, ref64, label, min_same=0.995):
 
 # widths: powers of two with every last-pass radix (2, 4, 8, 16), the Paley factors 12 and 20 alone and
 # combined with Sylvester digits, the FLUX widths
-WIDTHS = [8, 16, 32, 64, 128, 512, 4096, 24, 48, 96, 768, 3072, 40, 160, 2560]
+WIDTHS = [8, 16, 32, 64, 128, 512, 4096, 24, 48, 96, 768, 3072, 40, 160, 2560,
+          8192, 12288, 5120, 24576]          # wider than 4096: four waves share a row
 
 
 @pytest.mark.parametrize("K", WIDTHS)
@@ -93,6 +94,26 @@ def test_unit_vectors_give_the_rows_of_the_matrix():
         got = OF.bf16_bits_to_f64(_host_bits(y))
         ref = OF.bf16_bits_to_f64(OH.to_bf16_bits(4.0 * OH.hadamard_matrix(K)))
         assert np.array_equal(got, ref), K
+
+
+def test_wide_exact_inputs_and_fused_quantizer():
+    """K = 16384 = 4^7 with integer inputs: exact arithmetic, four waves per row; and the quantizing call
+    equals rotation followed by quantizer."""
+    rows, K = 5, 16384
+    rng = np.random.default_rng(9955)
+    x_bits = _bits(rng.integers(-8, 9, size=(rows, K)).astype(np.float64))
+    perm = rng.permutation(K).astype(np.int32)
+    perm_d = torch.from_numpy(perm).to(DEV)
+    ref_bits = OH.to_bf16_bits(OH.rotate_reordered(OF.bf16_bits_to_f64(x_bits), perm))
+    y = pq.pq_hadamard_reorder(_dev(x_bits), perm_d)
+    torch.cuda.synchronize()
+    assert np.array_equal(_host_bits(y), ref_bits)
+    for fmt, g in ((pq.FMT_INT4, 64), (pq.FMT_NVFP4, 16), (pq.FMT_INT3, 256)):
+        Ta = torch.full((1,), 0.01, dtype=torch.float32, device=DEV)
+        want = pq.pq_quantize_act_packed(fmt, g, y, Ta, torch.zeros(pq.pq_operand_bytes(fmt, g, rows, K), dtype=torch.uint8, device=DEV))
+        got = pq.pq_hadamard_quantize_act_packed(fmt, g, _dev(x_bits), Ta, perm_d, operand=torch.zeros_like(want))
+        torch.cuda.synchronize()
+        assert torch.equal(got, want), (fmt, g)
 
 
 @pytest.mark.parametrize("fmt,g", FMTS)

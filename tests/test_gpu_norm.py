@@ -285,3 +285,32 @@ def test_layernorm_rows_with_a_dominant_mean():
     # outputs: if one of them sits next to a bf16 rounding boundary, all its copies round the other way
     _check_close(_host_bits(y), _oracle(ADALN, x_bits, perm, None, None, None, 0, 1e-6), "dominant mean",
                  min_same=0.9)
+
+
+@pytest.mark.parametrize("kind", [RMS, ADALN])
+@pytest.mark.parametrize("rows,K,rows_per_mod", [(13, 6144, 5), (7, 12288, 0), (3, 4104, 2)])
+def test_wide_rows_share_a_workgroup(kind, rows, K, rows_per_mod):
+    """Rows wider than 4096 channels are worked on by the four waves of a workgroup together: same
+    results as the oracle, and the quantizing call still equals norm followed by quantizer."""
+    _say("norm wide kind=%d rows=%d K=%d" % (kind, rows, K))
+    rng = np.random.default_rng(9650 + kind + rows + K)
+    x_bits = _activations(rng, rows, K)
+    perm = rng.permutation(K).astype(np.int32)
+    n_mod = 1 if rows_per_mod <= 0 else -(-rows // rows_per_mod)
+    gamma_bits = _bits(1.0 + 0.3 * rng.standard_normal(K))
+    s_bits = _bits(0.5 * rng.standard_normal((n_mod, K)))
+    b_bits = _bits(0.5 * rng.standard_normal((n_mod, K)))
+    perm_d = torch.from_numpy(perm).to(DEV)
+    x, gamma, s, b = _dev(x_bits), _dev(gamma_bits), _dev(s_bits), _dev(b_bits)
+    y = pq.pq_norm_reorder(kind, x, 1e-6, perm_d, gamma, s, b, rows_per_mod)
+    torch.cuda.synchronize()
+    _check_close(_host_bits(y), _oracle(kind, x_bits, perm, gamma_bits, s_bits, b_bits, rows_per_mod, 1e-6), "wide")
+    if K % 64 == 0:
+        for fmt, g in ((pq.FMT_INT4, 64), (pq.FMT_NVFP4, 16), (pq.FMT_INT3, 256)):
+            Ta = torch.full((1,), 0.004, dtype=torch.float32, device=DEV)
+            want = pq.pq_quantize_act_packed(fmt, g, y, Ta, torch.zeros(pq.pq_operand_bytes(fmt, g, rows, K), dtype=torch.uint8, device=DEV))
+            y2 = torch.empty_like(y)
+            got = pq.pq_norm_quantize_act_packed(kind, fmt, g, x, 1e-6, Ta, perm_d, gamma, s, b, rows_per_mod,
+                                                 operand=torch.zeros_like(want), y=y2)
+            torch.cuda.synchronize()
+            assert torch.equal(y2, y) and torch.equal(got, want), (fmt, g)
