@@ -125,18 +125,20 @@ __global__ __launch_bounds__(64 * kTy) void moments_partial_kernel(BatchPtrs xs,
   }
 }
 
-// sumsq[i] += sum of the partials of column i.  A workgroup covers 64 columns; its four waves
-// each add a contiguous quarter of the partials in order, and the four sums are combined in
-// wave order: the result does not depend on scheduling.
-__global__ __launch_bounds__(256) void moments_finish_kernel(const double* __restrict__ partial,
-                                                            int n_partials, int64_t K,
-                                                            double* __restrict__ sumsq,
-                                                            const float* __restrict__ blockmax,
-                                                            int n_blockmax, float* __restrict__ absmax) {
-  __shared__ double quarter[4][64];
-  const int lane = threadIdx.x & 63, part = threadIdx.x >> 6;
-  const int64_t i = (int64_t)blockIdx.x * 64 + lane;
-  const int per = (n_partials + 3) / 4;
+// sumsq[i] += sum of the partials of column i.  A workgroup covers kFinCols columns; its threads form
+// kFinParts groups that each add a contiguous share of the partials in order, and the shares are
+// combined in group order: the result does not depend on scheduling.  (Sixteen columns by sixteen
+// shares: 4 K / 64 workgroups with short chains instead of K / 64 with long ones.)
+constexpr int kFinCols = 16, kFinParts = 16;
+__global__ __launch_bounds__(kFinCols * kFinParts) void moments_finish_kernel(const double* __restrict__ partial,
+                                                                             int n_partials, int64_t K,
+                                                                             double* __restrict__ sumsq,
+                                                                             const float* __restrict__ blockmax,
+                                                                             int n_blockmax, float* __restrict__ absmax) {
+  __shared__ double share[kFinParts][kFinCols];
+  const int col = threadIdx.x % kFinCols, part = threadIdx.x / kFinCols;
+  const int64_t i = (int64_t)blockIdx.x * kFinCols + col;
+  const int per = (n_partials + kFinParts - 1) / kFinParts;
   const int r0 = part * per, r1 = min(n_partials, r0 + per);
   double s = 0.0;
   if (i < K) {
@@ -150,12 +152,17 @@ __global__ __launch_bounds__(256) void moments_finish_kernel(const double* __res
     }
     for (; r < r1; ++r) s += partial[(int64_t)r * K + i];
   }
-  quarter[part][lane] = s;
+  share[part][col] = s;
   __syncthreads();
-  if (part == 0 && i < K) sumsq[i] += ((quarter[0][lane] + quarter[1][lane]) + quarter[2][lane]) + quarter[3][lane];
+  if (part == 0 && i < K) {
+    double t = 0.0;
+#pragma unroll
+    for (int p = 0; p < kFinParts; ++p) t += share[p][col];
+    sumsq[i] += t;
+  }
   if (absmax && blockIdx.x == 0) {
     float m = 0.0f;
-    for (int b = threadIdx.x; b < n_blockmax; b += 256) m = fmaxf(m, blockmax[b]);
+    for (int b = threadIdx.x; b < n_blockmax; b += kFinCols * kFinParts) m = fmaxf(m, blockmax[b]);
     m = wave_max(m);
     __shared__ float wm[4];
     if ((threadIdx.x & 63) == 0) wm[threadIdx.x >> 6] = m;
@@ -183,7 +190,8 @@ int launch_moments(const void* const* xs, int n_batches, int64_t rows, int64_t K
                        blockmax);
     int rc = check_hip(hipGetLastError(), "moments_partial_kernel");
     if (rc) return rc;
-    hipLaunchKernelGGL(moments_finish_kernel, dim3((unsigned)((K + 63) / 64)), dim3(256), 0, st,
+    hipLaunchKernelGGL(moments_finish_kernel, dim3((unsigned)((K + kFinCols - 1) / kFinCols)),
+                       dim3(kFinCols * kFinParts), 0, st,
                        (const double*)partial, nb * slabs, K, sumsq, (const float*)blockmax,
                        (int)blockmax_count(K, slabs, nb), absmax);
     rc = check_hip(hipGetLastError(), "moments_finish_kernel");
