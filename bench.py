@@ -320,6 +320,16 @@ def main():
         "reference_stream_read_all_batches_cold": {"us": t_floor_mall * 1e6, "gbs": nb * mbytes / t_floor_mall / 1e9},
         "reference_mfma_only_loop": {"tflops": mfma_sustained, "frac_mfma_f16_peak": mfma_sustained / MFMA_F16_PEAK_TFLOPS},
     }
+    if fmt == pq.FMT_INT3:
+        # weights at rest in three bits per code: to and from the nibble form, and straight to the GEMM's
+        dense = pq.pq_int3_pack(w_codes)
+        t_p3 = time_calls(lambda i: pq.pq_int3_pack(w_codes, dense), it)
+        t_u3 = time_calls(lambda i: pq.pq_int3_unpack(dense, K, w_codes), it)
+        t_o3 = time_calls(lambda i: pq.pq_pack_operand_int3(g, dense, w_scales, K, w_op), it)
+        b3 = 0.875 * N * K
+        kernels["int3_pack_weights_warm"] = {"us": t_p3 * 1e6, "gbs": b3 / t_p3 / 1e9}
+        kernels["int3_unpack_weights_warm"] = {"us": t_u3 * 1e6, "gbs": b3 / t_u3 / 1e9}
+        kernels["pack_operand_int3_weights_warm"] = {"us": t_o3 * 1e6}
     if args.no_row_major_comparison:
         del kernels["qgemm_kernel_row_major_operands"], kernels["qgemm_call_row_major_with_scale_prep"]
     for k, v in kernels.items():

@@ -299,6 +299,31 @@ int pq_qgemm_packed_bias(pq_format fmt, int group, const void* a_operand, const 
                          const void* bias_bf16, void* y_bf16, int64_t ldy, void* stream);
 
 /*
+ * Dense 3-bit storage of INT3 codes (paper Eq. 1-2 with b = 3: codes in -3..3).  The quantizers store
+ * INT3 codes in nibbles like INT4; these calls hold them at three bits each, which is what the weights of
+ * a W3 model occupy at rest.  The paper prints no layout; this one is the library's: a row of K codes is
+ * a stream of 3 K bits, code k in bits 3k..3k+2 as the 3-bit two's complement of z (least significant
+ * bit first), bit b of the stream in bit b mod 8 of byte b div 8; a row takes 3 K / 8 bytes and rows
+ * follow each other unpadded.
+ *
+ * codes: [rows, K/2] bytes of nibbles as pq_quantize_weights / pq_quantize_act write them for INT3;
+ * dense: [rows, 3 K / 8] bytes = pq_int3_dense_bytes(rows, K) (0 for an invalid shape).  Both device
+ * memory, 16-byte aligned, caller-owned, and they must not overlap.  K: a positive multiple of 32; rows
+ * and K at most 2^24.  pq_int3_pack keeps the low three bits of every nibble: for the codes the
+ * quantizers emit (and for -4) pq_int3_unpack(pq_int3_pack(c)) == c, other nibbles are not checked.
+ * pq_pack_operand_int3 is pq_pack_operand for PQ_FMT_INT3 reading the dense form directly, so that the
+ * weights go from their stored form to the GEMM's in one pass:
+ *     pq_pack_operand_int3(g, pq_int3_pack(c), s) == pq_pack_operand(PQ_FMT_INT3, g, c, s)   byte for byte.
+ * Errors: PQ_ERR_NULL, PQ_ERR_SHAPE (rows, K, alignment), PQ_ERR_FORMAT (group), PQ_ERR_WORKSPACE
+ * (operand_size too small), PQ_ERR_HIP.  Asynchronous on `stream`.
+ */
+size_t pq_int3_dense_bytes(int64_t rows, int64_t K);
+int pq_int3_pack(const uint8_t* codes, int64_t rows, int64_t K, uint8_t* dense, void* stream);
+int pq_int3_unpack(const uint8_t* dense, int64_t rows, int64_t K, uint8_t* codes, void* stream);
+int pq_pack_operand_int3(int group, const uint8_t* dense, const void* scales, int64_t rows, int64_t K,
+                         void* operand, size_t operand_size, void* stream);
+
+/*
  * The other reorder criteria of the ablation (paper Tab. 2a: variance, absmax, round-robin, random; the
  * paper names them without formulas, the readings are the library's).  A criterion supplies one
  * non-negative statistic per channel and side that takes the place of the second moment in the joint

@@ -297,21 +297,59 @@ size_t pq_operand_bytes(pq_format fmt, int group, int64_t rows, int64_t K) {
   return operand_bytes(fmt, group, rows, K);
 }
 
-int pq_pack_operand(pq_format fmt, int group, const uint8_t* codes, const void* scales, int64_t rows,
-                    int64_t K, void* operand, size_t operand_size, void* stream) {
-  if (!codes || !scales || !operand) return fail(PQ_ERR_NULL, "pq_pack_operand: a required pointer is NULL");
+static int pack_operand_common(const char* name, pq_format fmt, int group, const uint8_t* codes, const void* scales,
+                               int64_t rows, int64_t K, void* operand, size_t operand_size, bool dense3,
+                               void* stream) {
+  if (!codes || !scales || !operand) return fail(PQ_ERR_NULL, "%s: a required pointer is NULL", name);
   int rc = check_format(fmt, group, K);
   if (rc) return rc;
-  if (rows <= 0) return fail(PQ_ERR_SHAPE, "pq_pack_operand: rows=%lld must be positive", (long long)rows);
-  if (K % 32) return fail(PQ_ERR_SHAPE, "pq_pack_operand: K=%lld must be a multiple of 32", (long long)K);
-  if (rows > (1 << 24) || K > (1 << 24)) return fail(PQ_ERR_SHAPE, "pq_pack_operand: a dimension exceeds 2^24");
+  if (rows <= 0) return fail(PQ_ERR_SHAPE, "%s: rows=%lld must be positive", name, (long long)rows);
+  if (K % 32) return fail(PQ_ERR_SHAPE, "%s: K=%lld must be a multiple of 32", name, (long long)K);
+  if (rows > (1 << 24) || K > (1 << 24)) return fail(PQ_ERR_SHAPE, "%s: a dimension exceeds 2^24", name);
   if (!aligned16(codes) || !aligned16(scales) || !aligned16(operand))
-    return fail(PQ_ERR_SHAPE, "pq_pack_operand: buffers must be 16-byte aligned");
+    return fail(PQ_ERR_SHAPE, "%s: buffers must be 16-byte aligned", name);
   const size_t need = operand_bytes(fmt, group, rows, K);
   if (operand_size < need)
-    return fail(PQ_ERR_WORKSPACE, "pq_pack_operand: operand buffer of %zu bytes needed, %zu given", need,
-                operand_size);
-  return run_pack_operand(fmt, group, codes, scales, rows, K, operand, as_stream(stream));
+    return fail(PQ_ERR_WORKSPACE, "%s: operand buffer of %zu bytes needed, %zu given", name, need, operand_size);
+  return run_pack_operand(fmt, group, codes, scales, rows, K, operand, dense3, as_stream(stream));
+}
+
+int pq_pack_operand(pq_format fmt, int group, const uint8_t* codes, const void* scales, int64_t rows,
+                    int64_t K, void* operand, size_t operand_size, void* stream) {
+  return pack_operand_common("pq_pack_operand", fmt, group, codes, scales, rows, K, operand, operand_size, false,
+                             stream);
+}
+
+int pq_pack_operand_int3(int group, const uint8_t* dense, const void* scales, int64_t rows, int64_t K,
+                         void* operand, size_t operand_size, void* stream) {
+  return pack_operand_common("pq_pack_operand_int3", PQ_FMT_INT3, group, dense, scales, rows, K, operand,
+                             operand_size, true, stream);
+}
+
+size_t pq_int3_dense_bytes(int64_t rows, int64_t K) {
+  if (rows <= 0 || K <= 0 || K % 32 || rows > (1 << 24) || K > (1 << 24)) return 0;
+  return (size_t)rows * (size_t)(K / 8 * 3);
+}
+
+static int int3_common(const char* name, const void* src, void* dst, int64_t rows, int64_t K) {
+  if (!src || !dst) return fail(PQ_ERR_NULL, "%s: a required pointer is NULL", name);
+  if (rows <= 0) return fail(PQ_ERR_SHAPE, "%s: rows=%lld must be positive", name, (long long)rows);
+  if (K <= 0 || K % 32) return fail(PQ_ERR_SHAPE, "%s: K=%lld must be a positive multiple of 32", name, (long long)K);
+  if (rows > (1 << 24) || K > (1 << 24)) return fail(PQ_ERR_SHAPE, "%s: a dimension exceeds 2^24", name);
+  if (!aligned16(src) || !aligned16(dst)) return fail(PQ_ERR_SHAPE, "%s: buffers must be 16-byte aligned", name);
+  return PQ_OK;
+}
+
+int pq_int3_pack(const uint8_t* codes, int64_t rows, int64_t K, uint8_t* dense, void* stream) {
+  int rc = int3_common("pq_int3_pack", codes, dense, rows, K);
+  if (rc) return rc;
+  return launch_int3_pack(codes, rows, K, dense, as_stream(stream));
+}
+
+int pq_int3_unpack(const uint8_t* dense, int64_t rows, int64_t K, uint8_t* codes, void* stream) {
+  int rc = int3_common("pq_int3_unpack", dense, codes, rows, K);
+  if (rc) return rc;
+  return launch_int3_unpack(dense, rows, K, codes, as_stream(stream));
 }
 
 int pq_quantize_act_packed(pq_format fmt, int group, const void* x, int64_t M, int64_t K, int64_t ld,

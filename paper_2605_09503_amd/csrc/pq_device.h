@@ -190,6 +190,34 @@ __device__ __forceinline__ uint32_t int_codes8(const float (&x)[8], float inv) {
   for (int j = 0; j < 8; ++j) acc = (as_u32(x[j] * inv + 12582920.0f) << (4 * j)) + acc;
   return (acc - kConst) ^ 0x88888888u;
 }
+// Dense 3-bit storage of INT3 codes: code k of a row sits in bits 3k..3k+2 of the row's bit stream
+// (z mod 8, least significant bit first), so eight codes -- one word of two's complement nibbles,
+// element j at bits 4j -- make one 24-bit word.  The squeeze drops bit 3 of every nibble (for codes
+// in -4..3 it repeats bit 2) and closes the gaps in three steps: nibble pairs to 6 bits per byte,
+// byte pairs to 12 bits per half word, the two halves to 24 bits.  The spread is the inverse and
+// restores bit 3 from bit 2.
+__device__ __forceinline__ uint32_t int3_squeeze8(uint32_t nibbles) {
+  const uint32_t a = (nibbles & 0x07070707u) | ((nibbles & 0x70707070u) >> 1);
+  const uint32_t b = (a & 0x003F003Fu) | ((a & 0x3F003F00u) >> 2);
+  return (b & 0x00000FFFu) | ((b & 0x0FFF0000u) >> 4);
+}
+__device__ __forceinline__ uint32_t int3_spread8(uint32_t w24) {
+  const uint32_t b = (w24 & 0x00000FFFu) | ((w24 & 0x00FFF000u) << 4);
+  const uint32_t a = (b & 0x003F003Fu) | ((b << 2) & 0x3F003F00u);
+  const uint32_t n = (a & 0x07070707u) | ((a << 1) & 0x70707070u);
+  return n | ((n & 0x44444444u) << 1);
+}
+// 32 codes: four nibble words <-> twelve bytes (three little-endian words)
+__device__ __forceinline__ void int3_squeeze32(const uint4& n, uint32_t (&o)[3]) {
+  const uint32_t w0 = int3_squeeze8(n.x), w1 = int3_squeeze8(n.y), w2 = int3_squeeze8(n.z), w3 = int3_squeeze8(n.w);
+  o[0] = w0 | (w1 << 24);
+  o[1] = (w1 >> 8) | (w2 << 16);
+  o[2] = (w2 >> 16) | (w3 << 8);
+}
+__device__ __forceinline__ uint4 int3_spread32(uint32_t o0, uint32_t o1, uint32_t o2) {
+  return make_uint4(int3_spread8(o0 & 0x00FFFFFFu), int3_spread8((o0 >> 24) | ((o1 & 0x0000FFFFu) << 8)),
+                    int3_spread8((o1 >> 16) | ((o2 & 0x000000FFu) << 16)), int3_spread8(o2 >> 8));
+}
 // the same integer as a float (for the error evaluation)
 __device__ __forceinline__ float int_code_value(float x, float inv, float Q) {
   const float v = __builtin_amdgcn_fmed3f(x * inv, -Q, Q);

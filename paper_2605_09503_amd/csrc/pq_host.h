@@ -89,7 +89,9 @@ inline OperandLayout operand_layout(pq_format fmt, int group, int64_t rows, int6
 }
 size_t operand_bytes(pq_format fmt, int group, int64_t rows, int64_t K);
 int run_pack_operand(pq_format fmt, int group, const uint8_t* codes, const void* scales, int64_t rows,
-                     int64_t K, void* operand, hipStream_t st);
+                     int64_t K, void* operand, bool dense3, hipStream_t st);   // dense3: codes as pq_int3_pack stores them
+int launch_int3_pack(const uint8_t* codes, int64_t rows, int64_t K, uint8_t* dense, hipStream_t st);
+int launch_int3_unpack(const uint8_t* dense, int64_t rows, int64_t K, uint8_t* codes, hipStream_t st);
 int run_quantize_packed(pq_format fmt, int group, const void* x, int64_t rows, int64_t K, int64_t ld,
                         const float* ts, void* operand, uint8_t* codes, void* scales, hipStream_t st);
 int run_norm_reorder(const pq_norm_params& p, const void* x, int64_t rows, int64_t K, int64_t ld, void* y,

@@ -29,7 +29,9 @@ constexpr int kPackRows = 8;      // rows per workgroup
 //   codes:  a wave covers 8 rows x 4 steps per trip -- it reads 128 contiguous bytes of each row
 //           and writes four runs of 256 bytes.
 //   scales: a wave covers 8 rows x 8 units per trip.
-template <int FMT, int G>
+// DENSE3: the codes come from the dense 3-bit storage of INT3 (pq_int3.hip), rows of 3 K / 8 bytes;
+// 32 codes are twelve bytes there and are widened to nibbles on the way.
+template <int FMT, int G, bool DENSE3>
 __global__ __launch_bounds__(256) void pack_operand_kernel(const uint8_t* __restrict__ codes,
                                                            const void* __restrict__ scales,
                                                            int64_t rows, int64_t K, int64_t steps,
@@ -49,7 +51,14 @@ __global__ __launch_bounds__(256) void pack_operand_kernel(const uint8_t* __rest
         const int64_t step = s0 + t * 16 + wave * 4 + s_local;
         const int64_t k0 = step * 64 + half * 32;
         v[t] = make_uint4(0u, 0u, 0u, 0u);
-        if (r < rows && k0 < K) v[t] = *reinterpret_cast<const uint4*>(codes + r * (K / 2) + k0 / 2);
+        if (r < rows && k0 < K) {
+          if constexpr (DENSE3) {
+            const uint32_t* d = reinterpret_cast<const uint32_t*>(codes + r * (K / 8 * 3) + k0 / 8 * 3);
+            v[t] = int3_spread32(d[0], d[1], d[2]);
+          } else {
+            v[t] = *reinterpret_cast<const uint4*>(codes + r * (K / 2) + k0 / 2);
+          }
+        }
       }
 #pragma unroll
       for (int t = 0; t < 4; ++t) {
@@ -105,21 +114,31 @@ __global__ __launch_bounds__(256) void pack_operand_kernel(const uint8_t* __rest
   }
 }
 
-template <int FMT, int G>
+template <int FMT, int G, bool DENSE3 = false>
 static int launch_pack(const uint8_t* codes, const void* scales, int64_t rows, int64_t K,
                        const OperandLayout& L, uint8_t* operand, hipStream_t st) {
   const int64_t blocks = (rows + kPackRows - 1) / kPackRows;
-  hipLaunchKernelGGL((pack_operand_kernel<FMT, G>), dim3((unsigned)blocks), dim3(256), 0, st, codes, scales,
+  hipLaunchKernelGGL((pack_operand_kernel<FMT, G, DENSE3>), dim3((unsigned)blocks), dim3(256), 0, st, codes, scales,
                      rows, K, L.steps, L.units, operand + L.codes, (uint16_t*)(operand + L.scales),
                      (float*)(operand + L.mul));
   return check_hip(hipGetLastError(), "pack_operand_kernel");
 }
 
 int run_pack_operand(pq_format fmt, int group, const uint8_t* codes, const void* scales, int64_t rows,
-                     int64_t K, void* operand, hipStream_t st) {
+                     int64_t K, void* operand, bool dense3, hipStream_t st) {
   if (rows > 0x7FFFFFF0) return fail(PQ_ERR_SHAPE, "too many rows");
   const OperandLayout L = operand_layout(fmt, group, rows, K);
   uint8_t* o = (uint8_t*)operand;
+  if (dense3) {
+    if (fmt != PQ_FMT_INT3) return fail(PQ_ERR_FORMAT, "dense 3-bit codes are INT3 only");
+    switch (group) {
+      case 32: return launch_pack<kInt3, 32, true>(codes, scales, rows, K, L, o, st);
+      case 64: return launch_pack<kInt3, 64, true>(codes, scales, rows, K, L, o, st);
+      case 128: return launch_pack<kInt3, 128, true>(codes, scales, rows, K, L, o, st);
+      case 256: return launch_pack<kInt3, 256, true>(codes, scales, rows, K, L, o, st);
+    }
+    return fail(PQ_ERR_FORMAT, "unsupported (format, group) = (%d, %d)", (int)fmt, group);
+  }
   if (fmt == PQ_FMT_NVFP4) return launch_pack<kNvfp4, 16>(codes, scales, rows, K, L, o, st);
 #define PQ_INT_CASE(F, FE)                                                \
   if (fmt == F) {                                                         \

@@ -263,10 +263,10 @@ int run_select_output(pq_format fmt, int group, const double* act_sumsq, const d
     const int32_t* perm = c == 0 ? nullptr : W.cands + (int64_t)(c - 1) * K;
     // the tensor scale of the weights does not depend on the order: the caller's value is used
     if ((rc = launch_quantize_rows(fmt, group, w, N, K, K, perm, W.ts + 1, W.w_codes, W.w_scales, st))) return rc;
-    if ((rc = run_pack_operand(fmt, group, W.w_codes, W.w_scales, N, K, W.w_op, st))) return rc;
+    if ((rc = run_pack_operand(fmt, group, W.w_codes, W.w_scales, N, K, W.w_op, false, st))) return rc;
     for (int b = 0; b < n_batches; ++b) {
       if ((rc = launch_quantize_rows(fmt, group, x_calib[b], M, K, K, perm, W.ts, W.x_codes, W.x_scales, st))) return rc;
-      if ((rc = run_pack_operand(fmt, group, W.x_codes, W.x_scales, M, K, W.x_op, st))) return rc;
+      if ((rc = run_pack_operand(fmt, group, W.x_codes, W.x_scales, M, K, W.x_op, false, st))) return rc;
       if ((rc = run_qgemm_packed(fmt, group, W.x_op, W.ts, W.w_op, W.ts + 1, M, N, K, nullptr, W.y_hat, ldn, true, st)))
         return rc;
       hipLaunchKernelGGL(sqdiff_partial_kernel, dim3(kDiffBlocks), dim3(256), 0, st,

@@ -84,6 +84,11 @@ def load():
     lib.pq_operand_bytes.argtypes = [i32, i32, i64, i64]
     lib.pq_pack_operand.argtypes = [i32, i32, vp, vp, i64, i64, vp, sz, vp]
     lib.pq_quantize_act_packed.argtypes = [i32, i32, vp, i64, i64, i64, vp, vp, sz, vp, vp, vp]
+    lib.pq_int3_dense_bytes.restype = sz
+    lib.pq_int3_dense_bytes.argtypes = [i64, i64]
+    lib.pq_int3_pack.argtypes = [vp, i64, i64, vp, vp]
+    lib.pq_int3_unpack.argtypes = [vp, i64, i64, vp, vp]
+    lib.pq_pack_operand_int3.argtypes = [i32, vp, vp, i64, i64, vp, sz, vp]
     packed_args = [i32, i32, vp, vp, vp, vp, i64, i64, i64, vp, i64, vp]
     lib.pq_qgemm_packed.argtypes = packed_args
     lib.pq_qgemm_packed_f32.argtypes = packed_args
@@ -304,6 +309,40 @@ def pq_pack_operand(fmt: int, group: int, codes: torch.Tensor, scales: torch.Ten
         operand = torch.empty(max(pq_operand_bytes(fmt, group, rows, K), 16), dtype=torch.uint8, device=codes.device)
     _check(load().pq_pack_operand(fmt, group, _ptr(codes), _ptr(scales), rows, K, _ptr(operand),
                                   operand.numel(), _stream()))
+    return operand
+
+
+def pq_int3_dense_bytes(rows: int, K: int) -> int:
+    return int(load().pq_int3_dense_bytes(rows, K))
+
+
+def pq_int3_pack(codes: torch.Tensor, dense: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """INT3 codes in nibbles [rows, K/2] -> dense 3-bit storage [rows, 3K/8] (allocates unless given)."""
+    rows, K = codes.shape[0], codes.shape[1] * 2
+    if dense is None:
+        dense = torch.empty((rows, K // 8 * 3), dtype=torch.uint8, device=codes.device)
+    _check(load().pq_int3_pack(_ptr(codes), rows, K, _ptr(dense), _stream()))
+    return dense
+
+
+def pq_int3_unpack(dense: torch.Tensor, K: int, codes: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Dense 3-bit storage [rows, 3K/8] -> nibbles [rows, K/2] (allocates unless given)."""
+    rows = dense.shape[0]
+    if codes is None:
+        codes = torch.empty((rows, K // 2), dtype=torch.uint8, device=dense.device)
+    _check(load().pq_int3_unpack(_ptr(dense), rows, K, _ptr(codes), _stream()))
+    return codes
+
+
+def pq_pack_operand_int3(group: int, dense: torch.Tensor, scales: torch.Tensor, K: int,
+                         operand: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Dense 3-bit codes + scales -> the GEMM's panel layout (allocates the buffer unless given)."""
+    rows = dense.shape[0]
+    if operand is None:
+        operand = torch.empty(max(pq_operand_bytes(FMT_INT3, group, rows, K), 16), dtype=torch.uint8,
+                              device=dense.device)
+    _check(load().pq_pack_operand_int3(group, _ptr(dense), _ptr(scales), rows, K, _ptr(operand),
+                                       operand.numel(), _stream()))
     return operand
 
 

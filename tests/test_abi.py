@@ -258,3 +258,27 @@ def test_norm_validation(lib):
     assert g(C.byref(ok), 0, 16, FAKE, 8, 48, 48, FAKE, FAKE, 1 << 20, None, 0, None) == PQ_ERR_SHAPE   # K % 32
     assert g(C.byref(ok), 1, 64, FAKE, 8, 64, 64, None, FAKE, 16, None, 0, None) == PQ_ERR_WORKSPACE
     assert b"operand buffer" in lib.pq_last_error()
+
+
+def test_int3_dense_validation(lib):
+    db = pq.pq_int3_dense_bytes
+    assert db(12288, 3072) == 12288 * 3072 * 3 // 8
+    assert db(1, 32) == 12
+    assert db(0, 64) == 0 and db(4, 40) == 0 and db(4, 0) == 0 and db(-1, 64) == 0
+    for f in (lib.pq_int3_pack, lib.pq_int3_unpack):
+        assert f(None, 8, 64, FAKE, None) == PQ_ERR_NULL
+        assert f(FAKE, 8, 64, None, None) == PQ_ERR_NULL
+        assert f(FAKE, 0, 64, FAKE, None) == PQ_ERR_SHAPE
+        assert f(FAKE, 8, 40, FAKE, None) == PQ_ERR_SHAPE          # K % 32
+        assert f(FAKE, 8, 0, FAKE, None) == PQ_ERR_SHAPE
+        assert f(FAKE, (1 << 24) + 1, 64, FAKE, None) == PQ_ERR_SHAPE
+        assert f(C.c_void_p(0x1004), 8, 64, FAKE, None) == PQ_ERR_SHAPE
+        assert f(FAKE, 8, 64, C.c_void_p(0x1008), None) == PQ_ERR_SHAPE
+        assert "pq_int3_" in pq.pq_last_error()
+    p = lib.pq_pack_operand_int3
+    assert p(32, None, FAKE, 8, 64, FAKE, 1 << 20, None) == PQ_ERR_NULL
+    assert p(32, FAKE, FAKE, 8, 64, None, 1 << 20, None) == PQ_ERR_NULL
+    assert p(48, FAKE, FAKE, 8, 96, FAKE, 1 << 20, None) == PQ_ERR_FORMAT
+    assert p(32, FAKE, FAKE, 0, 64, FAKE, 1 << 20, None) == PQ_ERR_SHAPE
+    assert p(32, FAKE, FAKE, 8, 64, FAKE, 16, None) == PQ_ERR_WORKSPACE
+    assert "pq_pack_operand_int3" in pq.pq_last_error()
