@@ -165,6 +165,42 @@ __device__ __forceinline__ void int_scales(const float (&amax)[R], IntScale (&ou
     for (int r = 0; r < R; ++r) out[r].inv = normal[r] ? 1.0f / out[r].s : 0.0f;
   }
 }
+// Scales of four rows at once, for groups of LANES >= 4 lanes (a quad of lanes then lies inside one
+// group).  a[r]: this lane's maximum over its own channels of row r.  The maxima are first combined
+// across the quads of the group (mirror exchanges keep all four values per lane), then inside the
+// quad by a transposing reduction: after two exchange steps lane l holds the group maximum of row
+// l & 3 only.  Each lane derives the scale of its row -- a quarter of the arithmetic of doing all
+// four in every lane -- and the quad broadcasts the four results.  Same values as int_scale.
+template <int FMT, int LANES>
+__device__ __forceinline__ void int_scales_rows4(const float (&a)[4], int lane, IntScale (&out)[4]) {
+  static_assert(LANES >= 4, "a quad must lie inside a group");
+  uint32_t u[4];
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    u[r] = as_u32(a[r]);
+    if constexpr (LANES >= 8) u[r] = max(u[r], dpp_u32<0x141>(u[r]));    // row_half_mirror
+    if constexpr (LANES >= 16) u[r] = max(u[r], dpp_u32<0x140>(u[r]));   // row_mirror
+#pragma unroll
+    for (int off = 16; off < LANES; off <<= 1) u[r] = max(u[r], (uint32_t)__shfl_xor((int)u[r], off, kWave));
+  }
+  const bool odd = lane & 1, upper = lane & 2;
+  uint32_t k01 = odd ? u[1] : u[0], g01 = odd ? u[0] : u[1];
+  uint32_t k23 = odd ? u[3] : u[2], g23 = odd ? u[2] : u[3];
+  k01 = max(k01, dpp_u32<0xB1>(g01));                                    // quad_perm [1,0,3,2]
+  k23 = max(k23, dpp_u32<0xB1>(g23));
+  uint32_t k = upper ? k23 : k01;
+  const uint32_t g = upper ? k01 : k23;
+  k = max(k, dpp_u32<0x4E>(g));                                          // quad_perm [2,3,0,1]
+  const IntScale mine = int_scale<FMT>(as_f32(k));
+  out[0].s = dpp_f32<0x00>(mine.s);                                      // quad_perm [r,r,r,r]
+  out[1].s = dpp_f32<0x55>(mine.s);
+  out[2].s = dpp_f32<0xAA>(mine.s);
+  out[3].s = dpp_f32<0xFF>(mine.s);
+  out[0].inv = dpp_f32<0x00>(mine.inv);
+  out[1].inv = dpp_f32<0x55>(mine.inv);
+  out[2].inv = dpp_f32<0xAA>(mine.inv);
+  out[3].inv = dpp_f32<0xFF>(mine.inv);
+}
 // clip(rint(x * inv), -Q, Q) as a float: clipping first is the same for integer Q, and adding
 // 1.5 * 2^23 rounds to the nearest integer (ties to even) in the adder; the low mantissa bits of
 // the sum are then the two's complement integer.

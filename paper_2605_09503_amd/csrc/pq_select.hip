@@ -103,6 +103,8 @@ struct TensorList {
 
 // fewest rows a workgroup of the error evaluation covers (bounds the number of partial sums)
 constexpr int kQeMinRowsPerBlock = 8;
+constexpr int kQeMaxWaves = 16;           // waves of such a workgroup
+constexpr int64_t kQeParts(int64_t rows) { return (rows / kQeMinRowsPerBlock + 1) * kQeMaxWaves; }
 
 template <int R>
 struct FloatVec;
@@ -123,7 +125,7 @@ struct FloatVec<4> { typedef float type __attribute__((ext_vector_type(4))); };
 // ends up with the wave's total for candidate c: part[((y * gridDim.x + x) * waves + wave) *
 // n_cand + c].
 template <int FMT, int G, int R>
-__global__ __launch_bounds__(512) void quant_error_kernel(TensorList xs, int rows, int K,
+__global__ __launch_bounds__(64 * kQeMaxWaves) void quant_error_kernel(TensorList xs, int rows, int K,
                                                           const int32_t* __restrict__ cands,
                                                           int n_cand, int identity_first, float T,
                                                           int rows_per_block,
@@ -131,11 +133,14 @@ __global__ __launch_bounds__(512) void quant_error_kernel(TensorList xs, int row
   typedef typename FloatVec<R>::type vec_t;
   extern __shared__ __attribute__((aligned(16))) float slots[];     // (K + K / 8) * R floats
   const int tid = threadIdx.x, nthr = blockDim.x;
-  const int lane = tid & 63, wave = tid >> 6;
+  const int lane = tid & 63, n_waves = nthr >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const uint16_t* x = xs.p[blockIdx.y];
   const int row0 = blockIdx.x * rows_per_block;
   const int row_end = min(rows, row0 + rows_per_block);
   const int chunks = K / 8;
+  const int wave_chunks = (chunks + 63) >> 6;
+  const int n_items = n_cand * wave_chunks;
   const float encT = (FMT == kNvfp4) ? nv4_enc_scale(T) : 0.0f;
   double acc = 0.0;
   for (int rg = row0; rg < row_end; rg += R) {
@@ -161,16 +166,23 @@ __global__ __launch_bounds__(512) void quant_error_kernel(TensorList xs, int row
       }
     }
     __syncthreads();
-    for (int cand = 0; cand < n_cand; ++cand) {
+    // work items (candidate, block of 64 chunks), candidate-major, dealt to the waves in turn: the
+    // number of waves is free of K, and a group (at most 32 lanes) never leaves its wave
+    for (int item = wave; item < n_items; item += n_waves) {
+      const int cand = item / wave_chunks;          // uniform over the wave
       const int32_t* perm = nullptr;
       if (!(identity_first && cand == 0)) perm = cands + (int64_t)(cand - identity_first) * K;
       double errs[R];                               // one chain per resident row
 #pragma unroll
       for (int rr = 0; rr < R; ++rr) errs[rr] = 0.0;
-      for (int c0 = 0; c0 < chunks; c0 += nthr) {
-        const int c = c0 + tid;                     // every lane runs the group reduction
+      // every lane runs the group reduction; a lane past the last chunk (its whole group is, K being a
+      // multiple of the group size) works on chunk 0 and its result is dropped
+      const int c_lane = (item - cand * wave_chunks) * 64 + lane;
+      const bool live = c_lane < chunks;
+      {
+        const int c = live ? c_lane : 0;
         float v[R][8];
-        if (c < chunks) {
+        {
           int slot[8];
           if (perm) {
             const int4* pp = reinterpret_cast<const int4*>(perm + c * 8);
@@ -191,19 +203,15 @@ __global__ __launch_bounds__(512) void quant_error_kernel(TensorList xs, int row
               for (int rr = 0; rr < R; ++rr) v[rr][j] = g[rr];
             }
           }
-        } else {
-#pragma unroll
-          for (int rr = 0; rr < R; ++rr)
-#pragma unroll
-            for (int j = 0; j < 8; ++j) v[rr][j] = 0.0f;
         }
+        constexpr bool kRows4 = FMT != kNvfp4 && R == 4 && G >= 32;    // scales shared out over a quad
         float amax[R];
 #pragma unroll
         for (int rr = 0; rr < R; ++rr) {
           float a = 0.0f;
 #pragma unroll
           for (int j = 0; j < 8; ++j) a = fmaxf(a, fabsf(v[rr][j]));
-          amax[rr] = group_max<G / 8>(a);
+          amax[rr] = kRows4 ? a : group_max<G / 8>(a);
         }
         if constexpr (FMT == kNvfp4) {
           Nv4Scale s[R];
@@ -224,7 +232,8 @@ __global__ __launch_bounds__(512) void quant_error_kernel(TensorList xs, int row
           }
         } else {
           IntScale s[R];
-          int_scales<FMT, R>(amax, s);
+          if constexpr (kRows4) int_scales_rows4<FMT, G / 8>(amax, lane, s);
+          else int_scales<FMT, R>(amax, s);
 #pragma unroll
           for (int rr = 0; rr < R; ++rr) {
 #pragma unroll
@@ -246,7 +255,7 @@ __global__ __launch_bounds__(512) void quant_error_kernel(TensorList xs, int row
       double err = errs[0];
 #pragma unroll
       for (int rr = 1; rr < R; ++rr) err += errs[rr];
-      err = wave_sum(err);                 // fixed xor-tree order
+      err = wave_sum(live ? err : 0.0);    // fixed xor-tree order
       if (lane == cand) acc += err;
     }
   }
@@ -325,28 +334,29 @@ __global__ __launch_bounds__(256) void select_tail_kernel(TailArgs a, double* __
   if (threadIdx.x == 0) out[dst] = red[0];
 }
 
-// Launch shape of the error evaluation for `rows` rows per tensor of width K.
+// Launch shape of the error evaluation of n_cand orders for `rows` rows per tensor of width K.
 struct QeShape {
   int r;                 // rows resident in LDS together (1, 2 or 4)
-  int threads;           // a multiple of 64 that divides K / 8 when one exists
+  int threads;
   int rows_per_block;
   int blocks;            // per tensor
   size_t shmem;
   int parts() const { return blocks * (threads / 64); }    // partial sums per tensor and candidate
 };
 
-static QeShape qe_shape(int64_t rows, int64_t K, int n_tensors) {
+static QeShape qe_shape(int64_t rows, int64_t K, int n_tensors, int n_cand) {
   QeShape q;
   const size_t slot_floats = (size_t)(K + K / 8);
   q.r = slot_floats * 16 <= 64 * 1024 ? 4 : slot_floats * 8 <= 64 * 1024 ? 2 : 1;
-  const int chunks = (int)(K / 8);
-  q.threads = 256;
-  for (int t : {512, 384, 256, 192, 128, 64})
-    if (chunks % t == 0) {
-      q.threads = t;
-      break;
-    }
-  if (chunks < 64) q.threads = 64;
+  q.shmem = slot_floats * q.r * sizeof(float);
+  // waves: the work items of a set of resident rows (candidate x block of 64 chunks) are dealt to the
+  // waves in turn; take the fewest waves that need the fewest turns.  Two workgroups share a compute
+  // unit when their rows fit its LDS twice (one stages while the other computes): twelve waves each
+  // then, sixteen otherwise.
+  const int items = n_cand * (int)((K / 8 + 63) / 64);
+  const int max_waves = 2 * q.shmem <= 160 * 1024 ? 12 : kQeMaxWaves;
+  const int turns = (items + max_waves - 1) / max_waves;
+  q.threads = 64 * ((items + turns - 1) / turns);
   // enough workgroups to fill the chip several times over, at least kQeMinRowsPerBlock rows each
   int64_t rpb = rows * n_tensors / 2048;
   rpb = rpb / q.r * q.r;
@@ -354,7 +364,6 @@ static QeShape qe_shape(int64_t rows, int64_t K, int n_tensors) {
   if (rpb > 64) rpb = 64;
   q.rows_per_block = (int)rpb;
   q.blocks = (int)((rows + rpb - 1) / rpb);
-  q.shmem = slot_floats * q.r * sizeof(float);
   return q;
 }
 
@@ -429,9 +438,9 @@ static size_t carve_select(void* base, int64_t M, int64_t N, int64_t K, int n_ba
   size_t o_keys = take((size_t)PQ_MAX_ALPHAS * K * 8);
   size_t o_cands = take((size_t)PQ_MAX_ALPHAS * K * 4);
   size_t o_rank = take((size_t)PQ_MAX_ALPHAS * K * 4);
-  // a workgroup covers at least kQeMinRowsPerBlock rows with at most 8 waves: no more partial sums
-  // than rows + 8 per tensor
-  size_t o_rowerr = take((size_t)((int64_t)n_batches * (M + 8) + (N + 8)) * kMaxCand * 8);
+  // a workgroup covers at least kQeMinRowsPerBlock rows with at most kQeMaxWaves waves: no more
+  // partial sums than kQeParts(rows) per tensor
+  size_t o_rowerr = take((size_t)((int64_t)n_batches * kQeParts(M) + kQeParts(N)) * kMaxCand * 8);
   size_t o_sums = take(((size_t)(n_batches + 1) * kMaxCand + 2 + PQ_MAX_ALPHAS) * 8);
   if (w) {
     char* b = (char*)base;
@@ -448,14 +457,14 @@ size_t select_workspace_bytes(int64_t M, int64_t N, int64_t K, int n_batches) {
   return carve_select(nullptr, M, N, K, n_batches, nullptr);
 }
 
-size_t quant_error_workspace_bytes(int64_t rows) { return align_up((size_t)(rows + 8) * 8, 256); }
+size_t quant_error_workspace_bytes(int64_t rows) { return align_up((size_t)kQeParts(rows) * 8, 256); }
 
 int run_quant_error(pq_format fmt, int group, const void* x, int64_t rows, int64_t K,
                     const int32_t* perm, float ts, double* err_out, void* ws, hipStream_t st) {
   double* part = (double*)ws;
   TensorList tl;
   for (int b = 0; b < kMaxMomentBatches; ++b) tl.p[b] = (const uint16_t*)x;
-  const QeShape q = qe_shape(rows, K, 1);
+  const QeShape q = qe_shape(rows, K, 1, 1);
   int rc = launch_quant_error(fmt, group, tl, 1, rows, (int)K, q, perm, 1, perm ? 0 : 1, ts, part, st);
   if (rc) return rc;
   hipLaunchKernelGGL(reduce_rows_kernel, dim3(1, 1), dim3(256), 0, st, part, (int64_t)q.parts(), 1, 1, err_out);
@@ -533,7 +542,7 @@ int run_select(pq_format fmt, int group, const double* act_sumsq, const double* 
   if ((rc = launch_candidate_orders(act_sumsq, w_sumsq, K, alphas, n_alpha, W.keys, W.rank, W.cands, st))) return rc;
   double* sums = W.sums;
   // activations: all batches of a launch share one grid (up to kMaxMomentBatches per launch)
-  const QeShape qa = qe_shape(M, K, n_batches < kMaxMomentBatches ? n_batches : kMaxMomentBatches);
+  const QeShape qa = qe_shape(M, K, n_batches < kMaxMomentBatches ? n_batches : kMaxMomentBatches, n_cand);
   for (int b0 = 0; b0 < n_batches; b0 += kMaxMomentBatches) {
     const int nb = n_batches - b0 < kMaxMomentBatches ? n_batches - b0 : kMaxMomentBatches;
     TensorList tl;
@@ -543,7 +552,7 @@ int run_select(pq_format fmt, int group, const double* act_sumsq, const double* 
     if (rc) return rc;
   }
   double* w_part = W.row_err + (size_t)n_batches * qa.parts() * n_cand;
-  const QeShape qw = qe_shape(N, K, 1);
+  const QeShape qw = qe_shape(N, K, 1, n_cand);
   TensorList wl;
   for (int b = 0; b < kMaxMomentBatches; ++b) wl.p[b] = (const uint16_t*)w;
   rc = launch_quant_error(fmt, group, wl, 1, N, (int)K, qw, W.cands, n_cand, 1, w_ts, w_part, st);
