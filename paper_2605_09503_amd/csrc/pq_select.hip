@@ -47,37 +47,41 @@ __global__ __launch_bounds__(256) void key_kernel(const double* __restrict__ sa,
   key[(int64_t)blockIdx.y * K + i] = k;
 }
 
-constexpr int kRankChunk = 256;    // keys compared per workgroup of the counting pass
+constexpr int kRankChunk = 128;    // keys compared per workgroup of the counting pass (divides 256)
 
 // Counting pass of the stable descending sort: workgroup (x, y, z) compares its 256 channels i
-// with the 256 keys j of chunk y of candidate z and adds how many of them sort before i to
+// with the kRankChunk keys j of chunk y of candidate z and adds how many of them sort before i to
 // rank[z][i] (integer atomics: the sum does not depend on the order of the workgroups).
-// Chunks are aligned with the channel blocks, so every key of an earlier chunk has j < i (it
-// sorts before i when key_j >= key_i), every key of a later chunk has j > i (key_j > key_i), and
-// only the diagonal workgroup needs the index comparison: one compare and one add per key.
+// A chunk lies inside one channel block, so every key of a chunk in an earlier block has j < i (it
+// sorts before i when key_j >= key_i), every key in a later block has j > i (key_j > key_i), and
+// only the chunks of the workgroup's own block need the index comparison.  A wave's time is the
+// chain of its scalar key loads, hence short chunks and deep unrolling.
 __global__ __launch_bounds__(256) void rank_count_kernel(const double* __restrict__ keys, int K,
                                                          int32_t* __restrict__ rank) {
-  __shared__ double tile[kRankChunk];
   const double* key = keys + (int64_t)blockIdx.z * K;
   const int i = blockIdx.x * 256 + threadIdx.x;
   const int j0 = blockIdx.y * kRankChunk;
   const int n = min(kRankChunk, K - j0);
-  if ((int)threadIdx.x < n) tile[threadIdx.x] = key[j0 + threadIdx.x];
-  __syncthreads();
   if (i >= K) return;
   const double ki = key[i];
+  // the keys of the chunk are the same for every lane: they come through scalar loads and sit in
+  // scalar registers, the compare takes them as an operand
+  const double* tile = key + j0;
   int before = 0;
-  if (blockIdx.y < blockIdx.x) {
-#pragma unroll 8
+  const int key_block = blockIdx.y / (256 / kRankChunk);      // the channel block the chunk lies in
+  if (key_block < (int)blockIdx.x) {
+#pragma unroll 32
     for (int t = 0; t < n; ++t) before += tile[t] >= ki ? 1 : 0;
-  } else if (blockIdx.y > blockIdx.x) {
-#pragma unroll 8
+  } else if (key_block > (int)blockIdx.x) {
+#pragma unroll 32
     for (int t = 0; t < n; ++t) before += tile[t] > ki ? 1 : 0;
   } else {
-#pragma unroll 8
+#pragma unroll 32
     for (int t = 0; t < n; ++t) {
+      // without short-circuit evaluation: no branches, the loads of a whole unrolled trip go out together
       const double kj = tile[t];
-      before += (kj > ki || (kj == ki && j0 + t < i)) ? 1 : 0;
+      const int gt = kj > ki ? 1 : 0, eq = kj == ki ? 1 : 0, earlier = j0 + t < i ? 1 : 0;
+      before += gt | (eq & earlier);
     }
   }
   atomicAdd(&rank[(int64_t)blockIdx.z * K + i], before);
