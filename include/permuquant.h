@@ -19,8 +19,11 @@
  *   - bf16 tensors are passed as const void* to 16-bit elements.
  *   - Unless a parameter says "host", every pointer is DEVICE memory owned by the caller and
  *     must stay valid until the work queued on `stream` has finished.  Tensor pointers must be
- *     16-byte aligned.  The library allocates nothing; scratch memory comes in through
- *     `workspace` (size from pq_workspace_bytes()).
+ *     16-byte aligned.  The library allocates no device memory; scratch memory comes in
+ *     through `workspace` (size from pq_workspace_bytes()).  The one host allocation: the two
+ *     selection calls, which synchronise anyway, read their error sums back through a small
+ *     pinned host buffer (4 KB for up to 30 batches) that the calling thread allocates at its
+ *     first such call and keeps until the process ends.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls are
  *     asynchronous on it unless stated otherwise.
  *   - All arguments are validated on the host before anything is launched.  Every function

@@ -48,6 +48,7 @@ int run_select(pq_format fmt, int group, const double* act_sumsq, const double* 
 int launch_candidate_orders(const double* act_sumsq, const double* w_sumsq, int64_t K, const double* alphas,
                             int n_alpha, double* keys, int32_t* rank, int32_t* cands, hipStream_t st);
 int launch_identity_order(int32_t* perm, int64_t K, hipStream_t st);
+double* pinned_doubles(size_t n);     // the calling thread's pinned host buffer, kept for the process lifetime
 int launch_round_robin(const int32_t* order, int64_t K, int group, int32_t* perm, hipStream_t st);
 size_t random_order_workspace_bytes(int64_t K);      // also enough for one candidate order (keys + ranks)
 int launch_random_order(uint64_t seed, int64_t K, int32_t* perm, void* ws, hipStream_t st);

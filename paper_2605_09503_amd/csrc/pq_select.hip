@@ -535,6 +535,28 @@ int launch_identity_order(int32_t* perm, int64_t K, hipStream_t st) {
   return check_hip(hipGetLastError(), "iota_kernel");
 }
 
+// A pinned host buffer of at least n doubles that the calling thread keeps until the process ends
+// (a device-to-host copy into pageable memory goes through a staging copy and costs some 10 us
+// more).  Grown, never shrunk; nullptr when the allocation fails.
+double* pinned_doubles(size_t n) {
+  thread_local double* buf = nullptr;
+  thread_local size_t cap = 0;
+  if (n > cap) {
+    if (buf) (void)hipHostFree(buf);
+    buf = nullptr;
+    cap = 0;
+    const size_t want = n < 512 ? 512 : n;
+    void* p = nullptr;
+    if (hipHostMalloc(&p, want * sizeof(double), hipHostMallocDefault) != hipSuccess) {
+      (void)hipGetLastError();
+      return nullptr;
+    }
+    buf = (double*)p;
+    cap = want;
+  }
+  return buf;
+}
+
 int run_select(pq_format fmt, int group, const double* act_sumsq, const double* w_sumsq, int64_t K,
                const void* const* x_calib, int n_batches, int64_t M, const void* w, int64_t N,
                float act_ts, float w_ts, const double* alphas, int n_alpha, double tau,
@@ -568,9 +590,9 @@ int run_select(pq_format fmt, int group, const double* act_sumsq, const double* 
 
   const size_t n_tot = (size_t)(n_batches + 1) * kMaxCand;      // offset of the two totals
   const size_t n_sums = n_tot + 2 + (size_t)n_alpha;
-  std::vector<double> h(n_sums);
-  if ((rc = check_hip(hipMemcpyAsync(h.data(), sums, n_sums * 8, hipMemcpyDeviceToHost, st), "copy sums")))
-    return rc;
+  double* h = pinned_doubles(n_sums);
+  if (!h) return fail(PQ_ERR_HIP, "pq_select_perm: no pinned host memory for %zu sums", n_sums);
+  if ((rc = check_hip(hipMemcpyAsync(h, sums, n_sums * 8, hipMemcpyDeviceToHost, st), "copy sums"))) return rc;
   if ((rc = check_hip(hipStreamSynchronize(st), "hipStreamSynchronize"))) return rc;
 
   const double sum_x2 = h[n_tot], sum_w2 = h[n_tot + 1];

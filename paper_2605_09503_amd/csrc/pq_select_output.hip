@@ -277,8 +277,9 @@ int run_select_output(pq_format fmt, int group, const double* act_sumsq, const d
     if ((rc = check_hip(hipGetLastError(), "sqdiff kernels"))) return rc;
   }
 
-  std::vector<double> h(kNumSums);
-  if ((rc = check_hip(hipMemcpyAsync(h.data(), W.sums, (size_t)kNumSums * 8, hipMemcpyDeviceToHost, st), "copy sums")))
+  double* h = pinned_doubles(kNumSums);
+  if (!h) return fail(PQ_ERR_HIP, "pq_select_perm_output_error: no pinned host memory for the sums");
+  if ((rc = check_hip(hipMemcpyAsync(h, W.sums, (size_t)kNumSums * 8, hipMemcpyDeviceToHost, st), "copy sums")))
     return rc;
   if ((rc = check_hip(hipStreamSynchronize(st), "hipStreamSynchronize"))) return rc;
 
