@@ -99,7 +99,8 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(const uint16_t* __re
                                                             const int32_t* __restrict__ perm,
                                                             const float* __restrict__ tensor_scale,
                                                             uint32_t* __restrict__ codes,
-                                                            void* __restrict__ scales) {
+                                                            void* __restrict__ scales, int staged) {
+  extern __shared__ __align__(16) uint16_t row_lds[];       // staged: the row, K elements
   float T = 0.0f, encT = 0.0f;
   if constexpr (FMT == kNvfp4) {
     T = *tensor_scale;
@@ -108,6 +109,15 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(const uint16_t* __re
   const int64_t row = blockIdx.x;
   const uint16_t* xr = x + row * ld;
   const int chunks = (int)(K / 8);
+  // gather: the row is read once in whole lines and the channels are picked out of LDS (scattered
+  // two-byte reads from memory keep the texture addresser busy a cycle per lane)
+  const uint16_t* src = xr;
+  if (staged) {
+    for (int c = threadIdx.x; c < chunks; c += 256)
+      reinterpret_cast<uint4*>(row_lds)[c] = *reinterpret_cast<const uint4*>(xr + (int64_t)c * 8);
+    __syncthreads();
+    src = row_lds;
+  }
   // all 256 lanes iterate together so the group reduction always sees whole groups
   for (int c0 = 0; c0 < chunks; c0 += 256) {
     int c = c0 + threadIdx.x;
@@ -116,10 +126,10 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(const uint16_t* __re
       if (perm) {
         const int4* pp = reinterpret_cast<const int4*>(perm + (int64_t)c * 8);
         int4 i0 = pp[0], i1 = pp[1];
-        v[0] = bf16_to_f32(xr[i0.x]); v[1] = bf16_to_f32(xr[i0.y]);
-        v[2] = bf16_to_f32(xr[i0.z]); v[3] = bf16_to_f32(xr[i0.w]);
-        v[4] = bf16_to_f32(xr[i1.x]); v[5] = bf16_to_f32(xr[i1.y]);
-        v[6] = bf16_to_f32(xr[i1.z]); v[7] = bf16_to_f32(xr[i1.w]);
+        v[0] = bf16_to_f32(src[i0.x]); v[1] = bf16_to_f32(src[i0.y]);
+        v[2] = bf16_to_f32(src[i0.z]); v[3] = bf16_to_f32(src[i0.w]);
+        v[4] = bf16_to_f32(src[i1.x]); v[5] = bf16_to_f32(src[i1.y]);
+        v[6] = bf16_to_f32(src[i1.z]); v[7] = bf16_to_f32(src[i1.w]);
       } else {
         unpack8(*reinterpret_cast<const uint4*>(xr + (int64_t)c * 8), v);
       }
@@ -145,8 +155,10 @@ static int launch_q(const void* x, int64_t rows, int64_t K, int64_t ld, const in
                        (const uint4*)x, n_chunks, ts, (uint32_t*)codes, scales);
     return check_hip(hipGetLastError(), "quantize_flat_kernel");
   }
-  hipLaunchKernelGGL((quantize_rows_kernel<FMT, G>), dim3((unsigned)rows), dim3(256), 0, st,
-                     (const uint16_t*)x, K, ld, perm, ts, (uint32_t*)codes, scales);
+  // with a gather the row goes through LDS when it fits 48 KB
+  const int staged = perm && K * 2 <= 48 * 1024 ? 1 : 0;
+  hipLaunchKernelGGL((quantize_rows_kernel<FMT, G>), dim3((unsigned)rows), dim3(256), staged ? (size_t)K * 2 : 0, st,
+                     (const uint16_t*)x, K, ld, perm, ts, (uint32_t*)codes, scales, staged);
   return check_hip(hipGetLastError(), "quantize_rows_kernel");
 }
 
