@@ -19,8 +19,6 @@
 // The final argmin / acceptance decision is a handful of scalar operations and runs on the host.
 #include <string.h>
 
-#include <vector>
-
 #include "pq_device.h"
 #include "pq_host.h"
 

@@ -8,8 +8,6 @@
 // and deterministic (fixed summation order).
 #include <string.h>
 
-#include <vector>
-
 #include "pq_qgemm_common.h"
 
 namespace pq {
