@@ -124,8 +124,8 @@ struct FloatVec<4> { typedef float type __attribute__((ext_vector_type(4))); };
 // lane reads the eight channel indices of its chunk once and gathers the R rows of each channel
 // with one LDS read; the quantizer is the lane-cooperative one of the runtime kernels; squared
 // errors are accumulated in fp64 (every product below is exact in fp64).  Lane c of every wave
-// ends up with the wave's total for candidate c: part[((y * gridDim.x + x) * waves + wave) *
-// n_cand + c].
+// ends up with the wave's total for candidate c: part[y][c][x * waves + wave] (candidate-major, so
+// that the sums over the workgroups read contiguous memory).
 template <int FMT, int G, int R>
 __global__ __launch_bounds__(64 * kQeMaxWaves) void quant_error_kernel(TensorList xs, int rows, int K,
                                                           const int32_t* __restrict__ cands,
@@ -262,7 +262,7 @@ __global__ __launch_bounds__(64 * kQeMaxWaves) void quant_error_kernel(TensorLis
     }
   }
   if (lane < n_cand)
-    part[(((int64_t)blockIdx.y * gridDim.x + blockIdx.x) * (nthr >> 6) + wave) * n_cand + lane] = acc;
+    part[((int64_t)blockIdx.y * n_cand + lane) * ((int64_t)gridDim.x * n_waves) + (int64_t)blockIdx.x * n_waves + wave] = acc;
 }
 
 // out[seg][c] = sum over the rows of segment seg of row_err[r][c]; one workgroup per
@@ -292,8 +292,8 @@ __global__ __launch_bounds__(256) void reduce_rows_kernel(const double* __restri
 //   next 2                          sum of act_sumsq, sum of w_sumsq      -> out[(n_batches + 1) * kMaxCand + 0 / 1]
 //   next n_alpha                    number of channels candidate j moves  -> out[... + 2 + j] (as a double)
 struct TailArgs {
-  const double* x_part;     // [n_batches][x_parts][n_cand]
-  const double* w_part;     // [w_parts][n_cand]
+  const double* x_part;     // [n_batches][n_cand][x_parts]
+  const double* w_part;     // [n_cand][w_parts]
   const double* act_sumsq;
   const double* w_sumsq;
   const int32_t* cands;     // [n_alpha][K]
@@ -312,7 +312,7 @@ __global__ __launch_bounds__(256) void select_tail_kernel(TailArgs a, double* __
     const int seg = is_w ? 0 : b / a.n_cand, c = is_w ? b - n_x : b % a.n_cand;
     const int64_t n = is_w ? a.w_parts : a.x_parts;
     const double* base = is_w ? a.w_part : a.x_part + (int64_t)seg * n * a.n_cand;
-    for (int64_t r = threadIdx.x; r < n; r += 256) s += base[r * a.n_cand + c];
+    for (int64_t r = threadIdx.x; r < n; r += 256) s += base[(int64_t)c * n + r];
     dst = (int64_t)(is_w ? a.n_batches : seg) * kMaxCand + c;
   } else if (b < n_x + a.n_cand + 2) {
     const int which = b - n_x - a.n_cand;
@@ -395,7 +395,7 @@ static int launch_qe(const TensorList& xs, int n_tensors, int64_t rows, int K, c
   }
 }
 
-// part: [n_tensors][q.parts()][n_cand]
+// part: [n_tensors][n_cand][q.parts()]
 static int launch_quant_error(pq_format fmt, int group, const TensorList& x, int n_tensors, int64_t rows,
                               int K, const QeShape& q, const int32_t* cands, int n_cand,
                               int identity_first, float T, double* part, hipStream_t st) {
@@ -423,7 +423,7 @@ struct SelectWs {
   double* keys;      // [PQ_MAX_ALPHAS][K]
   int32_t* cands;    // [PQ_MAX_ALPHAS][K]
   int32_t* rank;     // [PQ_MAX_ALPHAS][K] position of every channel in the sorted order
-  double* row_err;   // partial error sums: [n_batches][parts(M)][n_cand], then [parts(N)][n_cand]
+  double* row_err;   // partial error sums: [n_batches][n_cand][parts(M)], then [n_cand][parts(N)]
   double* sums;      // [(n_batches + 1) * kMaxCand + 2 + PQ_MAX_ALPHAS]: per-batch errors, weight
                      // errors, |X|^2, |W|^2, moved-channel counts
 };
