@@ -282,3 +282,31 @@ def test_int3_dense_validation(lib):
     assert p(32, FAKE, FAKE, 0, 64, FAKE, 1 << 20, None) == PQ_ERR_SHAPE
     assert p(32, FAKE, FAKE, 8, 64, FAKE, 16, None) == PQ_ERR_WORKSPACE
     assert "pq_pack_operand_int3" in pq.pq_last_error()
+
+
+def test_header_is_plain_c_and_links(tmp_path, lib):
+    """include/permuquant.h compiles as C99 without a HIP or C++ header in sight, and a C program linked
+    against the library reaches the host-side argument checks."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no C compiler")
+    src = tmp_path / "use_pq.c"
+    src.write_text(
+        '#include <stdio.h>\n'
+        '#include "permuquant.h"\n'
+        'int main(void) {\n'
+        '  int rc = pq_quantize_act(PQ_FMT_INT4, 64, NULL, 8, 64, 64, NULL, NULL, NULL, NULL, NULL);\n'
+        '  printf("%d %d %s\\n", pq_version(), rc, pq_last_error());\n'
+        '  return rc == PQ_ERR_NULL ? 0 : 1;\n'
+        '}\n')
+    exe = tmp_path / "use_pq"
+    libdir = os.path.dirname(pq.lib_path())
+    cmd = [gcc, "-std=c99", "-pedantic", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"), str(src),
+           "-L", libdir, "-lpermuquant", "-Wl,-rpath," + libdir, "-o", str(exe)]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+    r = subprocess.run([str(exe)], capture_output=True, text=True, timeout=60)
+    assert r.returncode == 0, r.stdout + r.stderr
+    assert "NULL" in r.stdout
