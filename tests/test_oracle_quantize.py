@@ -280,3 +280,137 @@ def test_packed_codes_layout():
     q = Qz.quantize_int(x, 16, F.FMT_INT4)
     p = Qz.packed_codes(F.FMT_INT4, q)
     assert p.shape == (1, 8) and p[0, 0] == (7 | (9 << 4)) and p[0, 1] == 1
+
+
+# ----------------------------------------------------------------------------------------------
+# The binary32 steps of the quantizers, re-derived in exact rational arithmetic.
+#
+# Where a floating-point value decides an integer code, oracle and kernels take the decision in
+# binary32, step by step:  INT    s = fl(amax / Q), r = fl(1 / s), v = fl(x r), z = rint(v);
+#                          NVFP4  r_T = fl(1 / T), t = fl(fl(amax r_T) / 6), byte = E4M3(t),
+#                                 d = fl(E4M3(byte) T), r = fl(1 / d), v = fl(x r), code = E2M1(|v|).
+# Below every fl() is a rounding of an exact fraction to 24 significant bits, ties to even, written
+# with integers only; E4M3 and E2M1 are nearest-value searches over their value lists.  The inputs
+# were picked (by a search over bf16 values) so that leaving out any single fl() changes a code or
+# a scale byte: a sequence with one step kept in higher precision fails here.
+from fractions import Fraction
+
+
+def _rn24(q: Fraction) -> Fraction:
+    if q == 0:
+        return q
+    a = abs(q)
+    e = a.numerator.bit_length() - a.denominator.bit_length()
+    if Fraction(2) ** e > a:
+        e -= 1
+    assert Fraction(2) ** e <= a < Fraction(2) ** (e + 1) and -126 <= e <= 127
+    ulp = Fraction(2) ** (e - 23)
+    n = a / ulp
+    fl = n.numerator // n.denominator
+    rem = n - fl
+    if rem > Fraction(1, 2) or (rem == Fraction(1, 2) and fl % 2 == 1):
+        fl += 1
+    return (fl * ulp) if q > 0 else -(fl * ulp)
+
+
+def _rint_half_even(q: Fraction) -> int:
+    fl = q.numerator // q.denominator
+    rem = q - fl
+    if rem > Fraction(1, 2) or (rem == Fraction(1, 2) and fl % 2 == 1):
+        fl += 1
+    return fl
+
+
+def _nearest(values, q: Fraction) -> int:
+    """Index of the value nearest to q >= 0 in an ascending list, ties to the even index, saturating."""
+    best = 0
+    for i, v in enumerate(values):
+        d, db = abs(v - q), abs(values[best] - q)
+        if d < db or (d == db and i % 2 == 0):
+            best = i
+    return best
+
+
+_E4M3_VALUES = [Fraction(m, 8) * Fraction(2) ** -6 for m in range(8)] + \
+               [(1 + Fraction(m, 8)) * Fraction(2) ** e for e in range(-6, 9) for m in range(8)][:-1]
+_E2M1_VALUES = [Fraction(v) for v in (0, 0.5, 1, 1.5, 2, 3, 4, 6)]
+
+
+def _int_codes_rational(x, Q):
+    xs = [Fraction(float(v)) for v in x]
+    amax = max(abs(v) for v in xs)
+    s = _rn24(amax / Q)
+    r = _rn24(1 / s)
+    return s, [max(-Q, min(Q, _rint_half_even(_rn24(v * r)))) for v in xs]
+
+
+def _nvfp4_rational(x, T):
+    xs = [Fraction(float(v)) for v in x]
+    T = Fraction(float(np.float32(T)))
+    amax = max(abs(v) for v in xs)
+    t = _rn24(_rn24(amax * _rn24(1 / T)) / 6)
+    byte = _nearest(_E4M3_VALUES, t)
+    d = _rn24(_E4M3_VALUES[byte] * T)
+    r = _rn24(1 / d)
+    return byte, [_nearest(_E2M1_VALUES, abs(_rn24(v * r))) for v in xs]
+
+
+def test_e4m3_value_list_of_the_rational_check():
+    assert len(_E4M3_VALUES) == 127 and _E4M3_VALUES[-1] == 448 and _E4M3_VALUES[1] == Fraction(1, 512)
+    assert [float(v) for v in _E4M3_VALUES] == [float(v) for v in F.e4m3_decode(np.arange(127))]
+
+
+_INT_SENSITIVE = [
+    (7, [-1.025910023599863e-09, 0.000583648681640625, -0.00116729736328125, 3.119930624961853e-08]),
+    (7, [-0.0025482177734375, -2.8172507882118225e-08, 0.005096435546875, 0.00025177001953125]),
+    (7, [2.293381839990616e-08, 210.0, 75.0, -0.0069580078125]),
+    (3, [976.0, 944.0, 4.678964614868164e-06, -5664.0]),
+    (7, [-5.125999450683594e-06, 2.3365020751953125e-05, -1.6689300537109375e-06, -1.3262033462524414e-06]),
+    (7, [0.00677490234375, -3.623426891863346e-09, 1.2922100722789764e-08, -0.0135498046875]),
+    (7, [91.0, 32.5, -32.5, 6.5]),
+]
+
+
+@pytest.mark.parametrize("Q,x", _INT_SENSITIVE)
+def test_int_binary32_sequence_in_rational_arithmetic(Q, x):
+    fmt = F.FMT_INT4 if Q == 7 else F.FMT_INT3
+    q = Qz.quantize_int(np.array([x]), len(x), fmt)
+    s, z = _int_codes_rational(x, Q)
+    assert Fraction(float(q.scale[0, 0])) == s
+    assert q.z[0].tolist() == z
+
+
+_NVFP4_SENSITIVE = [
+    # (T, amax element, +-x): the reciprocal of the block scale, then the product, decide a code
+    (1.0, [1.4375, 0.29296875, -0.29296875]),
+    (1.0, [1.4375, 0.5859375, -0.5859375]),
+    (1.0, [0.859375, 0.03515625, -0.03515625]),
+    (1.0, [0.859375, 0.17578125, -0.17578125]),
+    # the reciprocal of T, then the product with the block maximum, decide the scale byte
+    (0.29891306161880493, [0.040283203125, 0.01, -0.02]),
+    (0.394097238779068, [0.006927490234375, 0.001, -0.003]),
+]
+
+
+@pytest.mark.parametrize("T,head", _NVFP4_SENSITIVE)
+def test_nvfp4_binary32_sequence_in_rational_arithmetic(T, head):
+    x = np.zeros(16)
+    x[:len(head)] = F.bf16_bits_to_f64(F.f64_to_bf16_bits_rne(np.array(head)))
+    q = Qz.quantize_nvfp4(x[None, :], np.float32(T))
+    byte, idx = _nvfp4_rational(x, T)
+    assert int(q.scale[0, 0]) == byte
+    assert (q.code[0] & 7).tolist() == idx
+
+
+def test_binary32_sequence_on_random_rows():
+    rng = np.random.default_rng(77)
+    for trial in range(40):
+        x = F.bf16_bits_to_f64(F.f64_to_bf16_bits_rne(rng.standard_normal(16) * np.exp(rng.standard_normal(16))))
+        Q = 7 if trial % 2 else 3
+        q = Qz.quantize_int(x[None, :], 16, F.FMT_INT4 if Q == 7 else F.FMT_INT3)
+        s, z = _int_codes_rational(x, Q)
+        assert Fraction(float(q.scale[0, 0])) == s and q.z[0].tolist() == z
+        T = np.float32(rng.uniform(0.001, 0.01))
+        qn = Qz.quantize_nvfp4(x[None, :], T)
+        byte, idx = _nvfp4_rational(x, T)
+        assert int(qn.scale[0, 0]) == byte and (qn.code[0] & 7).tolist() == idx
