@@ -47,6 +47,18 @@ def qbytes_out(fmt, g, M, K):
     return (0.5 + (1.0 / 16 if fmt == 0 else 4.0 / g)) * M * K
 
 
+def blas_threads():
+    """Threads the oracle's matmul actually runs on (its elementwise steps run on one)."""
+    try:
+        from threadpoolctl import threadpool_info
+        n = [int(p.get("num_threads", 0)) for p in threadpool_info() if p.get("user_api") in ("blas", "openmp")]
+        if n and max(n) > 0:
+            return max(n)
+    except Exception:
+        pass
+    return int(os.environ.get("OMP_NUM_THREADS", 0)) or os.cpu_count()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -386,7 +398,7 @@ def main():
             used += 1
         t_step_cpu = t_w_cpu + t_act_cpu * nb / used + t_fwd_full
         cpu = {"value": flops / t_step_cpu / 1e12, "unit": "TFLOP/s",
-               "cores": os.cpu_count(), "kind": "oracle",
+               "cores": blas_threads(), "kind": "oracle",
                "sample": "the oracle (numpy fp64) on the same workload: calibration half (moments, sorts, error of "
                          "the original and six candidate orders) measured on W and on %d of %d calibration batches "
                          "(%.1f s + %.1f s, scaled to all batches), forward half (quantize_act + dequantized "
