@@ -349,7 +349,7 @@ struct QeShape {
 static QeShape qe_shape(int64_t rows, int64_t K, int n_tensors, int n_cand) {
   QeShape q;
   const size_t slot_floats = (size_t)(K + K / 8);
-  q.r = slot_floats * 16 <= 64 * 1024 ? 4 : slot_floats * 8 <= 64 * 1024 ? 2 : 1;
+  q.r = slot_floats * 16 <= 64 * 1024 ? 4 : slot_floats * 8 <= 128 * 1024 ? 2 : 1;
   q.shmem = slot_floats * q.r * sizeof(float);
   // waves: the work items of a set of resident rows (candidate x block of 64 chunks) are dealt to the
   // waves in turn; take the fewest waves that need the fewest turns.  Two workgroups share a compute

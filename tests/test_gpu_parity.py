@@ -327,7 +327,8 @@ def test_quant_error(fmt, g):
 @pytest.mark.parametrize("fmt,g,rows,K", [
     (pq.FMT_NVFP4, 16, 5, 272),       # 34 chunks of 8: a single wave with idle lanes
     (pq.FMT_INT4, 32, 13, 4096),      # two rows resident
-    (pq.FMT_INT4, 64, 9, 8192),       # one row resident
+    (pq.FMT_INT4, 64, 9, 8192),       # two rows resident, one workgroup per compute unit
+    (pq.FMT_INT4, 64, 5, 16384),      # one row resident
     (pq.FMT_INT3, 32, 70, 3072),      # four rows resident, 384 threads, 70 = 4 * 17 + 2 rows
     (pq.FMT_NVFP4, 16, 3, 12288),     # widest configuration, fewer rows than a workgroup covers
     (pq.FMT_INT4, 256, 1, 256),       # one row, one group
