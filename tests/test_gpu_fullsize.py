@@ -147,50 +147,82 @@ def _cand_error(args):
     return OC.squared_error(fmt, g, OF.bf16_bits_to_f64(bits), perm, ts)
 
 
-def test_select_perm_full_size_c1():
-    """Whole calibration of the benchmark workload against the oracle (the oracle's error sums are
-    computed by a pool of threads, one (candidate, batch) pair each; the arithmetic is unchanged)."""
-    cfg = synth.CONFIGS["c1"]
-    fmt, g, M, N, K, nb = cfg.fmt, cfg.group, cfg.M, cfg.N, cfg.K, cfg.n_calib
+def _oracle_selection(fmt, g, batches, w_bits, ta, tw, workers=8):
+    """The oracle's selection with its error sums computed by a pool of threads, one (candidate, tensor)
+    pair each (numpy releases the GIL in its array loops); the arithmetic is that of
+    oracle.calib.select_permutation.  Returns (candidate orders incl. None first, E per order, key gaps,
+    sum_x2, sum_w2)."""
+    K = w_bits.shape[1]
+    nb = len(batches)
+    ref_sa = np.zeros(K)
+    for b in batches:
+        ref_sa += OC.column_sumsq(OF.bf16_bits_to_f64(b))
+    ref_sw = OC.column_sumsq(OF.bf16_bits_to_f64(w_bits))
+    cands = [None] + [OC.sort_descending(OC.joint_key(ref_sa, ref_sw, a)) for a in OC.DEFAULT_ALPHAS]
+    gaps = [OC.min_relative_key_gap(OC.joint_key(ref_sa, ref_sw, a), p)
+            for a, p in zip(OC.DEFAULT_ALPHAS, cands[1:])]
+    tasks = [(fmt, g, bits, p, ts) for p in cands for bits, ts in [(b, ta) for b in batches] + [(w_bits, tw)]]
+    with cf.ThreadPoolExecutor(max_workers=workers) as ex:
+        errs = list(ex.map(_cand_error, tasks))
+    errs = np.array(errs).reshape(len(cands), nb + 1)
+    sum_x2, sum_w2 = float(np.sum(ref_sa)), float(np.sum(ref_sw))
+    E = [float(sum(e[:nb])) / sum_x2 + float(e[nb]) / sum_w2 for e in errs]
+    return cands, E, gaps, sum_x2, sum_w2
+
+
+# (config, calibration batches: all eight for the benchmark's INT4 layer, two or three elsewhere -- the
+# oracle's cost is in the rows, the kernels' launch shapes are in K, N and the format)
+SELECT_CASES = [("c1", 8), ("c2", 3), ("c3up", 2), ("c3down", 2), ("c4", 2)]
+
+
+@pytest.mark.parametrize("name,nb", SELECT_CASES)
+def test_select_perm_full_size(name, nb):
+    """Whole selection at the full shape of every configuration against the oracle: error sums of the
+    original and the six candidate orders, argmin, acceptance and the permutation."""
+    cfg = synth.CONFIGS[name]
+    fmt, g, M, N, K = cfg.fmt, cfg.group, cfg.M, cfg.N, cfg.K
     t0 = time.time()
     st = synth.make_struct(cfg)
     batches = [synth.make_batch(st, b) for b in range(nb)]
-    _say("select full-size c1: inputs generated in %.1f s" % (time.time() - t0))
+    _say("select full-size %s (K=%d, %d batches): inputs generated in %.1f s" % (name, K, nb, time.time() - t0))
     xs = [pq.bf16_from_bits(b, DEV) for b in batches]
     w = pq.bf16_from_bits(st.w_bits, DEV)
     sa = torch.zeros(K, dtype=torch.float64, device=DEV)
     sw = torch.zeros(K, dtype=torch.float64, device=DEV)
-    pq.pq_calib_moments_batched(xs, sa)
-    pq.pq_calib_moments(w, sw)
+    amax_a = torch.zeros(1, dtype=torch.float32, device=DEV)
+    amax_w = torch.zeros(1, dtype=torch.float32, device=DEV)
+    pq.pq_calib_moments_batched(xs, sa, amax_a)
+    pq.pq_calib_moments(w, sw, amax_w)
+    ta = tw = None
+    ts_a = ts_w = 1.0
+    if fmt == pq.FMT_NVFP4:
+        ta = OQ.nvfp4_tensor_scale(max(OC.absmax(OF.bf16_bits_to_f64(b)) for b in batches))
+        tw = OQ.nvfp4_tensor_scale(OC.absmax(OF.bf16_bits_to_f64(st.w_bits)))
+        assert np.float32(amax_a.item()) / np.float32(2688.0) == ta
+        ts_a, ts_w = float(ta), float(tw)
     perm_out = torch.empty(K, dtype=torch.int32, device=DEV)
-    rep = pq.pq_select_perm(fmt, g, sa, sw, xs, w, 1.0, 1.0, perm_out)
+    rep = pq.pq_select_perm(fmt, g, sa, sw, xs, w, ts_a, ts_w, perm_out)
     torch.cuda.synchronize()
     _say("  gpu: accepted=%s alpha_index=%d E_orig=%.8g E_best=%.8g (%.1f s)"
          % (rep.accepted, rep.alpha_index, rep.e_orig, rep.e_best, time.time() - t0))
+    got_perm = perm_out.cpu().numpy()
+    del xs, w
 
-    # oracle: moments, keys, sorts first; then the error sums
-    ref_sa = np.zeros(K)
-    for b in batches:
-        ref_sa += OC.column_sumsq(OF.bf16_bits_to_f64(b))
-    ref_sw = OC.column_sumsq(OF.bf16_bits_to_f64(st.w_bits))
-    cands = [None] + [OC.sort_descending(OC.joint_key(ref_sa, ref_sw, a)) for a in OC.DEFAULT_ALPHAS]
-    gaps = [OC.min_relative_key_gap(OC.joint_key(ref_sa, ref_sw, a), p)
-            for a, p in zip(OC.DEFAULT_ALPHAS, cands[1:])]
-    assert min(gaps) > 1e-11, "ill-posed: sort keys closer than the moments are accurate"
-    tasks = [(fmt, g, bits, p, None) for p in cands for bits in batches + [st.w_bits]]
-    with cf.ThreadPoolExecutor(max_workers=8) as ex:      # numpy releases the GIL in its array loops
-        errs = list(ex.map(_cand_error, tasks))
+    cands, E, gaps, sum_x2, sum_w2 = _oracle_selection(fmt, g, batches, st.w_bits, ta, tw)
     _say("  oracle error sums done (%.1f s)" % (time.time() - t0))
-    errs = np.array(errs).reshape(len(cands), nb + 1)
-    sum_x2, sum_w2 = float(np.sum(ref_sa)), float(np.sum(ref_sw))
-    E = [float(sum(e[:nb])) / sum_x2 + float(e[nb]) / sum_w2 for e in errs]
+    assert min(gaps) > 1e-11, "ill-posed: sort keys closer than the moments are accurate"
     j = int(np.argmin(E[1:]))
     accepted = (not np.array_equal(cands[1 + j], np.arange(K))) and (E[0] - E[1 + j]) / E[0] > 0.0
     assert abs((E[0] - E[1 + j]) / E[0]) > 1e-6, "acceptance margin too small for an exact comparison"
     np.testing.assert_allclose(rep.e_orig, E[0], rtol=T.ERRSUM_RTOL)
     np.testing.assert_allclose(rep.e_cand, E[1:], rtol=T.ERRSUM_RTOL)
-    assert rep.alpha_index == j and rep.accepted == accepted
+    np.testing.assert_allclose(rep.sum_x2, sum_x2, rtol=T.MOMENTS_RTOL)
+    np.testing.assert_allclose(rep.sum_w2, sum_w2, rtol=T.MOMENTS_RTOL)
+    runner_up = np.sort(np.asarray(E[1:]))
+    if runner_up[1] - runner_up[0] > 1e-9 * runner_up[0]:      # else several alphas give the same order
+        assert rep.alpha_index == j
+    assert rep.accepted == accepted
     want = cands[1 + j] if accepted else np.arange(K, dtype=np.int32)
-    np.testing.assert_array_equal(perm_out.cpu().numpy(), want)
+    np.testing.assert_array_equal(got_perm, want)
     # with / without the permutation: the accepted order never raises the calibration error
     assert (not rep.accepted) or rep.e_best < rep.e_orig

@@ -207,6 +207,12 @@ def _gpu_moments(xs, w, K):
     ("c2", pq.FMT_NVFP4, 16, 96, 128, 1024, 2),
     ("c3down", pq.FMT_NVFP4, 16, 64, 96, 2048, 2),
     ("c4", pq.FMT_INT3, 32, 200, 160, 640, 3),
+    # wide rows: the sort at 96 / 128 key chunks and the error evaluation with two rows (K = 12288, the
+    # down projection's width) or one row (K = 16384) resident in LDS, identity + six candidates
+    ("c3down", pq.FMT_NVFP4, 16, 64, 96, 12288, 2),
+    ("c4", pq.FMT_INT3, 32, 40, 48, 12288, 2),
+    ("c1", pq.FMT_INT4, 64, 48, 64, 16384, 2),
+    ("c2", pq.FMT_NVFP4, 16, 40, 48, 16384, 2),
 ])
 def test_select_perm_matches_oracle(name, fmt, g, M, N, K, nb):
     _say("select_perm %s fmt=%d g=%d M=%d N=%d K=%d" % (name, fmt, g, M, N, K))
@@ -233,6 +239,12 @@ def test_select_perm_matches_oracle(name, fmt, g, M, N, K, nb):
     assert rep.accepted == ref.accepted
     assert rep.alpha_index == ref.alpha_index
     np.testing.assert_array_equal(perm_out.cpu().numpy(), ref.perm)
+    # every candidate order of the grid, not only the winner (the same key / rank kernels, one alpha a call)
+    order = torch.empty(K, dtype=torch.int32, device=DEV)
+    for a, p_ref in zip(OC.DEFAULT_ALPHAS, ref.cand_perms):
+        pq.pq_order_by_score(sa, sw, a, order)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(order.cpu().numpy(), p_ref)
     # acceptance never raises the calibration error
     assert rep.e_best <= rep.e_orig or not rep.accepted
     # tau above the realised gain rejects and returns the identity
