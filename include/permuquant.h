@@ -122,6 +122,24 @@ int pq_calib_moments_batched(const void* const* x_batches, int n_batches, int64_
                              size_t workspace_bytes, void* stream);
 
 /*
+ * pq_calib_moments for callers that cannot allocate or bring a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same kernels, same summation order
+ * and therefore the same bits as pq_calib_moments; the partial sums go to a device array of
+ * PQ_STATIC_SCRATCH_BYTES that is part of the library's code object (every GPU the library runs on
+ * holds it until the process ends).  The call allocates nothing, on the device or on the host
+ * (its first call on a device looks the array's address up once).  Shapes whose partial sums need more
+ * than PQ_STATIC_SCRATCH_BYTES (= pq_workspace_bytes(PQ_OP_CALIB_MOMENTS, ., ., rows, 0, K, 1)) are
+ * refused with PQ_ERR_WORKSPACE before anything is launched (the need stays near 2 MB for any row count
+ * and widths up to some 390 000 channels: every tensor of a transformer layer fits).  All calls on one GPU share the one array, which keeps the last
+ * call's partial sums (nothing in it has to start at zero): calls that overlap on one GPU -- on
+ * different streams or from different threads -- race and must be serialised by the caller.
+ * Other arguments, result and error codes as for pq_calib_moments.
+ */
+#define PQ_STATIC_SCRATCH_BYTES ((size_t)3 << 20)
+int pq_calib_moments_static(const void* x_bf16, int64_t rows, int64_t K, int64_t ld, double* sumsq,
+                            float* absmax, void* stream);
+
+/*
  * NVFP4 per-tensor scale from a running absmax (the two-level reading of NVFP4 W4A4, paper
  * Sec. 4.4): tensor_scale_out[0] = fl32(absmax[0] / 2688), 2688 = 448 * 6, so that the largest
  * block scale lands on the E4M3 maximum.  Both pointers: float [1] device; may alias.

@@ -74,9 +74,8 @@ size_t pq_workspace_bytes(pq_op op, pq_format fmt, int group, int64_t M, int64_t
   }
 }
 
-static int calib_moments_common(const char* who, const void* const* xs, int n_batches, int64_t rows,
-                                int64_t K, int64_t ld, double* sumsq, float* absmax, void* workspace,
-                                size_t workspace_bytes, void* stream) {
+static int calib_moments_check(const char* who, const void* const* xs, int n_batches, int64_t rows,
+                               int64_t K, int64_t ld, double* sumsq) {
   if (!xs || !sumsq) return fail(PQ_ERR_NULL, "%s: x and sumsq must not be NULL", who);
   if (n_batches <= 0) return fail(PQ_ERR_SHAPE, "%s: n_batches=%d must be positive", who, n_batches);
   if (rows <= 0 || K <= 0) return fail(PQ_ERR_SHAPE, "%s: rows=%lld K=%lld must be positive", who,
@@ -88,6 +87,14 @@ static int calib_moments_common(const char* who, const void* const* xs, int n_ba
     if (!xs[b]) return fail(PQ_ERR_NULL, "%s: batch %d is NULL", who, b);
     if (!aligned16(xs[b])) return fail(PQ_ERR_SHAPE, "%s: batch %d must be 16-byte aligned", who, b);
   }
+  return PQ_OK;
+}
+
+static int calib_moments_common(const char* who, const void* const* xs, int n_batches, int64_t rows,
+                                int64_t K, int64_t ld, double* sumsq, float* absmax, void* workspace,
+                                size_t workspace_bytes, void* stream) {
+  int rc = calib_moments_check(who, xs, n_batches, rows, K, ld, sumsq);
+  if (rc) return rc;
   size_t need = moments_workspace_bytes(rows, K, n_batches);
   if (!workspace || workspace_bytes < need)
     return fail(PQ_ERR_WORKSPACE, "%s: workspace of %zu bytes needed, %zu given", who, need,
@@ -100,6 +107,14 @@ int pq_calib_moments(const void* x, int64_t rows, int64_t K, int64_t ld, double*
   const void* xs[1] = {x};
   return calib_moments_common("pq_calib_moments", x ? xs : nullptr, 1, rows, K, ld, sumsq, absmax,
                               workspace, workspace_bytes, stream);
+}
+
+int pq_calib_moments_static(const void* x, int64_t rows, int64_t K, int64_t ld, double* sumsq, float* absmax,
+                            void* stream) {
+  const void* xs[1] = {x};
+  int rc = calib_moments_check("pq_calib_moments_static", x ? xs : nullptr, 1, rows, K, ld, sumsq);
+  if (rc) return rc;
+  return launch_moments_static(x, rows, K, ld, sumsq, absmax, as_stream(stream));
 }
 
 int pq_calib_moments_batched(const void* const* x_batches, int n_batches, int64_t rows, int64_t K,

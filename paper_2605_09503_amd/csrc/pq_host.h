@@ -30,6 +30,10 @@ size_t moments_workspace_bytes(int64_t rows, int64_t K, int n_batches);
 int launch_moments(const void* const* xs, int n_batches, int64_t rows, int64_t K, int64_t ld,
                    double* sumsq, float* absmax, void* ws, hipStream_t st);
 
+constexpr size_t kStaticScratchBytes = 3u << 20;   // scratch the library itself holds on every device
+int launch_moments_static(const void* x, int64_t rows, int64_t K, int64_t ld, double* sumsq, float* absmax,
+                          hipStream_t st);
+
 int launch_absmax_to_tensor_scale(const void* x, int64_t n_elems, float* tensor_scale_out,
                                   hipStream_t st);
 int launch_dynamic_tensor_scale(const void* x, int64_t rows, int64_t K, int64_t ld, float* out, hipStream_t st);

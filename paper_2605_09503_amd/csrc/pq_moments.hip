@@ -9,6 +9,8 @@
 // partial[batch][slab][col] and blockmax[...]; a second kernel adds the partials in (batch,
 // slab) order to sumsq and folds the maxima, which keeps the result independent of scheduling
 // and free of atomics.
+#include <mutex>
+
 #include "pq_device.h"
 #include "pq_host.h"
 
@@ -198,6 +200,53 @@ int launch_moments(const void* const* xs, int n_batches, int64_t rows, int64_t K
     if (rc) return rc;
   }
   return PQ_OK;
+}
+
+// ---------------------------------------------------------------- scratch held by the library
+// pq_calib_moments_static: the same two kernels with their partial sums in a device array that is
+// part of the loaded code object, for callers that cannot bring a workspace (none may be allocated
+// where they run).  Every GPU the library runs on holds its own copy of the array at its own
+// address; in host code the array's name is only a handle for hipGetSymbolAddress, so the device
+// address is looked up once per device (with that device current) and only that pointer is handed
+// to the kernels.
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static void* g_scratch_ptr[kMaxDevices];      // device address of `scratch` per device, nullptr = not yet asked
+
+static int static_scratch(void** out) {
+  int dev = -1;
+  int rc = check_hip(hipGetDevice(&dev), "hipGetDevice");
+  if (rc) return rc;
+  if (dev < 0 || dev >= kMaxDevices) return fail(PQ_ERR_HIP, "device index %d outside 0..%d", dev, kMaxDevices - 1);
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    rc = check_hip(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)), "hipGetSymbolAddress(scratch)");
+    if (rc) return rc;
+    if (!p) return fail(PQ_ERR_HIP, "hipGetSymbolAddress(scratch) returned a null address");
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return PQ_OK;
+}
+
+int launch_moments_static(const void* x, int64_t rows, int64_t K, int64_t ld, double* sumsq, float* absmax,
+                          hipStream_t st) {
+  const size_t need = moments_workspace_bytes(rows, K, 1);
+  if (need > kStaticScratchBytes)
+    return fail(PQ_ERR_WORKSPACE,
+                "pq_calib_moments_static: rows=%lld K=%lld need %zu bytes of scratch, the library holds %zu; "
+                "use pq_calib_moments with a workspace",
+                (long long)rows, (long long)K, need, (size_t)kStaticScratchBytes);
+  void* ws = nullptr;
+  int rc = static_scratch(&ws);
+  if (rc) return rc;
+  const void* xs[1] = {x};
+  // every partial sum and maximum the second kernel reads is written by the first one in this call:
+  // nothing in the array has to start at zero
+  return launch_moments(xs, 1, rows, K, ld, sumsq, absmax, ws, st);
 }
 
 // ---------------------------------------------------------------- per-channel sum and absmax

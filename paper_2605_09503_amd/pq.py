@@ -65,6 +65,7 @@ def load():
     lib.pq_workspace_bytes.restype = sz
     lib.pq_workspace_bytes.argtypes = [i32, i32, i32, i64, i64, i64, i32]
     lib.pq_calib_moments.argtypes = [vp, i64, i64, i64, vp, vp, vp, sz, vp]
+    lib.pq_calib_moments_static.argtypes = [vp, i64, i64, i64, vp, vp, vp]
     lib.pq_calib_moments_batched.argtypes = [C.POINTER(vp), i32, i64, i64, i64, vp, vp, vp, sz, vp]
     lib.pq_tensor_scale.argtypes = [vp, vp, vp]
     lib.pq_tensor_scale.restype = i32
@@ -157,6 +158,20 @@ def pq_calib_moments(x: torch.Tensor, sumsq: torch.Tensor, absmax: Optional[torc
         workspace = _workspace(pq_workspace_bytes(OP_CALIB_MOMENTS, 0, 0, rows, 0, K, 1), x.device)
     _check(load().pq_calib_moments(_ptr(x), rows, K, ld, _ptr(sumsq), _ptr(absmax), _ptr(workspace),
                                    0 if workspace is None else workspace.numel(), _stream()))
+
+
+STATIC_SCRATCH_BYTES = 3 << 20      # PQ_STATIC_SCRATCH_BYTES of the header
+
+
+def pq_calib_moments_static(x: torch.Tensor, sumsq: torch.Tensor, absmax: Optional[torch.Tensor] = None,
+                            rows: Optional[int] = None, K: Optional[int] = None,
+                            ld: Optional[int] = None) -> None:
+    """pq_calib_moments with the partial sums in scratch memory the library holds itself: the call
+    takes no workspace and allocates nothing."""
+    rows = x.shape[0] if rows is None else rows
+    K = x.shape[1] if K is None else K
+    ld = x.stride(0) if ld is None else ld
+    _check(load().pq_calib_moments_static(_ptr(x), rows, K, ld, _ptr(sumsq), _ptr(absmax), _stream()))
 
 
 def pq_calib_moments_batched(xs: Sequence[torch.Tensor], sumsq: torch.Tensor,

@@ -61,6 +61,26 @@ def test_calib_moments_validation(lib):
     assert "workspace" in pq.pq_last_error()
 
 
+def test_calib_moments_static_validation(lib):
+    """The variant with library-held scratch: same argument checks, and shapes whose partial sums do not
+    fit the array are refused on the host (no launch, no GPU needed)."""
+    f = lib.pq_calib_moments_static
+    assert f(None, 8, 64, 64, FAKE, None, None) == PQ_ERR_NULL
+    assert f(FAKE, 8, 64, 64, None, None, None) == PQ_ERR_NULL
+    assert f(FAKE, 0, 64, 64, FAKE, None, None) == PQ_ERR_SHAPE
+    assert f(FAKE, 8, 60, 64, FAKE, None, None) == PQ_ERR_SHAPE
+    assert f(FAKE, 8, 64, 32, FAKE, None, None) == PQ_ERR_SHAPE
+    assert f(C.c_void_p(0x1004), 8, 64, 64, FAKE, None, None) == PQ_ERR_SHAPE
+    # the benchmark's tensors fit; a tensor half a million channels wide does not
+    for rows, K in [(4608, 3072), (4608, 12288), (8192, 3072), (12288, 3072), (3072, 12288)]:
+        assert lib.pq_workspace_bytes(pq.OP_CALIB_MOMENTS, 0, 0, rows, 0, K, 1) <= pq.STATIC_SCRATCH_BYTES
+    assert lib.pq_workspace_bytes(pq.OP_CALIB_MOMENTS, 0, 0, 64, 0, 524288, 1) > pq.STATIC_SCRATCH_BYTES
+    assert f(FAKE, 64, 524288, 524288, FAKE, None, None) == PQ_ERR_WORKSPACE
+    assert "scratch" in pq.pq_last_error()
+    text = open(HEADER).read()
+    assert "#define PQ_STATIC_SCRATCH_BYTES ((size_t)3 << 20)" in text and pq.STATIC_SCRATCH_BYTES == 3 << 20
+
+
 def test_quantize_validation(lib):
     qa = lib.pq_quantize_act
     assert qa(pq.FMT_NVFP4, 16, None, 4, 64, 64, None, FAKE, FAKE, FAKE, None) == PQ_ERR_NULL
