@@ -455,8 +455,9 @@ int pq_hadamard_quantize_act_packed(const int32_t* perm, pq_format fmt, int grou
                                     void* stream);
 
 /*
- * Measurement aids (no part of the method; they give the timings of the kernels above a
- * reference measured on the same device in the same run).
+ * Measurement aids (no part of the method and not covered by the version contract of the calls above:
+ * they may change with the kernels they are references for; they give the timings of the kernels above
+ * a reference measured on the same device in the same run).
  *
  * pq_probe_stream: a plain streaming kernel that reads read_bytes from src and writes
  * write_bytes to dst (16 bytes per lane and access, no arithmetic worth naming) -- the time a
@@ -471,6 +472,17 @@ int pq_hadamard_quantize_act_packed(const int32_t* perm, pq_format fmt, int grou
  */
 int pq_probe_stream(const void* src, size_t read_bytes, void* dst, size_t write_bytes, void* stream);
 int pq_probe_mfma(int iters, float* sink, double* flops_out, void* stream);
+/*
+ * pq_probe_mfma_operands: the same matrix-pipe-only loop on the values pq_qgemm_packed multiplies.  The
+ * rate the matrix pipes sustain depends on the operand values (under its power limit the chip lowers its
+ * clock, the sooner the more the operands switch from one instruction to the next), so the reference for
+ * the product on given data is this loop on that data: every lane unpacks eight fragments of a_operand
+ * and four of w_operand (operands as written by pq_quantize_act_packed / pq_pack_operand for these
+ * fmt, group, M, N, K; K a multiple of 64) with the product kernel's own code and the loop cycles
+ * through them.  sink, flops_out as for pq_probe_mfma.
+ */
+int pq_probe_mfma_operands(pq_format fmt, int group, const void* a_operand, const void* w_operand, int64_t M,
+                           int64_t N, int64_t K, int iters, float* sink, double* flops_out, void* stream);
 
 #ifdef __cplusplus
 }

@@ -625,4 +625,17 @@ int pq_probe_mfma(int iters, float* sink, double* flops_out, void* stream) {
   return launch_probe_mfma(iters, sink, flops_out, as_stream(stream));
 }
 
+int pq_probe_mfma_operands(pq_format fmt, int group, const void* a_operand, const void* w_operand, int64_t M,
+                           int64_t N, int64_t K, int iters, float* sink, double* flops_out, void* stream) {
+  if (!a_operand || !w_operand || !sink) return fail(PQ_ERR_NULL, "pq_probe_mfma_operands: NULL pointer");
+  int rc = check_format(fmt, group, K);
+  if (rc) return rc;
+  if (M <= 0 || N <= 0 || K % 64) return fail(PQ_ERR_SHAPE, "pq_probe_mfma_operands: M=%lld N=%lld must be positive, K=%lld a multiple of 64",
+                                             (long long)M, (long long)N, (long long)K);
+  if (M * 32 > 0x7FFFFFFF || N * 32 > 0x7FFFFFFF) return fail(PQ_ERR_SHAPE, "pq_probe_mfma_operands: too many rows");
+  if (!aligned16(a_operand) || !aligned16(w_operand)) return fail(PQ_ERR_SHAPE, "pq_probe_mfma_operands: operands must be 16-byte aligned");
+  if (iters <= 0 || iters > (1 << 24)) return fail(PQ_ERR_SHAPE, "pq_probe_mfma_operands: iters=%d out of range", iters);
+  return launch_probe_mfma_operands(fmt, group, a_operand, w_operand, M, N, K, iters, sink, flops_out, as_stream(stream));
+}
+
 }  // extern "C"

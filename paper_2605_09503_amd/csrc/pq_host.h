@@ -116,5 +116,7 @@ int run_qgemm_packed(pq_format fmt, int group, const void* a_operand, const floa
 
 int launch_probe_stream(const void* src, size_t read_bytes, void* dst, size_t write_bytes, hipStream_t st);
 int launch_probe_mfma(int iters, float* sink, double* flops_out, hipStream_t st);
+int launch_probe_mfma_operands(pq_format fmt, int group, const void* a_operand, const void* w_operand, int64_t M,
+                               int64_t N, int64_t K, int iters, float* sink, double* flops_out, hipStream_t st);
 
 }  // namespace pq

@@ -23,8 +23,6 @@
 // LDS rows are 64 fp16 plus one 16-byte piece of padding (144 bytes): measured on gfx950, the
 // 16-byte fragment reads of the 32-row MFMA operand pattern run at full LDS rate with this
 // stride (an XOR swizzle of unpadded rows reaches two thirds of it).
-#include <stdlib.h>
-
 #include "pq_qgemm_common.h"
 
 namespace pq {
@@ -47,16 +45,23 @@ __global__ __launch_bounds__(WGM* WGN * 64) void qgemm_kernel(OperandView A, Ope
   const float* __restrict__ w_mul = W.mul;
   const int a_mul_stride = A.mul_stride, w_mul_stride = W.mul_stride;
   constexpr int T = WGM * WGN * 64;
-  constexpr int WTM = BM / WGM, WTN = BN / WGN;      // wave tile
+  // wave tile: WTM x WTN outputs.  BM need not divide evenly over the WGM wave rows: the last wave row
+  // then owns TM_LAST < TM MFMA tiles along M (a 224-row tile is 128 + 96), and the waves are numbered so
+  // that every SIMD hosts one wave of each kind (see below)
+  constexpr int WTM = (BM + WGM * 32 - 1) / (WGM * 32) * 32, WTN = BN / WGN;
   constexpr int TM = WTM / 32, TN = WTN / 32;        // MFMA tiles per wave
-  constexpr int SL = BM * 2 / T;                     // slices per operand per thread
-  static_assert(BM == BN && BM * 2 % T == 0, "square tile, whole slices per thread");
-  static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile");
-  constexpr int A_TILE_BYTES = BM * kRowBytes, W_TILE_BYTES = BN * kRowBytes;
+  constexpr int TM_LAST = (BM - (WGM - 1) * WTM) / 32;
+  constexpr bool RAGGED_M = TM_LAST != TM;
+  constexpr int SL = BN * 2 / T;                     // slices per operand per thread
+  static_assert(BN * 2 % T == 0 && (BM * 2 + T - 1) / T == SL, "whole slices per thread, as many for A as for W");
+  static_assert(BM % 32 == 0 && WTN % 32 == 0 && TM_LAST >= 1 && TM_LAST <= TM, "wave tile");
+  static_assert(!RAGGED_M || (WGM == 2 && WGN == 4), "the uneven split is laid out for 2 x 4 waves");
+  // the loader covers SL * T / 2 rows of each operand; an A tile of fewer rows (BM = 224) still gets all
+  // of them in LDS, so that no thread needs a predicate around its unpack writes (the spare rows hold zeros
+  // and are never read)
+  constexpr int A_TILE_BYTES = SL * (T / 2) * kRowBytes, W_TILE_BYTES = BN * kRowBytes;
   constexpr int STAGE_BYTES = A_TILE_BYTES + W_TILE_BYTES;
-  constexpr int NM = TN * TM;                        // MFMAs per 16-wide k slice
   constexpr int NT = 8 * SL;                         // unpack pair tasks per k slice
-  static_assert(NT % NM == 0 || NM % NT == 0, "pair tasks divide over the MFMAs");
 
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
@@ -65,7 +70,12 @@ __global__ __launch_bounds__(WGM* WGN * 64) void qgemm_kernel(OperandView A, Ope
   // 8 along M so that concurrently running workgroups share A and W strips.
   const int n_tiles = tiles_m * tiles_n;
   int pid = blockIdx.x;
-  if (n_tiles % 8 == 0) pid = (pid & 7) * (n_tiles >> 3) + (pid >> 3);
+  {
+    // XCD x runs the workgroups with id % 8 == x: (n_tiles - x + 7) / 8 of them, which get the tiles
+    // from x * (n_tiles / 8) + min(x, n_tiles % 8) on
+    const int x = pid & 7, q8 = n_tiles >> 3, r8 = n_tiles & 7;
+    pid = x * q8 + min(x, r8) + (pid >> 3);
+  }
   constexpr int BAND = 8;
   const int band_sz = BAND * tiles_n;
   const int band = pid / band_sz;
@@ -78,7 +88,13 @@ __global__ __launch_bounds__(WGM* WGN * 64) void qgemm_kernel(OperandView A, Ope
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
-  const int wave_m = wave % WGM, wave_n = wave / WGM;
+  // Waves of a workgroup go to the four SIMDs in turn (wave w on SIMD w % 4).  With the uneven split
+  // waves w and w + 4 take different wave rows, so that every SIMD's matrix pipe gets TM + TM_LAST tile
+  // rows of work per step.
+  const int wave_m = RAGGED_M ? ((wave >> 2) ^ wave) & 1 : wave % WGM;
+  const int wave_n = RAGGED_M ? wave >> 1 : wave / WGM;
+  // MFMA tile rows this wave owns (wave-uniform, kept in a scalar register)
+  const int tm_cnt = RAGGED_M ? __builtin_amdgcn_readfirstlane(wave_m == WGM - 1 ? TM_LAST : TM) : TM;
 
   // loader: this thread owns tile rows tid / 2 + q * (T / 2), k offset 32 * (tid & 1), of both
   // operands
@@ -89,7 +105,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void qgemm_kernel(OperandView A, Ope
 #pragma unroll
   for (int q = 0; q < SL; ++q) {
     const int r = ld_row + q * (T / 2);
-    a_ok[q] = m0 + r < M;
+    a_ok[q] = m0 + r < M && r < BM;
     w_ok[q] = n0 + r < N;
     const int a_row = min(m0 + r, M - 1), w_row = min(n0 + r, N - 1);
     a_crow[q] = A.codes + (int64_t)a_row * A.code_row;
@@ -164,8 +180,12 @@ __global__ __launch_bounds__(WGM* WGN * 64) void qgemm_kernel(OperandView A, Ope
   load_w(2, raw_w[0]);
   __syncthreads();
 
-  auto body = [&](auto Pc, int s) {
+  // TMc: the MFMA tile rows of the calling wave as a compile-time constant (TM, or TM_LAST for the
+  // short wave row of an uneven split) -- each kind of wave runs its own straight-line loop
+  auto body = [&](auto Pc, auto TMc, int s) {
     constexpr int P = decltype(Pc)::value;
+    constexpr int TMW = decltype(TMc)::value;
+    constexpr int NM = TN * TMW;                     // MFMAs per 16-wide k slice
     const unsigned char* a_t = smem + P * STAGE_BYTES;
     const unsigned char* w_t = a_t + A_TILE_BYTES;
     unsigned char* a_nx = smem + (P ^ 1) * STAGE_BYTES;
@@ -193,7 +213,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void qgemm_kernel(OperandView A, Ope
       xf[set][j] = *reinterpret_cast<const half8_t*>(a_t + x_frag_base[j] + piece_off[kk]);
     };
 #pragma unroll
-    for (int j = 0; j < TM; ++j) read_x(0, 0, j);
+    for (int j = 0; j < TMW; ++j) read_x(0, 0, j);
 #pragma unroll
     for (int i = 0; i < TN; ++i) read_w(0, i);
 
@@ -203,11 +223,11 @@ __global__ __launch_bounds__(WGM* WGN * 64) void qgemm_kernel(OperandView A, Ope
       const int cur = kk & 1;
 #pragma unroll
       for (int mi = 0; mi < NM; ++mi) {
-        const int i = mi / TM, j = mi % TM;
+        const int i = mi / TMW, j = mi % TMW;
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(wf[i], xf[cur][j], acc[i][j], 0, 0, 0);
         if (kk < 3) {
-          if (j == TM - 1) read_w(kk + 1, i);                 // wf[i] is free now
-          if (mi < TM) read_x(cur ^ 1, kk + 1, mi);           // next slice's activations, early
+          if (j == TMW - 1) read_w(kk + 1, i);                // wf[i] is free now
+          if (mi < TMW) read_x(cur ^ 1, kk + 1, mi);          // next slice's activations, early
         }
         // unpack tasks: NT pairs per k slice, spread evenly over the MFMAs.  Task order over
         // the whole step: A slot 0 (4 pieces x 4 pairs), A slot 1, ..., then the W slots.
@@ -242,9 +262,17 @@ __global__ __launch_bounds__(WGM* WGN * 64) void qgemm_kernel(OperandView A, Ope
   // two steps per trip so that the LDS stage and the register set are compile-time constants;
   // an odd step count runs one extra step on all-zero operands (loads beyond K are zeroed),
   // which keeps a single loop exit (two exits would double the live accumulators)
-  for (int s = 0; s < ksteps; s += 2) {
-    body(IntC<0>{}, s);
-    body(IntC<1>{}, s + 1);
+  if (!RAGGED_M || tm_cnt == TM) {
+    for (int s = 0; s < ksteps; s += 2) {
+      body(IntC<0>{}, IntC<TM>{}, s);
+      body(IntC<1>{}, IntC<TM>{}, s + 1);
+    }
+  } else {
+    // same number of barriers as the other kind of wave: one per step
+    for (int s = 0; s < ksteps; s += 2) {
+      body(IntC<0>{}, IntC<TM_LAST>{}, s);
+      body(IntC<1>{}, IntC<TM_LAST>{}, s + 1);
+    }
   }
 
   // ---- epilogue: lane holds, per MFMA tile, column m = lane % 32 and rows
@@ -269,6 +297,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void qgemm_kernel(OperandView A, Ope
       }
 #pragma unroll
   for (int j = 0; j < TM; ++j) {
+    if (RAGGED_M && j >= tm_cnt) break;         // wave-uniform
     const int ml = wave_m * WTM + j * 32 + frag_row;
     const int m = m0 + ml;
     const float am = a_mul[(int64_t)(min(m, M - 1) * a_mul_stride)];
@@ -404,7 +433,7 @@ template <int FMT, int G, int BM, int BN, int WGM, int WGN, bool OUT_F32>
 static int launch_gemm(const OperandView& A, const OperandView& W, int M, int N, int K, void* y, int64_t ldy,
                        hipStream_t st) {
   constexpr int T = WGM * WGN * 64;
-  constexpr size_t shmem = 2 * (size_t)(BM + BN) * kRowBytes;
+  constexpr size_t shmem = 2 * (size_t)((BM * 2 + T - 1) / T * (T / 2) + BN) * kRowBytes;
   auto kern = qgemm_kernel<FMT, G, BM, BN, WGM, WGN, OUT_F32>;
   if (shmem > 48 * 1024) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -418,36 +447,33 @@ static int launch_gemm(const OperandView& A, const OperandView& W, int M, int N,
   return check_hip(hipGetLastError(), "qgemm_kernel");
 }
 
-// Tile choice.  256 x 256 with eight waves unless the output is so small that 128 x 128 tiles
-// (four waves, about 35 % more operand traffic per output) fill more of the 256 compute units.
-// The cost of a variant is the number of rounds its tiles need times the tile area.
-// PQ_QGEMM_TILE (0: 256 x 256 with 4 waves, 1: 256 x 256 with 8 waves, 2: 128 x 128) overrides
-// the choice for tuning runs.
-static int tile_override() {
-  static int v = [] {
-    const char* e = getenv("PQ_QGEMM_TILE");
-    return e ? atoi(e) : -1;
-  }();
-  return v;
-}
-
+// Tile choice.  The cost of a variant is the number of rounds its tiles need on the 256 compute units
+// (one workgroup per unit: the LDS stages take 135 KB or more) times the tile area:
+//   256 x 256, eight waves                          the default;
+//   224 x 256, eight waves (wave rows of 128 + 96)  when that saves a round or shortens the only one: at
+//                                                   M = 4608 (18 x 256 = 20.6 x 224) a grid of 18 x 12 tiles
+//                                                   leaves 40 units idle, one of 21 x 12 keeps 252 busy with
+//                                                   7/8 of the work each;
+//   128 x 128, four waves                           small outputs (about 35 % more operand traffic per
+//                                                   output, but more of the units get a tile).
 static int choose_tile(int M, int N) {
   auto rounds = [&](int bm, int bn) {
     int64_t tiles = (int64_t)((M + bm - 1) / bm) * ((N + bn - 1) / bn);
     return (double)((tiles + 255) / 256);
   };
   const double c256 = rounds(256, 256) * 256 * 256;
+  const double c224 = rounds(224, 256) * 224 * 256;
   const double c128 = rounds(128, 128) * 128 * 128 * 1.35;
-  return c128 < c256 ? 2 : 1;
+  if (c128 < c256 && c128 < c224) return 2;
+  return c224 < c256 ? 3 : 1;
 }
 
 template <int FMT, int G, bool OUT_F32>
 static int pick_tile(const OperandView& A, const OperandView& W, int M, int N, int K, void* y, int64_t ldy,
                      hipStream_t st) {
-  int choice = choose_tile(M, N);
-  if (tile_override() >= 0 && tile_override() <= 2) choice = tile_override();
-  if (choice == 0) return launch_gemm<FMT, G, 256, 256, 2, 2, OUT_F32>(A, W, M, N, K, y, ldy, st);
+  const int choice = choose_tile(M, N);
   if (choice == 1) return launch_gemm<FMT, G, 256, 256, 2, 4, OUT_F32>(A, W, M, N, K, y, ldy, st);
+  if (choice == 3) return launch_gemm<FMT, G, 224, 256, 2, 4, OUT_F32>(A, W, M, N, K, y, ldy, st);
   return launch_gemm<FMT, G, 128, 128, 2, 2, OUT_F32>(A, W, M, N, K, y, ldy, st);
 }
 

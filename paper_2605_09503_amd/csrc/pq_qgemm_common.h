@@ -119,6 +119,28 @@ struct IntC {
   static constexpr int value = V;
 };
 
+// view of an operand in the panel layout (pq_pack.hip)
+inline OperandView panel_view(pq_format fmt, int group, const void* operand, int64_t rows, int64_t K,
+                              const float* tensor_scale) {
+  const OperandLayout L = operand_layout(fmt, group, rows, K);
+  const uint8_t* o = (const uint8_t*)operand;
+  OperandView v;
+  v.codes = o + L.codes;
+  v.code_row = 32;
+  v.code_step = (int)(rows * 32);
+  v.scales = o + L.scales;
+  v.sc_row = 2;
+  v.sc_step = (int)(rows * 2);
+  if (fmt == PQ_FMT_NVFP4) {
+    v.mul = tensor_scale;
+    v.mul_stride = 0;
+  } else {
+    v.mul = (const float*)(o + L.mul);
+    v.mul_stride = 1;
+  }
+  return v;
+}
+
 // the product kernel on two operand views (pq_qgemm.hip)
 int launch_qgemm_views(pq_format fmt, int group, const OperandView& A, const OperandView& W, int64_t M,
                        int64_t N, int64_t K, void* y, int64_t ldy, bool out_f32, hipStream_t st);

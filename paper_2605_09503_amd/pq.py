@@ -107,6 +107,7 @@ def load():
                                                 vp, i64, vp]
     lib.pq_probe_stream.argtypes = [vp, sz, vp, sz, vp]
     lib.pq_probe_mfma.argtypes = [i32, vp, C.POINTER(C.c_double), vp]
+    lib.pq_probe_mfma_operands.argtypes = [i32, i32, vp, vp, i64, i64, i64, i32, vp, C.POINTER(C.c_double), vp]
     for name in ("pq_calib_moments", "pq_calib_moments_batched", "pq_select_perm", "pq_quant_error", "pq_quantize_weights",
                  "pq_quantize_act", "pq_qgemm", "pq_qgemm_f32", "pq_qgemm_run", "pq_qgemm_prep", "pq_probe_stream",
                  "pq_probe_mfma", "pq_pack_operand", "pq_qgemm_packed", "pq_qgemm_packed_f32",
@@ -522,6 +523,15 @@ def pq_probe_mfma(iters: int, sink: torch.Tensor) -> float:
     """Matrix-pipe-only loop on every compute unit; returns the floating-point operations issued."""
     flops = C.c_double(0.0)
     _check(load().pq_probe_mfma(iters, _ptr(sink), C.byref(flops), _stream()))
+    return flops.value
+
+
+def pq_probe_mfma_operands(fmt: int, group: int, a_operand: torch.Tensor, w_operand: torch.Tensor, M: int, N: int,
+                           K: int, iters: int, sink: torch.Tensor) -> float:
+    """Matrix-pipe-only loop on fragments of the two packed operands; returns the operations issued."""
+    flops = C.c_double(0.0)
+    _check(load().pq_probe_mfma_operands(fmt, group, _ptr(a_operand), _ptr(w_operand), M, N, K, iters, _ptr(sink),
+                                         C.byref(flops), _stream()))
     return flops.value
 
 

@@ -436,8 +436,16 @@ def test_qgemm_small_ragged(fmt, g):
 
 @pytest.mark.parametrize("fmt,g", FMTS[:4])
 def test_qgemm_large_tile_path(fmt, g):
-    # enough 256x256 tiles to select the large-tile kernel; ragged edges; odd tile count
+    # enough outputs to select the large-tile kernel -- here the 224 x 256 tile (wave rows of 128 + 96),
+    # 11 x 15 of them; ragged edges; odd tile count
     _gemm_case(fmt, g, 2304 + 40, 3584 + 72, 256, 700 + g, ldy_pad=8)
+
+
+@pytest.mark.parametrize("fmt,g", [(pq.FMT_NVFP4, 16), (pq.FMT_INT4, 64)])
+def test_qgemm_square_tile_path(fmt, g):
+    # 16 x 16 tiles of 256 x 256 fill the compute units exactly (tiles 224 rows high would need a second
+    # round), so the square tile is chosen; ragged last row and column of tiles
+    _gemm_case(fmt, g, 4096 - 6, 4096 - 9, 128, 750 + g)
 
 
 @pytest.mark.parametrize("fmt,g", FMTS[:4])
