@@ -105,8 +105,8 @@ size_t pq_workspace_bytes(pq_op op, pq_format fmt, int group, int64_t M, int64_t
  * before the first batch; call once per calibration batch, and once with x = W, rows = N.
  * absmax: float [1], in/out, >= 0 (zero-filled by the caller), may be NULL.
  * workspace: pq_workspace_bytes(PQ_OP_CALIB_MOMENTS, ., ., rows, 0, K, n_batches) bytes
- * (n_batches = 1 here); contents are scratch.  Results are deterministic (fixed summation order
- * for fixed sizes, no atomics).
+ * (n_batches = 1 here); contents are scratch and need not be initialised.  Results are deterministic
+ * (fixed summation order for fixed sizes, no atomics).  Two launches; may be captured into a HIP graph.
  */
 int pq_calib_moments(const void* x_bf16, int64_t rows, int64_t K, int64_t ld, double* sumsq,
                      float* absmax, void* workspace, size_t workspace_bytes, void* stream);

@@ -1,14 +1,20 @@
 // Column second moments and running absmax (paper Sec. 3.2, mu_i^2 = E[x_i^2]; Sec. 3.3 uses
 // them for activations and weights).  HBM-bound: every bf16 element is read once.
 //
-// Layout: a workgroup is 64 lanes (x) by kTy row-interleaved waves (y).  Lane l of every wave
-// owns 8 consecutive columns (one 16-byte load per row), so a wave reads 1 KB of a row at a
-// time.  grid.x tiles the columns, grid.y splits the rows into R slabs, grid.z runs over the
-// batches of one call.  Each workgroup reduces its slab to one fp64 partial per column (squares
-// of bf16 are exact in fp32, the accumulation is fp64) and to one absmax, written to
-// partial[batch][slab][col] and blockmax[...]; a second kernel adds the partials in (batch,
-// slab) order to sumsq and folds the maxima, which keeps the result independent of scheduling
-// and free of atomics.
+// A workgroup is 8 waves; a wave reads four rows at a time, sixteen lanes per row, a lane owning 8
+// consecutive columns (one 16-byte load): a workgroup covers a strip of 128 columns (256 contiguous
+// bytes per row) and a slab of rows.  grid.x tiles the columns, grid.y the row slabs, grid.z runs over
+// the batches of one call.  Each workgroup reduces its slab to one fp64 partial per column (squares of
+// bf16 are exact, the accumulation is fp64) and one absmax, written to partial[batch][slab][col] /
+// blockmax[...]; a second small kernel adds the partials in (batch, slab) order to sumsq and folds the
+// maxima, which keeps the result independent of scheduling and free of atomics.
+//
+// (One launch instead of two -- the workgroup that arrives last at a strip's counter adds the strip's
+// partials up -- was built and measured on c1's 28 MB batch, 9 us with two launches: 160 us with
+// device-scope fences around the hand-over (each one writes back and invalidates a whole L2), 77 us
+// with device-scope atomic accesses for the few values that cross and a compare-and-swap ticket, 23 us
+// with a fetch-add ticket -- the 32 arrivals at one address are served one after the other, about
+// 0.6 us each.  Two launches stay.)
 #include <mutex>
 
 #include "pq_device.h"
@@ -16,35 +22,46 @@
 
 namespace pq {
 
-constexpr int kTy = 8;             // waves per workgroup
+constexpr int kTy = 8;               // waves per workgroup
 constexpr int kColsPerLane = 8;
-constexpr int kColsPerBlock = 64 * kColsPerLane;
+constexpr int kLanesPerRow = 16;     // lanes of a wave that share a row
+constexpr int kRowsPerWave = 64 / kLanesPerRow;
+constexpr int kRowsPerPass = kTy * kRowsPerWave;            // rows a workgroup reads per pass
+constexpr int kStripCols = kLanesPerRow * kColsPerLane;     // 128 columns per workgroup
+constexpr int kMaxSlabs = 64;
 
 struct BatchPtrs {
   const uint16_t* p[kMaxMomentBatches];
 };
 
-// Row slabs per (column block, batch): the smallest count that gives every one of the 256
-// compute units the same number of workgroups (two or three of them), so that no unit idles
-// while others finish, capped so that a wave keeps at least four rows.
+static int64_t strip_count(int64_t K) { return (K + kStripCols - 1) / kStripCols; }
+
+// Row slabs per (strip, batch): about three workgroups per compute unit in total, every slab at least
+// two passes long.
 static int moments_slabs(int64_t rows, int64_t K, int n_batches) {
-  const int64_t col_blocks = (K + kColsPerBlock - 1) / kColsPerBlock;
-  const int64_t per_slab = col_blocks * n_batches;
-  int64_t want = (512 + per_slab - 1) / per_slab;                                // >= 512 workgroups
-  for (int64_t s = want; s <= want + 8; ++s)
-    if (s * per_slab % 256 == 0) {
-      want = s;
-      break;
-    }
-  const int64_t max_slabs = (rows + 4 * kTy - 1) / (4 * kTy);                    // >= 4 rows per wave
+  const int64_t per_slab = strip_count(K) * n_batches;
+  int64_t want = (768 + per_slab - 1) / per_slab;
+  const int64_t max_slabs = (rows + 2 * kRowsPerPass - 1) / (2 * kRowsPerPass);
   if (want > max_slabs) want = max_slabs;
+  if (want > kMaxSlabs) want = kMaxSlabs;
   if (want < 1) want = 1;
-  if (want > 64) want = 64;
   return (int)want;
 }
 
-static size_t blockmax_count(int64_t K, int slabs, int n_batches) {
-  return (size_t)((K + kColsPerBlock - 1) / kColsPerBlock) * slabs * n_batches;
+struct MomentsWs {
+  double* partial;                // [n_batches * slabs][K]
+  float* blockmax;                // [n_batches * slabs][strips]
+};
+
+static size_t carve_moments(void* base, int64_t K, int slabs, int n_batches, MomentsWs* w) {
+  const size_t strips = (size_t)strip_count(K);
+  const size_t o_max = align_up((size_t)n_batches * slabs * (size_t)K * sizeof(double), 256);
+  const size_t total = o_max + align_up((size_t)n_batches * slabs * strips * sizeof(float), 256);
+  if (w) {
+    w->partial = (double*)base;
+    w->blockmax = (float*)((char*)base + o_max);
+  }
+  return total;
 }
 
 size_t moments_workspace_bytes(int64_t rows, int64_t K, int n_batches) {
@@ -53,9 +70,7 @@ size_t moments_workspace_bytes(int64_t rows, int64_t K, int n_batches) {
   // a call is cut into launches of at most kMaxMomentBatches batches; cover the largest need
   size_t need = 0;
   for (int nb = 1; nb <= per_launch; ++nb) {
-    const int slabs = moments_slabs(rows, K, nb);
-    const size_t b = align_up((size_t)nb * slabs * (size_t)K * sizeof(double), 256) +
-                     align_up(blockmax_count(K, slabs, nb) * sizeof(float), 256);
+    const size_t b = carve_moments(nullptr, K, moments_slabs(rows, K, nb), nb, nullptr);
     if (b > need) need = b;
   }
   return need;
@@ -65,12 +80,16 @@ __global__ __launch_bounds__(64 * kTy) void moments_partial_kernel(BatchPtrs xs,
                                                                   int64_t ld, int rows_per_slab,
                                                                   double* __restrict__ partial,
                                                                   float* __restrict__ blockmax) {
-  __shared__ double red[kTy][64][kColsPerLane + 1];
+  __shared__ double red[kTy * kRowsPerWave][kLanesPerRow][kColsPerLane + 1];
+  __shared__ double share[4][kStripCols];
   __shared__ float red_max[kTy];
   const int lane = threadIdx.x;
   const int ty = threadIdx.y;
+  const int tid = ty * 64 + lane;
+  const int sub = lane / kLanesPerRow, cl = lane % kLanesPerRow;
   const uint16_t* __restrict__ x = xs.p[blockIdx.z];
-  const int64_t col = (int64_t)blockIdx.x * kColsPerBlock + lane * kColsPerLane;
+  const int64_t col0 = (int64_t)blockIdx.x * kStripCols;
+  const int64_t col = col0 + cl * kColsPerLane;
   const int64_t r0 = (int64_t)blockIdx.y * rows_per_slab;
   int64_t r1 = r0 + rows_per_slab;
   if (r1 > rows) r1 = rows;
@@ -93,44 +112,49 @@ __global__ __launch_bounds__(64 * kTy) void moments_partial_kernel(BatchPtrs xs,
   };
   if (col < K) {
     const uint16_t* p = x + col;
-    int64_t r = r0 + ty;
+    int64_t r = r0 + ty * kRowsPerWave + sub;
     // four independent 16-byte loads in flight per lane
-    for (; r + 3 * kTy < r1; r += 4 * kTy) {
+    for (; r + 3 * kRowsPerPass < r1; r += 4 * kRowsPerPass) {
       uint4 v[4];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) v[u] = *reinterpret_cast<const uint4*>(p + (r + u * kTy) * ld);
+      for (int u = 0; u < 4; ++u) v[u] = *reinterpret_cast<const uint4*>(p + (r + u * kRowsPerPass) * ld);
 #pragma unroll
       for (int u = 0; u < 4; ++u) accumulate(v[u]);
     }
-    for (; r < r1; r += kTy) accumulate(*reinterpret_cast<const uint4*>(p + r * ld));
+    for (; r < r1; r += kRowsPerPass) accumulate(*reinterpret_cast<const uint4*>(p + r * ld));
   }
 #pragma unroll
-  for (int c = 0; c < kColsPerLane; ++c) red[ty][lane][c] = acc[c];
+  for (int c = 0; c < kColsPerLane; ++c) red[ty * kRowsPerWave + sub][cl][c] = acc[c];
   // widen the larger of the two 16-bit maxima to fp32 bits
   const uint32_t amax = max((uint32_t)amax2.x, (uint32_t)amax2.y);
-  float fm = wave_max(as_f32(amax << 16));
+  const float fm = wave_max(as_f32(amax << 16));
   if (lane == 0) red_max[ty] = fm;
   __syncthreads();
-  // waves 0..7 each finish one of the eight columns of every lane, adding in wave order
-  const int64_t slab_index = (int64_t)blockIdx.z * gridDim.y + blockIdx.y;
-  if (ty < kColsPerLane && col < K) {
+  // thread (part, j): column j of the strip, a quarter of the 32 row groups, added in index order; the
+  // four quarters are then added in order by the threads of part 0
+  const int j = tid % kStripCols, part = tid / kStripCols;
+  {
     double s = 0.0;
 #pragma unroll
-    for (int w = 0; w < kTy; ++w) s += red[w][lane][ty];
-    partial[slab_index * K + col + ty] = s;
+    for (int q = 0; q < kTy * kRowsPerWave / 4; ++q)
+      s += red[part * (kTy * kRowsPerWave / 4) + q][j / kColsPerLane][j % kColsPerLane];
+    share[part][j] = s;
   }
-  if (ty == 0 && lane == 0) {
+  __syncthreads();
+  const int64_t part_index = (int64_t)blockIdx.z * gridDim.y + blockIdx.y;
+  if (part == 0 && col0 + j < K)
+    partial[part_index * K + col0 + j] = ((share[0][j] + share[1][j]) + share[2][j]) + share[3][j];
+  if (tid == 0) {
     float m = 0.0f;
 #pragma unroll
     for (int w = 0; w < kTy; ++w) m = fmaxf(m, red_max[w]);
-    blockmax[slab_index * gridDim.x + blockIdx.x] = m;
+    blockmax[part_index * gridDim.x + blockIdx.x] = m;
   }
 }
 
 // sumsq[i] += sum of the partials of column i.  A workgroup covers kFinCols columns; its threads form
 // kFinParts groups that each add a contiguous share of the partials in order, and the shares are
-// combined in group order: the result does not depend on scheduling.  (Sixteen columns by sixteen
-// shares: 4 K / 64 workgroups with short chains instead of K / 64 with long ones.)
+// combined in group order: the result does not depend on scheduling.
 constexpr int kFinCols = 16, kFinParts = 16;
 __global__ __launch_bounds__(kFinCols * kFinParts) void moments_finish_kernel(const double* __restrict__ partial,
                                                                              int n_partials, int64_t K,
@@ -184,18 +208,16 @@ int launch_moments(const void* const* xs, int n_batches, int64_t rows, int64_t K
     const int rows_per_slab = (int)((rows + slabs - 1) / slabs);
     BatchPtrs bp;
     for (int b = 0; b < kMaxMomentBatches; ++b) bp.p[b] = (const uint16_t*)xs[b0 + (b < nb ? b : 0)];
-    double* partial = (double*)ws;
-    float* blockmax = (float*)((char*)ws + align_up((size_t)nb * slabs * (size_t)K * sizeof(double), 256));
-    dim3 grid((unsigned)((K + kColsPerBlock - 1) / kColsPerBlock), (unsigned)slabs, (unsigned)nb);
-    dim3 block(64, kTy);
-    hipLaunchKernelGGL(moments_partial_kernel, grid, block, 0, st, bp, rows, K, ld, rows_per_slab, partial,
-                       blockmax);
+    MomentsWs W;
+    carve_moments(ws, K, slabs, nb, &W);
+    const unsigned strips = (unsigned)strip_count(K);
+    hipLaunchKernelGGL(moments_partial_kernel, dim3(strips, (unsigned)slabs, (unsigned)nb), dim3(64, kTy), 0, st, bp,
+                       rows, K, ld, rows_per_slab, W.partial, W.blockmax);
     int rc = check_hip(hipGetLastError(), "moments_partial_kernel");
     if (rc) return rc;
     hipLaunchKernelGGL(moments_finish_kernel, dim3((unsigned)((K + kFinCols - 1) / kFinCols)),
-                       dim3(kFinCols * kFinParts), 0, st,
-                       (const double*)partial, nb * slabs, K, sumsq, (const float*)blockmax,
-                       (int)blockmax_count(K, slabs, nb), absmax);
+                       dim3(kFinCols * kFinParts), 0, st, (const double*)W.partial, nb * slabs, K, sumsq,
+                       (const float*)W.blockmax, (int)(strips * slabs * nb), absmax);
     rc = check_hip(hipGetLastError(), "moments_finish_kernel");
     if (rc) return rc;
   }
@@ -250,6 +272,7 @@ int launch_moments_static(const void* x, int64_t rows, int64_t K, int64_t ld, do
 }
 
 // ---------------------------------------------------------------- per-channel sum and absmax
+constexpr int kColsPerBlock = 64 * kColsPerLane;      // here a wave reads 1 KB of one row at a time
 // Statistics of the alternative reorder criteria (paper Tab. 2a: variance, absmax): per column the
 // sum (fp64) and the largest magnitude.  Same decomposition as above: partials per row slab, then a
 // second kernel that folds them in slab order.

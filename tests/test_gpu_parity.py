@@ -83,6 +83,53 @@ def test_calib_moments_batched(nb, rows, K):
     assert absmax.item() == np.float32(max(OC.absmax(x) for x in x64))
 
 
+def test_calib_moments_dirty_workspace_and_graph_replays():
+    """The workspace of the moments call is scratch nobody clears: whatever bytes it holds, the sums are
+    the same, and a captured call gives them again on every replay."""
+    rows, K = 1500, 1160
+    rng = np.random.default_rng(170)
+    bits = _rand_bits(rng, rows, K)
+    x = _to_dev(bits)
+    xf = OF.bf16_bits_to_f64(bits)
+    ref = OC.column_sumsq(xf)
+    nbytes = pq.pq_workspace_bytes(pq.OP_CALIB_MOMENTS, 0, 0, rows, 0, K, 1)
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(5)
+    for fill in ("ones", "random", "zeros"):
+        if fill == "random":
+            ws = torch.randint(0, 256, (nbytes,), dtype=torch.uint8, device=DEV, generator=gen)
+        else:
+            ws = torch.full((nbytes,), 0xFF if fill == "ones" else 0, dtype=torch.uint8, device=DEV)
+        sumsq = torch.zeros(K, dtype=torch.float64, device=DEV)
+        absmax = torch.zeros(1, dtype=torch.float32, device=DEV)
+        pq.pq_calib_moments(x, sumsq, absmax, workspace=ws)
+        torch.cuda.synchronize()
+        assert np.all(np.abs(sumsq.cpu().numpy() - ref) <= T.MOMENTS_RTOL * ref), fill
+        assert absmax.item() == np.float32(OC.absmax(xf))
+    # eager result, then a graph of two launches (same workspace) replayed three times with eager work between
+    eager = torch.zeros(K, dtype=torch.float64, device=DEV)
+    pq.pq_calib_moments(x, eager, None, workspace=ws)
+    pq.pq_calib_moments(x, eager, None, workspace=ws)
+    torch.cuda.synchronize()
+    out = torch.zeros(K, dtype=torch.float64, device=DEV)
+    amax = torch.zeros(1, dtype=torch.float32, device=DEV)
+    g_ = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g_):
+        pq.pq_calib_moments(x, out, amax, workspace=ws)
+        pq.pq_calib_moments(x, out, amax, workspace=ws)
+    for replay in range(3):
+        out.zero_()
+        amax.zero_()
+        torch.cuda.synchronize()
+        g_.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager), "replay %d differs from the eager result" % replay
+        assert amax.item() == np.float32(OC.absmax(xf))
+        scratch = torch.zeros(K, dtype=torch.float64, device=DEV)
+        pq.pq_calib_moments(x, scratch, None, workspace=ws)          # eager use of the same workspace in between
+        torch.cuda.synchronize()
+
+
 # ---------------------------------------------------------------------------- quantizers
 
 def _quantize_act_gpu(fmt, g, x, M, K, ld, perm, T_dev):
