@@ -54,6 +54,21 @@ __device__ __forceinline__ float e4m3_decode(uint32_t byte) {
   return as_f32(((e + 120u) << 23) | (m << 20));       // 2^(e-7) * (1 + m/8)
 }
 
+// The same rounding without branches, with the rounded value itself: the step of the E4M3 grid at t
+// is max(2^(e-3), 2^-9), e the exponent of t.  Adding M = max(2^(e+20), 2^14) makes that step the last
+// place of the sum, so the adder rounds t onto the grid (nearest, ties to even); sum - M is the grid
+// value, exactly, and the sum's mantissa field counts the steps: m in 8..16 of a normal result (16 is the
+// next binade's first value -- the carry lands in the exponent field), or 0..8 steps of 2^-9 below 2^-6,
+// which is the subnormal byte itself.  byte = m + 8 (e + 6) for normals, with (e + 6) = field(M) - 141.
+__device__ __forceinline__ void e4m3_round(float t, uint32_t& byte, float& value) {
+  t = fminf(t, 448.0f);
+  const uint32_t eb = as_u32(t) & 0x7F800000u;
+  const uint32_t mb = max(eb + (20u << 23), 141u << 23);       // bits of M; 2^14 has the exponent field 141
+  const float sum = t + as_f32(mb);
+  value = sum - as_f32(mb);
+  byte = (as_u32(sum) - mb) + ((mb >> 20) - (141u << 3));
+}
+
 // ---------------------------------------------------------------- E2M1 (element codes)
 // index 0..7 of the nearest E2M1 magnitude, ties to the even index, saturating at 6; a >= 0.
 // Adding 2^(e+22), e = exponent of max(a, 1), rounds a to a multiple of 2^(e-1) (one mantissa
@@ -263,44 +278,38 @@ __device__ __forceinline__ float int_code_value(float x, float inv, float Q) {
 struct Nv4Scale {
   uint32_t byte;
   float inv;
-  float d;       // decoded block scale times the tensor scale
+  float d;       // decoded block scale times the tensor scale, rounded to binary32
+  float value;   // decoded block scale (exact)
 };
 __device__ __forceinline__ float nv4_enc_scale(float T) { return is_normal32(T) ? 1.0f / T : 0.0f; }
+// A tensor scale T with an exponent field in [13, 241] keeps every non-zero d = value(s_b) * T (values
+// from 2^-9 to 448) a normal number with an exponent field in [4, 250], inside the window in which the
+// hardware reciprocal plus one Newton step is the IEEE quotient: no per-group test is needed then.  T is
+// the same for a whole launch, so the test is scalar and leaves the loops.
+__device__ __forceinline__ bool nv4_tensor_scale_is_tame(float T) { return ((as_u32(T) >> 23) - 13u) <= 228u; }
 __device__ __forceinline__ Nv4Scale nv4_scale(float amax, float T, float encT) {
   Nv4Scale r;
   // division by 6: the cheap sequence differs from IEEE only below 2^-124, far under the
   // smallest E4M3 value, where the byte is 0 either way
   const float t = div_const(amax * encT, 6.0f, 1.0f / 6.0f);
-  r.byte = e4m3_rne_sat(t);
-  r.d = e4m3_decode(r.byte) * T;
-  const bool normal = is_normal32(r.d);
-  const float inv = recip_exact(r.d, normal);
-  r.inv = normal ? inv : 0.0f;
+  e4m3_round(t, r.byte, r.value);
+  const float value = r.value;
+  r.d = value * T;
+  if (__builtin_expect(nv4_tensor_scale_is_tame(T), 1)) {
+    const float q = __builtin_amdgcn_rcpf(r.d);
+    const float e = __builtin_fmaf(-r.d, q, 1.0f);
+    r.inv = value != 0.0f ? __builtin_fmaf(e, q, q) : 0.0f;
+  } else {
+    const bool normal = is_normal32(r.d);
+    const float inv = recip_exact(r.d, normal);
+    r.inv = normal ? inv : 0.0f;
+  }
   return r;
 }
 template <int R>
 __device__ __forceinline__ void nv4_scales(const float (&amax)[R], float T, float encT, Nv4Scale (&out)[R]) {
-  bool normal[R];
-  bool fast = true;
 #pragma unroll
-  for (int r = 0; r < R; ++r) {
-    const float t = div_const(amax[r] * encT, 6.0f, 1.0f / 6.0f);
-    out[r].byte = e4m3_rne_sat(t);
-    out[r].d = e4m3_decode(out[r].byte) * T;
-    normal[r] = is_normal32(out[r].d);
-    fast = fast && (!normal[r] || ((as_u32(out[r].d) >> 23) - 3u) <= 248u);
-  }
-  if (__builtin_expect(__all(fast), 1)) {
-#pragma unroll
-    for (int r = 0; r < R; ++r) {
-      const float q = __builtin_amdgcn_rcpf(out[r].d);
-      const float e = __builtin_fmaf(-out[r].d, q, 1.0f);
-      out[r].inv = normal[r] ? __builtin_fmaf(e, q, q) : 0.0f;
-    }
-  } else {
-#pragma unroll
-    for (int r = 0; r < R; ++r) out[r].inv = normal[r] ? 1.0f / out[r].d : 0.0f;
-  }
+  for (int r = 0; r < R; ++r) out[r] = nv4_scale(amax[r], T, encT);
 }
 __device__ __forceinline__ uint32_t nv4_code(float x, float inv) {
   float v = x * inv;

@@ -220,7 +220,7 @@ __global__ __launch_bounds__(64 * kQeMaxWaves) void quant_error_kernel(TensorLis
           nv4_scales<R>(amax, T, encT, s);
 #pragma unroll
           for (int rr = 0; rr < R; ++rr) {
-            const double d = (double)e4m3_decode(s[rr].byte) * (double)T;   // exact: 4 + 24 bits
+            const double d = (double)s[rr].value * (double)T;   // exact: 4 + 24 bits
 #pragma unroll
             for (int j = 0; j < 8; j += 2) {
               // quantize two elements on the conversion unit and decode them again: q = +-E2M1 value
