@@ -155,219 +155,6 @@ int run_pack_operand(pq_format fmt, int group, const uint8_t* codes, const void*
   return fail(PQ_ERR_FORMAT, "unsupported (format, group) = (%d, %d)", (int)fmt, group);
 }
 
-// ------------------------------------------------------------------ fused quantizer -> panel
-// Dynamic activation quantization (paper Eq. 1-2, the contract of pq_quantize.hip) that stores
-// its result directly in the panel layout, so that the forward path needs no packing pass.
-// A workgroup of up to sixteen waves owns RPW rows (8 or 4); a wave works on 64 / RPW chunks (one
-// or two 64-wide K steps) of all its rows at a time: lane (64 / RPW) r + c holds chunk c (8
-// channels) of row r, the wave loads whole 128-byte lines and stores the rows' codes of a step as
-// one contiguous run of 32 RPW bytes.  Groups wider than what a wave covers per trip take
-// several trips' chunks at once.  INT: the group maxima of the rows are kept in LDS until the row
-// maximum, and with it the per-row power of two, is known.
-constexpr int kQuantPanelMaxWaves = 16;
-
-template <int FMT, int G, int RPW>
-__global__ __launch_bounds__(64 * kQuantPanelMaxWaves) void quantize_panel_kernel(
-    const uint16_t* __restrict__ x, int64_t rows, int64_t K, int64_t ld, const float* __restrict__ tensor_scale,
-    int64_t steps, int64_t units, uint8_t* __restrict__ p_codes, uint16_t* __restrict__ p_scales,
-    float* __restrict__ p_mul, uint32_t* __restrict__ c_codes, void* __restrict__ c_scales) {
-  constexpr int LPR = 64 / RPW;                             // lanes (= chunks per trip) of a row
-  constexpr int SPG = G > LPR * 8 ? G / (LPR * 8) : 1;      // trips' worth of chunks a group spans
-  constexpr int LPG = G / 8 < LPR ? G / 8 : LPR;            // lanes of a row that share a group
-  extern __shared__ float h_lds[];                          // INT: [RPW][units] group maxima
-  __shared__ float wave_rowmax[kQuantPanelMaxWaves][RPW];
-  // the wave index is uniform over a wave: held in a scalar register, so is every address part
-  // that depends only on the group block
-  const int tid = threadIdx.x, lane = tid & 63, n_waves = blockDim.x >> 6;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int r_local = lane / LPR, c_local = lane % LPR;
-  const int64_t r0 = (int64_t)blockIdx.x * RPW;
-  const int64_t r = r0 + r_local;
-  const bool r_ok = r < rows;
-  const int n_chunks = (int)steps * 8;                      // chunks per row, a half step past K included
-  const int k_chunks = (int)(K / 8);                        // chunks that exist
-  const int n_units = (int)units;
-  float T = 0.0f, encT = 0.0f;
-  if constexpr (FMT == kNvfp4) {
-    T = *tensor_scale;
-    encT = nv4_enc_scale(T);
-  }
-  float row_max = 0.0f;
-  const int blocks = (n_chunks + SPG * LPR - 1) / (SPG * LPR);       // group blocks along K
-  // per-lane parts of the addresses; chunk cb + c_local (cb a multiple of LPR, uniform) lives at
-  //   x_lane + 8 cb,   pc_lane + 32 rows (cb / 8),   ps_lane + rows (cb / 4)   (NVFP4 unit)
-  const uint16_t* x_lane = x + (r_ok ? r : 0) * ld + c_local * 8;
-  uint8_t* pc_lane = p_codes + ((int64_t)(c_local >> 3) * rows + r) * 32 + (c_local & 7) * 4;
-  uint16_t* ps_lane = p_scales + (int64_t)(c_local >> 2) * rows + r;
-  uint32_t* cc_lane = c_codes ? c_codes + r * k_chunks + c_local : nullptr;
-  // one group block: quantize, store codes and scales
-  auto process = [&](int b, const uint4 (&raw)[SPG]) {
-    float v[SPG][8];
-#pragma unroll
-    for (int t = 0; t < SPG; ++t) {
-      const uint4 p = raw[t];
-      v[t][0] = bf16_lo(p.x); v[t][1] = bf16_hi(p.x); v[t][2] = bf16_lo(p.y); v[t][3] = bf16_hi(p.y);
-      v[t][4] = bf16_lo(p.z); v[t][5] = bf16_hi(p.z); v[t][6] = bf16_lo(p.w); v[t][7] = bf16_hi(p.w);
-    }
-    float a = 0.0f;
-#pragma unroll
-    for (int t = 0; t < SPG; ++t)
-#pragma unroll
-      for (int j = 0; j < 8; ++j) a = fmaxf(a, fabsf(v[t][j]));
-    a = group_max<LPG>(a);
-    uint32_t codes[SPG];
-    uint32_t sc_bits;                               // NVFP4: E4M3 byte; INT: fp32 bits of the scale
-    if constexpr (FMT == kNvfp4) {
-      const Nv4Scale sc = nv4_scale(a, T, encT);
-#pragma unroll
-      for (int t = 0; t < SPG; ++t) {
-        uint32_t c = 0;
-        c = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(c, v[t][0] * sc.inv, v[t][1] * sc.inv, 1.0f, 0);
-        c = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(c, v[t][2] * sc.inv, v[t][3] * sc.inv, 1.0f, 1);
-        c = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(c, v[t][4] * sc.inv, v[t][5] * sc.inv, 1.0f, 2);
-        c = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(c, v[t][6] * sc.inv, v[t][7] * sc.inv, 1.0f, 3);
-        codes[t] = c;
-      }
-      sc_bits = sc.byte;
-    } else {
-      const IntScale sc = int_scale<FMT>(a);
-#pragma unroll
-      for (int t = 0; t < SPG; ++t) codes[t] = int_codes8(v[t], sc.inv);
-      sc_bits = as_u32(sc.s);
-      row_max = fmaxf(row_max, a);
-    }
-    // codes: the panel takes every chunk of a step (a half step past K holds zeros), the
-    // row-major copy only what exists
-#pragma unroll
-    for (int t = 0; t < SPG; ++t) {
-      const int cb = (b * SPG + t) * LPR;           // uniform
-      if (r_ok && cb + c_local < n_chunks)
-        *reinterpret_cast<uint32_t*>(pc_lane + (int64_t)(cb >> 3) * rows * 32) = codes[t];
-      if (c_codes && r_ok && cb + c_local < k_chunks) cc_lane[cb] = codes[t];
-    }
-    // scales
-    const int cb0 = b * SPG * LPR;
-    if constexpr (FMT == kNvfp4) {
-      // a unit is the two bytes of 32 k = four lanes; the first lane of the quad collects the byte
-      // of the second pair
-      const uint32_t other = dpp_u32<0x4E>(sc_bits);            // lane ^ 2
-      const int u = (cb0 + c_local) >> 2;
-      if ((c_local & 3) == 0 && r_ok && u < n_units) {
-        const uint16_t two = (uint16_t)(sc_bits | (other << 8));
-        ps_lane[(int64_t)(cb0 >> 2) * rows] = two;
-        if (c_scales) reinterpret_cast<uint16_t*>(c_scales)[r * (K / 32) + u] = two;
-      }
-    } else {
-      // group of this lane's chunk; its first lane stores
-      const int g = SPG > 1 ? b : (cb0 + c_local) / (G / 8);
-      if (c_local % LPG == 0 && r_ok && g < n_units) {
-        h_lds[r_local * n_units + g] = a;
-        if (c_scales) reinterpret_cast<uint32_t*>(c_scales)[r * units + g] = sc_bits;
-      }
-    }
-  };
-  // U group blocks per trip: their loads are all issued before the first is processed, so that a
-  // wave keeps several lines in flight
-  constexpr int U = SPG == 1 ? 3 : 1;
-  for (int b0 = wave; b0 < blocks; b0 += U * n_waves) {
-    uint4 raw[U][SPG];
-#pragma unroll
-    for (int q = 0; q < U; ++q)
-#pragma unroll
-      for (int t = 0; t < SPG; ++t) {
-        const int cb = ((b0 + q * n_waves) * SPG + t) * LPR;          // uniform
-        raw[q][t] = make_uint4(0u, 0u, 0u, 0u);
-        if (r_ok && cb + c_local < k_chunks) raw[q][t] = *reinterpret_cast<const uint4*>(x_lane + (int64_t)cb * 8);
-      }
-#pragma unroll
-    for (int q = 0; q < U; ++q) {
-      const int b = b0 + q * n_waves;
-      if (b < blocks) process(b, raw[q]);              // wave-uniform
-    }
-  }
-  if constexpr (FMT != kNvfp4) {
-    constexpr float Q = qmax_of(FMT);
-    row_max = group_max<LPR>(row_max);               // the lanes of a row
-    if (c_local == 0) wave_rowmax[wave][r_local] = row_max;
-    __syncthreads();
-    // every thread recomputes the factor of the row it will write below
-    const int wr = lane % RPW;                       // row of the write mapping
-    float mx = 0.0f;
-    for (int w = 0; w < n_waves; ++w) mx = fmaxf(mx, wave_rowmax[w][wr]);
-    // E = exponent(mx) - 10: the row maximum lands in [2^10, 2^11) (see pack_operand_kernel)
-    int e = (int)((as_u32(mx) >> 23) & 0xFF) - 127;
-    if (mx == 0.0f) e = 0;
-    const int E = max(-120, min(120, e - 10));
-    const float down = as_f32((uint32_t)(127 - E) << 23);
-    const int64_t row = r0 + wr;
-    if (wave == 0 && lane < RPW && row < rows) p_mul[row] = as_f32((uint32_t)(127 + E) << 23) / Q;
-    for (int u0 = 0; u0 < n_units; u0 += LPR * n_waves) {
-      const int u = u0 + wave * LPR + lane / RPW;
-      if (row < rows && u < n_units) {
-        const _Float16 hn = (_Float16)(h_lds[wr * n_units + u] * down);
-        p_scales[(int64_t)u * rows + row] = __builtin_bit_cast(uint16_t, hn);
-      }
-    }
-  }
-}
-
-template <int FMT, int G, int RPW>
-static int launch_qpanel_r(const void* x, int64_t rows, int64_t K, int64_t ld, const float* ts,
-                           const OperandLayout& L, uint8_t* operand, uint8_t* codes, void* scales,
-                           hipStream_t st) {
-  const int64_t blocks = (rows + RPW - 1) / RPW;
-  const size_t shmem = FMT == kNvfp4 ? 0 : (size_t)RPW * L.units * sizeof(float);
-  auto kern = quantize_panel_kernel<FMT, G, RPW>;
-  if (shmem > 48 * 1024) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
-    if (e != hipSuccess) return check_hip(e, "hipFuncSetAttribute(quantize_panel_kernel)");
-  }
-  // one wave per group block along K, up to eight (four workgroups per compute unit)
-  constexpr int LPR = 64 / RPW;
-  constexpr int SPG = G > LPR * 8 ? G / (LPR * 8) : 1;
-  const int64_t k_blocks = (L.steps * 8 + SPG * LPR - 1) / (SPG * LPR);
-  int n_waves = 1;
-  while (n_waves < 8 && n_waves * 3 <= k_blocks) n_waves *= 2;   // >= 2-3 trips per wave
-  hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(64 * n_waves), shmem, st, (const uint16_t*)x, rows, K, ld, ts,
-                     L.steps, L.units, operand + L.codes, (uint16_t*)(operand + L.scales),
-                     (float*)(operand + L.mul), (uint32_t*)codes, scales);
-  return check_hip(hipGetLastError(), "quantize_panel_kernel");
-}
-
-// Eight rows per workgroup: four rows (twice the workgroups, spread more evenly over the compute
-// units when rows / 8 is a little above a multiple of 256) measured the same within 2 % on
-// 4608 x 3072 with either four or eight waves, so the template is instantiated for 8 only.
-template <int FMT, int G>
-static int launch_qpanel(const void* x, int64_t rows, int64_t K, int64_t ld, const float* ts,
-                         const OperandLayout& L, uint8_t* operand, uint8_t* codes, void* scales,
-                         hipStream_t st) {
-  return launch_qpanel_r<FMT, G, 8>(x, rows, K, ld, ts, L, operand, codes, scales, st);
-}
-
-int run_quantize_packed(pq_format fmt, int group, const void* x, int64_t rows, int64_t K, int64_t ld,
-                        const float* ts, void* operand, uint8_t* codes, void* scales, hipStream_t st) {
-  if (rows > 0x7FFFFFF0) return fail(PQ_ERR_SHAPE, "too many rows");
-  const OperandLayout L = operand_layout(fmt, group, rows, K);
-  if (fmt != PQ_FMT_NVFP4 && (size_t)8 * L.units * 4 > 150 * 1024)
-    return fail(PQ_ERR_SHAPE, "K=%lld has too many groups for the fused quantizer", (long long)K);
-  uint8_t* o = (uint8_t*)operand;
-  if (fmt == PQ_FMT_NVFP4) return launch_qpanel<kNvfp4, 16>(x, rows, K, ld, ts, L, o, codes, scales, st);
-#define PQ_INT_CASE(F, FE)                                                                  \
-  if (fmt == F) {                                                                           \
-    switch (group) {                                                                        \
-      case 32: return launch_qpanel<FE, 32>(x, rows, K, ld, ts, L, o, codes, scales, st);   \
-      case 64: return launch_qpanel<FE, 64>(x, rows, K, ld, ts, L, o, codes, scales, st);   \
-      case 128: return launch_qpanel<FE, 128>(x, rows, K, ld, ts, L, o, codes, scales, st); \
-      case 256: return launch_qpanel<FE, 256>(x, rows, K, ld, ts, L, o, codes, scales, st); \
-    }                                                                                       \
-  }
-  PQ_INT_CASE(PQ_FMT_INT4, kInt4)
-  PQ_INT_CASE(PQ_FMT_INT3, kInt3)
-#undef PQ_INT_CASE
-  return fail(PQ_ERR_FORMAT, "unsupported (format, group) = (%d, %d)", (int)fmt, group);
-}
-
 int run_qgemm_packed(pq_format fmt, int group, const void* a_operand, const float* a_ts,
                      const void* w_operand, const float* w_ts, int64_t M, int64_t N, int64_t K,
                      const void* bias, void* y, int64_t ldy, bool out_f32, hipStream_t st) {
