@@ -20,10 +20,10 @@
  *   - Unless a parameter says "host", every pointer is DEVICE memory owned by the caller and
  *     must stay valid until the work queued on `stream` has finished.  Tensor pointers must be
  *     16-byte aligned.  The library allocates no device memory; scratch memory comes in
- *     through `workspace` (size from pq_workspace_bytes()).  The one host allocation: the two
- *     selection calls, which synchronise anyway, read their error sums back through a small
- *     pinned host buffer (4 KB for up to 30 batches) that the calling thread allocates at its
- *     first such call and keeps until the process ends.
+ *     through `workspace` (size from pq_workspace_bytes()).  The one host allocation: the calls
+ *     that synchronise anyway (the two selection calls, pq_qgemm_check_int_scales) read their
+ *     results back through a small pinned host buffer (4 KB for up to 30 batches) that the calling
+ *     thread allocates at its first such call and frees when the thread ends.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls are
  *     asynchronous on it unless stated otherwise.
  *   - All arguments are validated on the host before anything is launched.  Every function
@@ -165,6 +165,8 @@ int pq_tensor_scale(const float* absmax, float* tensor_scale_out, void* stream);
  * w_bf16: bf16 [N, K] contiguous.
  * act_tensor_scale / w_tensor_scale: NVFP4 only (host floats, T of the header comment; the
  * activation one comes from the calibration absmax, the weight one from max|W|); ignored for INT.
+ * K <= 34128: one row as fp32 must fit the LDS of the error evaluation (4.5 K bytes of 150 KB);
+ * pq_workspace_bytes returns 0 beyond, the call PQ_ERR_SHAPE before anything is launched.
  * alphas: HOST array of n_alpha values in [0, 1], 1 <= n_alpha <= PQ_MAX_ALPHAS.
  * perm_out: int32 [K] device.  report: HOST struct, filled on return.
  * This call synchronises `stream` once before returning (the decision is taken on the host).
@@ -209,7 +211,7 @@ int pq_select_perm_output_error(pq_format fmt, int group, const double* act_sums
  * sample; the building block of E above, also what "quantization error with / without the
  * permutation" reports):   err_out[0] = sum_{r,k} (x[r, perm[k]] - xhat)^2   (fp64).
  * x: bf16 [rows, K] contiguous.  perm: int32 [K] or NULL (identity).  tensor_scale: host float,
- * NVFP4 only.  err_out: double [1] device, overwritten.
+ * NVFP4 only.  err_out: double [1] device, overwritten.  K <= 34128 as for pq_select_perm.
  */
 int pq_quant_error(pq_format fmt, int group, const void* x_bf16, int64_t rows, int64_t K,
                    const int32_t* perm, float tensor_scale, double* err_out, void* workspace,
@@ -252,13 +254,28 @@ int pq_quantize_act(pq_format fmt, int group, const void* x_bf16, int64_t M, int
  * the quantizers above; a_tensor_scale / w_tensor_scale: float [1] device (NVFP4; ignored for
  * INT, may be NULL).  y_bf16: bf16 [M, ldy], ldy >= N, ldy % 8 == 0.
  * INT scales must be of the form fl32(h / Q) with h a bf16 value, which is what the quantizers
- * above produce from bf16 inputs (the kernel folds h exactly into its fp16 MFMA operands).
+ * above produce from bf16 inputs (the kernel folds h exactly into its fp16 MFMA operands; the
+ * product then differs from the stored-scale one by the 2^-24 rounding of h / Q per factor).  Scales
+ * of another origin give a different product without an error: check them once with
+ * pq_qgemm_check_int_scales.  Inside a row the operand holds h * 2^-E with E from the row's largest
+ * group: a group more than 2^24 below it loses low bits of h (below 2^-35: all of them) -- its terms
+ * are then below 2^-24 of the row's largest terms, the resolution of the fp32 accumulation anyway.
  * workspace: pq_workspace_bytes(PQ_OP_QGEMM, fmt, group, M, N, K, 0) bytes.
  */
 int pq_qgemm(pq_format fmt, int group, const uint8_t* a_codes, const void* a_scales,
              const float* a_tensor_scale, const uint8_t* w_codes, const void* w_scales,
              const float* w_tensor_scale, int64_t M, int64_t N, int64_t K, void* y_bf16,
              int64_t ldy, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Counts the INT group scales that pq_qgemm / pq_pack_operand would not reproduce exactly: those not of
+ * the form fl32(h / Q), h a non-negative bf16 value (also negative and non-finite ones).  scales: float
+ * [rows, K / group] device.  bad_count: HOST int64, written on return; 0 means the product computed from
+ * these scales is the one Eq. 8 defines with them.  workspace: at least 256 bytes of device memory.
+ * Synchronises `stream`.  PQ_ERR_FORMAT for NVFP4 (its E4M3 scales are always exact in the operand).
+ */
+int pq_qgemm_check_int_scales(pq_format fmt, int group, const void* scales, int64_t rows, int64_t K,
+                              int64_t* bad_count, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * pq_qgemm in two steps, for callers that want the scale preparation out of the per-token path

@@ -52,10 +52,10 @@ size_t pq_workspace_bytes(pq_op op, pq_format fmt, int group, int64_t M, int64_t
       if (M <= 0 || K <= 0) return 0;
       return moments_workspace_bytes(M, K, n_batches);
     case PQ_OP_SELECT_PERM:
-      if (M <= 0 || N <= 0 || K <= 0 || n_batches <= 0) return 0;
+      if (M <= 0 || N <= 0 || K <= 0 || K > kSelectMaxK || n_batches <= 0) return 0;
       return select_workspace_bytes(M, N, K, n_batches);
     case PQ_OP_QUANT_ERROR:
-      if (M <= 0) return 0;
+      if (M <= 0 || K > kSelectMaxK) return 0;
       return quant_error_workspace_bytes(M);
     case PQ_OP_CHANNEL_STATS:
       if (M <= 0 || K <= 0) return 0;
@@ -143,7 +143,10 @@ static int select_common(bool output_metric, pq_format fmt, int group, const dou
   if (n_batches <= 0) return fail(PQ_ERR_SHAPE, "%s: n_batches=%d must be positive", who, n_batches);
   if (n_alpha <= 0 || n_alpha > PQ_MAX_ALPHAS)
     return fail(PQ_ERR_SHAPE, "%s: n_alpha=%d outside 1..%d", who, n_alpha, PQ_MAX_ALPHAS);
-  if (K > 65536) return fail(PQ_ERR_SHAPE, "%s: K=%lld above the supported 65536", who, (long long)K);
+  if (K > (output_metric ? 65536 : kSelectMaxK))
+    return fail(PQ_ERR_SHAPE, "%s: K=%lld above the supported %lld%s", who, (long long)K,
+                (long long)(output_metric ? 65536 : kSelectMaxK),
+                output_metric ? "" : " (a row must fit the error evaluation's LDS)");
   if (output_metric && K % 32) return fail(PQ_ERR_SHAPE, "%s: K=%lld must be a multiple of 32", who, (long long)K);
   if (output_metric && (M > (1 << 24) || N > (1 << 24))) return fail(PQ_ERR_SHAPE, "%s: a dimension exceeds 2^24", who);
   for (int j = 0; j < n_alpha; ++j)
@@ -197,7 +200,9 @@ int pq_quant_error(pq_format fmt, int group, const void* x, int64_t rows, int64_
   int rc = check_format(fmt, group, K);
   if (rc) return rc;
   if (rows <= 0) return fail(PQ_ERR_SHAPE, "pq_quant_error: rows=%lld must be positive", (long long)rows);
-  if (K > 65536) return fail(PQ_ERR_SHAPE, "pq_quant_error: K=%lld above the supported 65536", (long long)K);
+  if (K > kSelectMaxK)
+    return fail(PQ_ERR_SHAPE, "pq_quant_error: K=%lld above the supported %lld (a row must fit the kernel's LDS)",
+                (long long)K, (long long)kSelectMaxK);
   if (!aligned16(x)) return fail(PQ_ERR_SHAPE, "pq_quant_error: x must be 16-byte aligned");
   size_t need = quant_error_workspace_bytes(rows);
   if (!workspace || workspace_bytes < need)
@@ -605,6 +610,20 @@ int pq_qgemm_packed_f32(pq_format fmt, int group, const void* a_operand, const f
                         int64_t K, float* y_f32, int64_t ldy, void* stream) {
   return qgemm_packed_common(fmt, group, a_operand, a_tensor_scale, w_operand, w_tensor_scale, M, N, K,
                              nullptr, y_f32, ldy, true, stream);
+}
+
+int pq_qgemm_check_int_scales(pq_format fmt, int group, const void* scales, int64_t rows, int64_t K,
+                              int64_t* bad_count, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!scales || !bad_count) return fail(PQ_ERR_NULL, "pq_qgemm_check_int_scales: scales and bad_count must not be NULL");
+  if (fmt != PQ_FMT_INT4 && fmt != PQ_FMT_INT3)
+    return fail(PQ_ERR_FORMAT, "pq_qgemm_check_int_scales: format %d has no fp32 group scales", (int)fmt);
+  int rc = check_format(fmt, group, K);
+  if (rc) return rc;
+  if (rows <= 0) return fail(PQ_ERR_SHAPE, "pq_qgemm_check_int_scales: rows=%lld must be positive", (long long)rows);
+  if (!workspace || workspace_bytes < 256)
+    return fail(PQ_ERR_WORKSPACE, "pq_qgemm_check_int_scales: workspace of 256 bytes needed, %zu given",
+                workspace ? workspace_bytes : (size_t)0);
+  return run_check_int_scales(fmt, group, scales, rows, K, bad_count, workspace, as_stream(stream));
 }
 
 int pq_probe_stream(const void* src, size_t read_bytes, void* dst, size_t write_bytes, void* stream) {

@@ -43,6 +43,9 @@ int launch_quantize_rows(pq_format fmt, int group, const void* x, int64_t rows, 
                          const int32_t* perm, const float* tensor_scale, uint8_t* codes, void* scales,
                          hipStream_t st);
 
+// The error evaluation keeps one row as fp32 in LDS, one spare slot per eight channels: 4.5 K bytes of the
+// 150 KB a workgroup may take.
+constexpr int64_t kSelectMaxK = 34128;      // largest multiple of 16 with 4.5 K <= 150 * 1024
 size_t select_workspace_bytes(int64_t M, int64_t N, int64_t K, int n_batches);
 size_t quant_error_workspace_bytes(int64_t rows);
 int run_select(pq_format fmt, int group, const double* act_sumsq, const double* w_sumsq, int64_t K,
@@ -114,6 +117,8 @@ int run_qgemm_packed(pq_format fmt, int group, const void* a_operand, const floa
                      const void* w_operand, const float* w_ts, int64_t M, int64_t N, int64_t K,
                      const void* bias, void* y, int64_t ldy, bool out_f32, hipStream_t st);
 
+int run_check_int_scales(pq_format fmt, int group, const void* scales, int64_t rows, int64_t K, int64_t* bad_count,
+                         void* ws, hipStream_t st);
 int launch_probe_stream(const void* src, size_t read_bytes, void* dst, size_t write_bytes, hipStream_t st);
 int launch_probe_mfma(int iters, float* sink, double* flops_out, hipStream_t st);
 int launch_probe_mfma_operands(pq_format fmt, int group, const void* a_operand, const void* w_operand, int64_t M,

@@ -23,6 +23,8 @@
 // LDS rows are 64 fp16 plus one 16-byte piece of padding (144 bytes): measured on gfx950, the
 // 16-byte fragment reads of the 32-row MFMA operand pattern run at full LDS rate with this
 // stride (an XOR swizzle of unpadded rows reaches two thirds of it).
+#include <string.h>
+
 #include "pq_qgemm_common.h"
 
 namespace pq {
@@ -392,6 +394,48 @@ __global__ __launch_bounds__(256) void int_scale_prep_kernel(const float* __rest
     h_out[(int64_t)row * groups + g] = __builtin_bit_cast(uint16_t, hh);
   }
   if (lane == 0) mul_out[row] = up / Q;
+}
+
+// ------------------------------------------------------------------------ INT scale form check
+// The product folds the group maximum h = bf16_rne(s * Q) into its fp16 operands instead of the stored
+// scale s, which is the same number only if s = fl32(h / Q) -- true for what the quantizers of this
+// library write from bf16 inputs, not for arbitrary fp32 scales.  This kernel counts the scales that
+// are not of that form (and the negative or non-finite ones).
+__global__ __launch_bounds__(256) void check_int_scales_kernel(const float* __restrict__ s, int64_t n, float Q,
+                                                               unsigned long long* __restrict__ bad) {
+  unsigned int mine = 0;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+    const float v = s[i];
+    const float h = as_f32(f32_to_bf16_rne(v * Q) << 16);
+    const bool ok = v >= 0.0f && v <= 3.0e38f && div_const(h, Q, 1.0f / Q) == v;
+    mine += ok ? 0u : 1u;
+  }
+  // wave total, one atomic per wave
+  for (int off = 32; off >= 1; off >>= 1) mine += (unsigned int)__shfl_xor((int)mine, off, kWave);
+  if ((threadIdx.x & 63) == 0 && mine) atomicAdd(bad, (unsigned long long)mine);
+}
+
+__global__ void zero_u64_kernel(unsigned long long* p) { *p = 0ull; }
+
+int run_check_int_scales(pq_format fmt, int group, const void* scales, int64_t rows, int64_t K, int64_t* bad_count,
+                         void* ws, hipStream_t st) {
+  const int64_t n = rows * (K / group);
+  unsigned long long* bad = (unsigned long long*)ws;
+  hipLaunchKernelGGL(zero_u64_kernel, dim3(1), dim3(1), 0, st, bad);
+  int64_t blocks = (n + 255) / 256;
+  if (blocks > 4096) blocks = 4096;
+  hipLaunchKernelGGL(check_int_scales_kernel, dim3((unsigned)blocks), dim3(256), 0, st, (const float*)scales, n,
+                     qmax_of((int)fmt), bad);
+  int rc = check_hip(hipGetLastError(), "check_int_scales_kernel");
+  if (rc) return rc;
+  double* h = pinned_doubles(1);
+  if (!h) return fail(PQ_ERR_HIP, "pq_qgemm_check_int_scales: no pinned host memory");
+  if ((rc = check_hip(hipMemcpyAsync(h, bad, 8, hipMemcpyDeviceToHost, st), "copy count"))) return rc;
+  if ((rc = check_hip(hipStreamSynchronize(st), "hipStreamSynchronize"))) return rc;
+  unsigned long long c;
+  memcpy(&c, h, 8);
+  *bad_count = (int64_t)c;
+  return PQ_OK;
 }
 
 // ------------------------------------------------------------------------ host side

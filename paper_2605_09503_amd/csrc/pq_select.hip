@@ -19,12 +19,15 @@
 // The final argmin / acceptance decision is a handful of scalar operations and runs on the host.
 #include <string.h>
 
+#include <atomic>
+
 #include "pq_device.h"
 #include "pq_host.h"
 
 namespace pq {
 
 constexpr int kMaxCand = PQ_MAX_ALPHAS + 1;   // identity + candidates
+constexpr int kMaxDevicesSeen = 64;
 
 struct AlphaList {
   double a[PQ_MAX_ALPHAS];
@@ -374,10 +377,16 @@ static int launch_qe_r(const TensorList& xs, int n_tensors, int64_t rows, int K,
                        const int32_t* cands, int n_cand, int identity_first, float T, double* part,
                        hipStream_t st) {
   auto kern = quant_error_kernel<FMT, G, R>;
-  if (q.shmem > 48 * 1024) {
+  // the attribute is per kernel instance and device; it is raised once per instance to the most any
+  // launch may ask for, not on every call
+  static std::atomic<bool> raised[kMaxDevicesSeen];
+  int dev = 0;
+  (void)hipGetDevice(&dev);
+  if (q.shmem > 48 * 1024 && (dev < 0 || dev >= kMaxDevicesSeen || !raised[dev].load(std::memory_order_acquire))) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)q.shmem);
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
     if (e != hipSuccess) return check_hip(e, "hipFuncSetAttribute(quant_error_kernel)");
+    if (dev >= 0 && dev < kMaxDevicesSeen) raised[dev].store(true, std::memory_order_release);
   }
   hipLaunchKernelGGL(kern, dim3((unsigned)q.blocks, (unsigned)n_tensors), dim3(q.threads), q.shmem, st, xs,
                      (int)rows, K, cands, n_cand, identity_first, T, q.rows_per_block, part);
@@ -400,7 +409,7 @@ static int launch_quant_error(pq_format fmt, int group, const TensorList& x, int
                               int K, const QeShape& q, const int32_t* cands, int n_cand,
                               int identity_first, float T, double* part, hipStream_t st) {
   if (rows > 0x7FFFFFFF) return fail(PQ_ERR_SHAPE, "too many rows");
-  if (q.shmem > 150 * 1024) return fail(PQ_ERR_SHAPE, "K=%d too large for the LDS-resident row", K);
+  if (q.shmem > 150 * 1024) return fail(PQ_ERR_SHAPE, "K=%d too large for the LDS-resident row", K);   // the entry points refuse this earlier
   if (fmt == PQ_FMT_NVFP4)
     return launch_qe<kNvfp4, 16>(x, n_tensors, rows, K, q, cands, n_cand, identity_first, T, part, st);
 #define PQ_INT_CASE(F, FE)                                                                                  \
@@ -533,26 +542,32 @@ int launch_identity_order(int32_t* perm, int64_t K, hipStream_t st) {
   return check_hip(hipGetLastError(), "iota_kernel");
 }
 
-// A pinned host buffer of at least n doubles that the calling thread keeps until the process ends
+// A pinned host buffer of at least n doubles that the calling thread keeps until it ends
 // (a device-to-host copy into pageable memory goes through a staging copy and costs some 10 us
 // more).  Grown, never shrunk; nullptr when the allocation fails.
-double* pinned_doubles(size_t n) {
-  thread_local double* buf = nullptr;
-  thread_local size_t cap = 0;
-  if (n > cap) {
+struct PinnedBuffer {
+  double* buf = nullptr;
+  size_t cap = 0;
+  ~PinnedBuffer() {                      // runs when the owning thread ends
     if (buf) (void)hipHostFree(buf);
-    buf = nullptr;
-    cap = 0;
+  }
+};
+double* pinned_doubles(size_t n) {
+  thread_local PinnedBuffer pb;
+  if (n > pb.cap) {
+    if (pb.buf) (void)hipHostFree(pb.buf);
+    pb.buf = nullptr;
+    pb.cap = 0;
     const size_t want = n < 512 ? 512 : n;
     void* p = nullptr;
     if (hipHostMalloc(&p, want * sizeof(double), hipHostMallocDefault) != hipSuccess) {
       (void)hipGetLastError();
       return nullptr;
     }
-    buf = (double*)p;
-    cap = want;
+    pb.buf = (double*)p;
+    pb.cap = want;
   }
-  return buf;
+  return pb.buf;
 }
 
 int run_select(pq_format fmt, int group, const double* act_sumsq, const double* w_sumsq, int64_t K,

@@ -106,6 +106,7 @@ def load():
     lib.pq_norm_quantize_act_packed.argtypes = [C.POINTER(NormParams), i32, i32, vp, i64, i64, i64, vp, vp, sz,
                                                 vp, i64, vp]
     lib.pq_probe_stream.argtypes = [vp, sz, vp, sz, vp]
+    lib.pq_qgemm_check_int_scales.argtypes = [i32, i32, vp, i64, i64, C.POINTER(C.c_int64), vp, sz, vp]
     lib.pq_probe_mfma.argtypes = [i32, vp, C.POINTER(C.c_double), vp]
     lib.pq_probe_mfma_operands.argtypes = [i32, i32, vp, vp, i64, i64, i64, i32, vp, C.POINTER(C.c_double), vp]
     for name in ("pq_calib_moments", "pq_calib_moments_batched", "pq_select_perm", "pq_quant_error", "pq_quantize_weights",
@@ -524,6 +525,15 @@ def pq_probe_mfma(iters: int, sink: torch.Tensor) -> float:
     flops = C.c_double(0.0)
     _check(load().pq_probe_mfma(iters, _ptr(sink), C.byref(flops), _stream()))
     return flops.value
+
+
+def pq_qgemm_check_int_scales(fmt: int, group: int, scales: torch.Tensor, rows: int, K: int) -> int:
+    """Number of INT group scales the product kernel would not reproduce exactly (synchronises)."""
+    ws = torch.empty(256, dtype=torch.uint8, device=scales.device)
+    bad = C.c_int64(-1)
+    _check(load().pq_qgemm_check_int_scales(fmt, group, _ptr(scales), rows, K, C.byref(bad), _ptr(ws), ws.numel(),
+                                            _stream()))
+    return bad.value
 
 
 def pq_probe_mfma_operands(fmt: int, group: int, a_operand: torch.Tensor, w_operand: torch.Tensor, M: int, N: int,

@@ -81,6 +81,23 @@ def test_calib_moments_static_validation(lib):
     assert "#define PQ_STATIC_SCRATCH_BYTES ((size_t)3 << 20)" in text and pq.STATIC_SCRATCH_BYTES == 3 << 20
 
 
+def test_select_width_limit_is_checked_on_the_host(lib):
+    """A row of the error evaluation must fit LDS: K above 34128 is refused before any launch, and
+    pq_workspace_bytes says so by returning 0."""
+    assert lib.pq_workspace_bytes(pq.OP_SELECT_PERM, pq.FMT_INT4, 64, 64, 64, 34112, 2) > 0
+    assert lib.pq_workspace_bytes(pq.OP_SELECT_PERM, pq.FMT_INT4, 64, 64, 64, 34176, 2) == 0
+    assert lib.pq_workspace_bytes(pq.OP_QUANT_ERROR, pq.FMT_INT4, 64, 64, 0, 34176, 0) == 0
+    qe = lib.pq_quant_error
+    assert qe(pq.FMT_INT4, 64, FAKE, 8, 34176, None, C.c_float(1.0), FAKE, FAKE, 1 << 20, None) == PQ_ERR_SHAPE
+    assert "LDS" in pq.pq_last_error()
+    chk = lib.pq_qgemm_check_int_scales
+    n = C.c_int64(0)
+    assert chk(pq.FMT_INT4, 64, None, 8, 64, C.byref(n), FAKE, 256, None) == PQ_ERR_NULL
+    assert chk(pq.FMT_NVFP4, 16, FAKE, 8, 64, C.byref(n), FAKE, 256, None) == PQ_ERR_FORMAT
+    assert chk(pq.FMT_INT4, 64, FAKE, 8, 64, C.byref(n), FAKE, 16, None) == PQ_ERR_WORKSPACE
+    assert chk(pq.FMT_INT4, 64, FAKE, 0, 64, C.byref(n), FAKE, 256, None) == PQ_ERR_SHAPE
+
+
 def test_quantize_validation(lib):
     qa = lib.pq_quantize_act
     assert qa(pq.FMT_NVFP4, 16, None, 4, 64, 64, None, FAKE, FAKE, FAKE, None) == PQ_ERR_NULL

@@ -567,6 +567,56 @@ def test_qgemm_int_wide_scale_range():
     assert np.all(err <= 32 * 2.0 ** -24 * mag), float((err / mag).max())
 
 
+def test_qgemm_int_group_far_below_row_maximum():
+    """Documented edge of the INT product: the operand of a row holds h * 2^-E with E from the row's largest
+    group maximum h, in fp16.  A group 2^26 below the row maximum is then a subnormal fp16 number and loses
+    low bits of h; its terms are below 2^-24 of the row's largest terms, which is the resolution of the fp32
+    accumulation, so the result still meets the accumulation bound against sum_k |xhat_k what_k|."""
+    M, N, K, g = 48, 40, 256, 64
+    rng = np.random.default_rng(915)
+    scale_a = np.array([1.0, 2.0 ** -26, 2.0 ** -13, 2.0 ** -30])          # per group of X
+    xb = synth.f64_to_bf16_bits(rng.standard_normal((M, K)) * np.repeat(scale_a, g)[None, :])
+    wb = synth.f64_to_bf16_bits(rng.standard_normal((N, K)))
+    x64, w64 = OF.bf16_bits_to_f64(xb), OF.bf16_bits_to_f64(wb)
+    qa, qw = OQ.quantize(pq.FMT_INT4, g, x64), OQ.quantize(pq.FMT_INT4, g, w64)
+    y_ref = OG.dequant_product(pq.FMT_INT4, g, qa, qw)
+    a_codes, a_scales = pq.alloc_quantized(pq.FMT_INT4, g, M, K, DEV)
+    w_codes, w_scales = pq.alloc_quantized(pq.FMT_INT4, g, N, K, DEV)
+    one = torch.ones(1, dtype=torch.float32, device=DEV)
+    pq.pq_quantize_act(pq.FMT_INT4, g, _to_dev(xb), None, None, a_codes, a_scales)
+    pq.pq_quantize_weights(pq.FMT_INT4, g, _to_dev(wb), None, w_codes, w_scales, one)
+    np.testing.assert_array_equal(a_scales.cpu().numpy(), qa.scale)          # the stored scales are still exact
+    y = torch.zeros((M, N), dtype=torch.float32, device=DEV)
+    pq.pq_qgemm_f32(pq.FMT_INT4, g, a_codes, a_scales, None, w_codes, w_scales, None, y)
+    torch.cuda.synchronize()
+    mag = np.abs(OQ.dequantize(pq.FMT_INT4, g, qa)) @ np.abs(OQ.dequantize(pq.FMT_INT4, g, qw)).T
+    err = np.abs(y.cpu().numpy().astype(np.float64) - y_ref)
+    assert np.all(err <= T.GEMM_ACC_UNITS * 2.0 ** -24 * mag), float((err / mag).max())
+    # and what is lost is really there: the far group's own contribution is not reproduced to its own precision
+    far = slice(3 * g, 4 * g)
+    part_ref = OQ.dequantize(pq.FMT_INT4, g, qa)[:, far] @ OQ.dequantize(pq.FMT_INT4, g, qw)[:, far].T
+    assert np.abs(part_ref).max() < 2.0 ** -24 * mag.min()
+
+
+def test_qgemm_check_int_scales():
+    """Scales written by the quantizers are of the form the product kernel reproduces exactly; arbitrary fp32
+    scales are counted."""
+    M, K, g = 70, 512, 64
+    rng = np.random.default_rng(916)
+    xb = _rand_bits(rng, M, K)
+    a_codes, a_scales = pq.alloc_quantized(pq.FMT_INT4, g, M, K, DEV)
+    pq.pq_quantize_act(pq.FMT_INT4, g, _to_dev(xb), None, None, a_codes, a_scales)
+    assert pq.pq_qgemm_check_int_scales(pq.FMT_INT4, g, a_scales, M, K) == 0
+    bad = a_scales.clone()
+    bad[3, 2] = 0.1234567            # not a bf16 value divided by 7
+    bad[5, 0] = -bad[5, 0].abs() - 1.0
+    bad[9, 7] = float("inf")
+    assert pq.pq_qgemm_check_int_scales(pq.FMT_INT4, g, bad, M, K) == 3
+    with pytest.raises(pq.PQError) as e:
+        pq.pq_qgemm_check_int_scales(pq.FMT_NVFP4, 16, a_scales, M, K)
+    assert e.value.code == -3
+
+
 # ------------------------------------------------------------------- packed GEMM operands
 
 @pytest.mark.parametrize("fmt,g", FMTS)
