@@ -10,6 +10,7 @@ from oracle import quantize as OQ
 
 # tolerances of the parity bar
 GEMM_F32_RTOL = 1e-3        # fp32-accumulator output vs fp64 reference, on |y_ref| > GEMM_ABS_FLOOR
+GEMM_F32_RTOL_NVFP4 = 1e-4  # the stricter form, met where outputs do not cancel heavily (measured ~1e-7 on NVFP4)
 GEMM_ABS_FLOOR = 1e-2
 GEMM_ACC_UNITS = 32         # allowed accumulation error in units of 2^-24 of sum_k |terms|
 MOMENTS_RTOL = 1e-12
@@ -38,13 +39,16 @@ def abs_product(fmt, g, qa, qw):
     return np.abs(OQ.dequantize(fmt, g, qa)) @ np.abs(OQ.dequantize(fmt, g, qw)).T
 
 
-def gemm_f32_check(y_gpu, y_ref, mag, label=""):
+def gemm_f32_check(y_gpu, y_ref, mag, label="", fmt=None):
     """fp32-accumulator output against the fp64 reference.
 
     (a) |err| <= 32 * 2^-24 * sum_k |terms| for every output: products are exact in the kernel,
         so the only error is the fp32 accumulation over K terms (worst case K * 2^-24 of the
         absolute sum, a few units of 2^-24 in practice) plus two roundings in the epilogue;
-    (b) the task's form: max relative error <= 1e-3 on outputs with |y_ref| > 1e-2.
+    (b) the task's form: max relative error <= 1e-3 on outputs with |y_ref| > 1e-2 -- 1e-4 for NVFP4
+        (fmt == 0).  The INT configurations with outlier channels have outputs just above the floor that
+        are the difference of terms thousands of times larger; there the relative form amplifies the
+        2^-24 accumulation error to as much as 5e-4, and only (a) is a tight statement.
     Returns the largest relative error of (b)."""
     y_gpu = np.asarray(y_gpu, dtype=np.float64)
     err = np.abs(y_gpu - y_ref)
@@ -54,7 +58,8 @@ def gemm_f32_check(y_gpu, y_ref, mag, label=""):
     big = np.abs(y_ref) > GEMM_ABS_FLOOR
     rel = err[big] / np.abs(y_ref[big])
     max_rel = float(rel.max()) if rel.size else 0.0
-    assert max_rel <= GEMM_F32_RTOL, "%s max rel err %.3e" % (label, max_rel)
+    rtol = GEMM_F32_RTOL_NVFP4 if fmt == 0 else GEMM_F32_RTOL
+    assert max_rel <= rtol, "%s max rel err %.3e" % (label, max_rel)
     return max_rel
 
 

@@ -137,7 +137,7 @@ def test_forward_path_full_size(name, nb):
     y32 = torch.empty((M, N), dtype=torch.float32, device=DEV)
     pq.pq_qgemm_f32(fmt, g, a_codes, a_scales, ts_a, w_codes, w_scales, ts_w, y32)
     torch.cuda.synchronize()
-    rel = T.gemm_f32_check(y32[rows_t][:, cols_t].cpu().numpy(), y_ref, T.abs_product(fmt, g, qa, qw), name)
+    rel = T.gemm_f32_check(y32[rows_t][:, cols_t].cpu().numpy(), y_ref, T.abs_product(fmt, g, qa, qw), name, fmt=fmt)
     _say("  gemm ok: max rel %.2e (fp32 out), bf16 identical to rne(ref) on %.4f of outputs (%.1f s)"
          % (rel, same, time.time() - t0))
 

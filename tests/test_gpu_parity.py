@@ -467,7 +467,7 @@ def _gemm_case(fmt, g, M, N, K, seed, ldy_pad=0):
     torch.cuda.synchronize()
     y32h = y32.cpu().numpy()
     y16h = y16.view(torch.int16).cpu().numpy().view(np.uint16)
-    rel = T.gemm_f32_check(y32h[:, :N], y_ref, T.abs_product(fmt, g, qa, qw), "fmt=%d g=%d" % (fmt, g))
+    rel = T.gemm_f32_check(y32h[:, :N], y_ref, T.abs_product(fmt, g, qa, qw), "fmt=%d g=%d" % (fmt, g), fmt=fmt)
     same = T.gemm_bf16_check(y16h[:, :N], y_ref, "fmt=%d g=%d" % (fmt, g))
     # nothing written beyond column N
     assert np.all(y32h[:, N:] == 777.0)

@@ -201,21 +201,29 @@ def test_nvfp4_band_errors_sign_and_saturation():
 
 
 def test_nvfp4_nearest_code_by_brute_force():
+    # A million elements.  The pinned binary32 sequence and the exact-real quotient disagree only within
+    # 2^-18 (relative) of an E2M1 midpoint; bf16 inputs land that close to a midpoint more often than a
+    # continuous distribution would (both x and the scale have few significant bits): 4.4e-4 of the
+    # elements here, none of them outside the near-tie window.
     rng = np.random.default_rng(13)
-    x = _bf16_values(rng, (32, 256), spread=1.0)
-    T = Qz.nvfp4_tensor_scale(np.max(np.abs(x)))
-    q = Qz.quantize_nvfp4(x, T)
-    d = np.repeat(F.e4m3_decode(q.scale) * np.float64(T), 16, axis=1)
-    ok = d > 0
-    v = np.abs(x[ok]) / d[ok]
-    dist = np.abs(v[:, None] - F.E2M1_VALUES[None, :])
-    chosen = np.abs(v - F.e2m1_decode(q.code[ok] & 7))
-    # agreement with the exact-real nearest code except within 2^-18 (relative) of a midpoint
-    bad = chosen > dist.min(axis=1)
-    mids = 0.5 * (F.E2M1_VALUES[:-1] + F.E2M1_VALUES[1:])
-    near = np.min(np.abs(v[:, None] - mids[None, :]) / mids[None, :], axis=1) < 2.0 ** -18
-    assert not np.any(bad & ~near)
-    assert bad.mean() < 1e-3
+    n_bad = n_all = 0
+    for _ in range(4):
+        x = _bf16_values(rng, (1024, 256), spread=1.0)
+        T = Qz.nvfp4_tensor_scale(np.max(np.abs(x)))
+        q = Qz.quantize_nvfp4(x, T)
+        d = np.repeat(F.e4m3_decode(q.scale) * np.float64(T), 16, axis=1)
+        ok = d > 0
+        v = np.abs(x[ok]) / d[ok]
+        dist = np.abs(v[:, None] - F.E2M1_VALUES[None, :])
+        chosen = np.abs(v - F.e2m1_decode(q.code[ok] & 7))
+        # agreement with the exact-real nearest code except within 2^-18 (relative) of a midpoint
+        bad = chosen > dist.min(axis=1)
+        mids = 0.5 * (F.E2M1_VALUES[:-1] + F.E2M1_VALUES[1:])
+        near = np.min(np.abs(v[:, None] - mids[None, :]) / mids[None, :], axis=1) < 2.0 ** -18
+        assert not np.any(bad & ~near)
+        n_bad += int(bad.sum())
+        n_all += bad.size
+    assert n_all >= 1000000 and n_bad < 1e-3 * n_all, (n_bad, n_all)
 
 
 def test_nvfp4_block_scale_against_direct_definition():
