@@ -209,6 +209,17 @@ def core_kernels(L, it, time_calls):
     t_mfma_o = time_calls(lambda i: pq.pq_probe_mfma_operands(fmt, g, L.a_op, L.w_op, M, N, K, mfma_iters, sink), 3,
                           warm_replays=3)
     t_fwd = time_calls(lambda i: L.forward(), it, warm_replays=4)
+    # two more views: the same kernel on all-zero operands at the full shape (no switching activity in the
+    # operands: what the kernel's structure allows when the chip is not held back by its power limit); and,
+    # for scale, the vendor library's dense bf16 GEMM (torch.matmul) of the unquantized tensors at the same
+    # shape -- neither is part of the path
+    a_zero, w_zero = torch.zeros_like(L.a_op), torch.zeros_like(L.w_op)
+    y_zero = torch.empty_like(L.y)
+    t_gemm_zero = time_calls(lambda i: pq.pq_qgemm_packed(fmt, g, a_zero, L.ts_a, w_zero, L.ts_w, y_zero, M, N, K), it,
+                             warm_replays=6)
+    del a_zero, w_zero, y_zero
+    t_blas = time_calls(lambda i: torch.matmul(L.x_run, L.w.t(), out=L.y), it, warm_replays=6)
+    L.forward()
 
     t_qa_warm = time_calls(lambda i: pq.pq_quantize_act_packed(fmt, g, L.x_run, L.ts_a, L.a_op), it)
     # cold: rotate through > 1 GB of distinct inputs so that no input is cache-resident
@@ -252,6 +263,10 @@ def core_kernels(L, it, time_calls):
         "qgemm_kernel": {"us": t_gemm * 1e6, "tflops": gemm_tflops, "frac_mfma_f16_peak": gemm_tflops / MFMA_F16_PEAK_TFLOPS,
                          "frac_of_mfma_only_loop_on_these_operands": gemm_tflops / mfma_o},
         "forward_quantize_act_plus_qgemm": {"us": t_fwd * 1e6, "tflops": L.flops / t_fwd / 1e12},
+        "qgemm_kernel_all_zero_operands": {"us": t_gemm_zero * 1e6, "tflops": L.flops / t_gemm_zero / 1e12,
+                                           "frac_mfma_f16_peak": L.flops / t_gemm_zero / 1e12 / MFMA_F16_PEAK_TFLOPS},
+        "reference_vendor_bf16_gemm_same_shape": {"us": t_blas * 1e6, "tflops": L.flops / t_blas / 1e12,
+                                                  "frac_mfma_f16_peak": L.flops / t_blas / 1e12 / MFMA_F16_PEAK_TFLOPS},
         "quantize_act_warm": hbm(qbytes, t_qa_warm),
         "quantize_act_cold": hbm(qbytes, t_qa_cold),
         "calib_moments_warm": hbm(mbytes, t_mom_warm),
