@@ -387,9 +387,9 @@ def cpu_baseline(layers, ms_gpu_step):
         perm_h = L.perm.cpu().numpy()
         ta = np.float32(L.ts_a.item()) if fmt == 0 else None
         tw = np.float32(L.ts_w.item()) if fmt == 0 else None
-        # about 12 M elements per sampled tensor: a second or two of the oracle's quantizer each
-        rows_w = int(min(N, max(64, (12 << 20) // K)))
-        rows_x = int(min(M, max(64, (12 << 20) // K)))
+        # about 6 M elements per sampled tensor: a second of the oracle's quantizer each
+        rows_w = int(min(N, max(64, (6 << 20) // K)))
+        rows_x = int(min(M, max(64, (6 << 20) // K)))
         w64 = OF.bf16_bits_to_f64(L.st.w_bits[:rows_w])
         x64 = OF.bf16_bits_to_f64(L.calib_bits[0][:rows_x])
         # calibration half: moments, the alpha grid's sorts, error of the original and six candidate orders
