@@ -174,3 +174,39 @@ def test_forward_path_replays_from_a_captured_graph():
         graph.replay()
         torch.cuda.synchronize()
         assert torch.equal(y.view(torch.int16), y_eager.view(torch.int16)), "replay %d differs" % i
+
+
+@pytest.mark.parametrize("fmt,g,M,N,K", [(pq.FMT_NVFP4, 16, 300, 264, 1088), (pq.FMT_INT4, 64, 520, 200, 1024),
+                                          (pq.FMT_NVFP4, 16, 4608, 512, 12288)])
+def test_forward_path_in_a_hip_graph(fmt, g, M, N, K):
+    """The deployment path (activations quantized straight into the GEMM's operand layout, then the product)
+    captured into a HIP graph: every replay, with eager work and synchronisations in between, gives the
+    bits of the eager run.  Nothing in the two calls allocates, synchronises or clears memory, so they can be
+    captured as they are.  (The third shape takes the large-tensor quantizer and the 224 x 256 product tile.)"""
+    _say("forward path in a graph fmt=%d g=%d %dx%dx%d" % (fmt, g, M, N, K))
+    rng = np.random.default_rng(9970 + g + M)
+    x = _dev(_bits(rng.standard_normal((M, K)) * np.exp(0.5 * rng.standard_normal(K))))
+    w_op, tw = _weights_operand(fmt, g, _bits(0.02 * rng.standard_normal((N, K))), None)
+    ta = torch.full((1,), 0.002, dtype=torch.float32, device=DEV)
+    a_op = torch.zeros(pq.pq_operand_bytes(fmt, g, M, K), dtype=torch.uint8, device=DEV)   # alignment gaps stay zero
+    y_eager = torch.empty((M, N), dtype=torch.bfloat16, device=DEV)
+    pq.pq_quantize_act_packed(fmt, g, x, ta, a_op)
+    pq.pq_qgemm_packed(fmt, g, a_op, ta, w_op, tw, y_eager, M, N, K)
+    torch.cuda.synchronize()
+    a_eager = a_op.clone()
+    y = torch.empty_like(y_eager)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        pq.pq_quantize_act_packed(fmt, g, x, ta, a_op)
+        pq.pq_qgemm_packed(fmt, g, a_op, ta, w_op, tw, y, M, N, K)
+    for replay in range(3):
+        a_op.zero_()
+        y.fill_(7.0)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(a_op, a_eager), "operand of replay %d differs" % replay
+        assert torch.equal(y.view(torch.int16), y_eager.view(torch.int16)), "output of replay %d differs" % replay
+        # eager use of the same buffers between the replays
+        pq.pq_quantize_act_packed(fmt, g, x, ta, a_op)
+        torch.cuda.synchronize()
