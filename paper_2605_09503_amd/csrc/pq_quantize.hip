@@ -183,17 +183,45 @@ int launch_quantize_rows(pq_format fmt, int group, const void* x, int64_t rows, 
 }
 
 // ------------------------------------------------------------------ NVFP4 tensor scale
+// The maximum of a workgroup goes to the one result word with a single atomic max (an integer max of
+// non-negative float bit patterns: order-free, so the result is deterministic).  Atomics on one address
+// are served one after the other, some 12 ns each from all over the chip: with an atomic per wave of
+// 2048 workgroups the weight tensor of an MLP layer took 100 us, of which the read was 15; hence few
+// workgroups (two per compute unit), one atomic each, and four loads in flight per lane.
+constexpr int kAbsmaxBlocks = 512;
+__device__ __forceinline__ void block_absmax_to(uint32_t m, uint32_t* out_bits) {
+  __shared__ float wave_m[4];
+  const float fm = wave_max(as_f32(m << 16));
+  if ((threadIdx.x & 63) == 0) wave_m[threadIdx.x >> 6] = fm;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const float all = fmaxf(fmaxf(wave_m[0], wave_m[1]), fmaxf(wave_m[2], wave_m[3]));
+    if (all > 0.0f) atomicMax(out_bits, as_u32(all));
+  }
+}
+__device__ __forceinline__ uint32_t absmax16(uint32_t m, const uint4& p) {
+  // |bf16| bit patterns of finite values order like the magnitudes; two 16-bit lanes per register
+  typedef uint16_t u16x2 __attribute__((ext_vector_type(2)));
+  u16x2 a = __builtin_bit_cast(u16x2, m);
+  const uint32_t w[4] = {p.x, p.y, p.z, p.w};
+#pragma unroll
+  for (int j = 0; j < 4; ++j) a = __builtin_elementwise_max(a, __builtin_bit_cast(u16x2, w[j] & 0x7FFF7FFFu));
+  return __builtin_bit_cast(uint32_t, a);
+}
 __global__ __launch_bounds__(256) void absmax_kernel(const uint4* __restrict__ x, int64_t n_chunks,
                                                      uint32_t* __restrict__ out_bits) {
-  uint32_t m = 0;
-  for (int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x; c < n_chunks; c += (int64_t)gridDim.x * 256) {
-    uint4 p = x[c];
-    uint32_t w[4] = {p.x, p.y, p.z, p.w};
+  uint32_t m2 = 0;                                      // running maxima of the even and the odd elements
+  const int64_t stride = (int64_t)gridDim.x * 256;
+  int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  for (; c + 3 * stride < n_chunks; c += 4 * stride) {
+    uint4 p[4];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) m = max(m, max(w[j] & 0x7FFFu, (w[j] >> 16) & 0x7FFFu));
+    for (int u = 0; u < 4; ++u) p[u] = x[c + u * stride];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) m2 = absmax16(m2, p[u]);
   }
-  float fm = wave_max(as_f32(m << 16));
-  if ((threadIdx.x & 63) == 0 && fm > 0.0f) atomicMax(out_bits, as_u32(fm));
+  for (; c < n_chunks; c += stride) m2 = absmax16(m2, x[c]);
+  block_absmax_to(max(m2 & 0xFFFFu, m2 >> 16), out_bits);
 }
 
 __global__ void zero_word_kernel(uint32_t* p) { *p = 0u; }
@@ -219,18 +247,14 @@ int launch_fill_float(float* p, float v, hipStream_t st) {
 // K are not read)
 __global__ __launch_bounds__(256) void absmax_rows_kernel(const uint16_t* __restrict__ x, int64_t rows, int k_chunks,
                                                           int64_t ld, uint32_t* __restrict__ out_bits) {
-  uint32_t m = 0;
+  uint32_t m2 = 0;
   const int64_t n_chunks = rows * k_chunks;
   for (int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x; c < n_chunks; c += (int64_t)gridDim.x * 256) {
     const int64_t r = c / k_chunks;
     const int col = (int)(c - r * k_chunks);
-    const uint4 p = *reinterpret_cast<const uint4*>(x + r * ld + (int64_t)col * 8);
-    const uint32_t w[4] = {p.x, p.y, p.z, p.w};
-#pragma unroll
-    for (int j = 0; j < 4; ++j) m = max(m, max(w[j] & 0x7FFFu, (w[j] >> 16) & 0x7FFFu));
+    m2 = absmax16(m2, *reinterpret_cast<const uint4*>(x + r * ld + (int64_t)col * 8));
   }
-  const float fm = wave_max(as_f32(m << 16));
-  if ((threadIdx.x & 63) == 0 && fm > 0.0f) atomicMax(out_bits, as_u32(fm));
+  block_absmax_to(max(m2 & 0xFFFFu, m2 >> 16), out_bits);
 }
 
 // The per-tensor scale of a live activation tensor, T = max|x| / (448 * 6), left in device memory
@@ -239,7 +263,7 @@ __global__ __launch_bounds__(256) void absmax_rows_kernel(const uint16_t* __rest
 int launch_dynamic_tensor_scale(const void* x, int64_t rows, int64_t K, int64_t ld, float* out, hipStream_t st) {
   const int64_t n_chunks = rows * (K / 8);
   int64_t blocks = (n_chunks + 255) / 256;
-  if (blocks > 2048) blocks = 2048;
+  if (blocks > kAbsmaxBlocks) blocks = kAbsmaxBlocks;
   hipLaunchKernelGGL(zero_word_kernel, dim3(1), dim3(1), 0, st, (uint32_t*)out);
   if (ld == K) {
     hipLaunchKernelGGL(absmax_kernel, dim3((unsigned)blocks), dim3(256), 0, st, (const uint4*)x, n_chunks,
@@ -255,7 +279,7 @@ int launch_dynamic_tensor_scale(const void* x, int64_t rows, int64_t K, int64_t 
 int launch_absmax_to_tensor_scale(const void* x, int64_t n_elems, float* out, hipStream_t st) {
   int64_t n_chunks = n_elems / 8;          // K is a multiple of 16, so no tail
   int64_t blocks = (n_chunks + 255) / 256;
-  if (blocks > 2048) blocks = 2048;
+  if (blocks > kAbsmaxBlocks) blocks = kAbsmaxBlocks;
   hipLaunchKernelGGL(zero_word_kernel, dim3(1), dim3(1), 0, st, (uint32_t*)out);
   hipLaunchKernelGGL(absmax_kernel, dim3((unsigned)blocks), dim3(256), 0, st, (const uint4*)x, n_chunks,
                      (uint32_t*)out);
