@@ -304,6 +304,22 @@ struct TailArgs {
   int n_cand, n_batches, n_alpha;
 };
 
+// s + p[i0] + p[i0 + stride] + ... (i < n), in that order, with eight loads in flight at a time (a plain
+// loop waits out one memory latency per element)
+__device__ __forceinline__ double strided_sum(const double* __restrict__ p, int64_t i0, int64_t n, int64_t stride) {
+  double s = 0.0;
+  int64_t i = i0;
+  for (; i + 7 * stride < n; i += 8 * stride) {
+    double v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = p[i + u * stride];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) s += v[u];
+  }
+  for (; i < n; i += stride) s += p[i];
+  return s;
+}
+
 __global__ __launch_bounds__(256) void select_tail_kernel(TailArgs a, double* __restrict__ out) {
   __shared__ double red[256];
   const int n_x = a.n_cand * a.n_batches;
@@ -315,18 +331,26 @@ __global__ __launch_bounds__(256) void select_tail_kernel(TailArgs a, double* __
     const int seg = is_w ? 0 : b / a.n_cand, c = is_w ? b - n_x : b % a.n_cand;
     const int64_t n = is_w ? a.w_parts : a.x_parts;
     const double* base = is_w ? a.w_part : a.x_part + (int64_t)seg * n * a.n_cand;
-    for (int64_t r = threadIdx.x; r < n; r += 256) s += base[(int64_t)c * n + r];
+    s = strided_sum(base + (int64_t)c * n, threadIdx.x, n, 256);
     dst = (int64_t)(is_w ? a.n_batches : seg) * kMaxCand + c;
   } else if (b < n_x + a.n_cand + 2) {
     const int which = b - n_x - a.n_cand;
     const double* p = which ? a.w_sumsq : a.act_sumsq;
-    for (int64_t i = threadIdx.x; i < a.K; i += 256) s += p[i];
+    s = strided_sum(p, threadIdx.x, a.K, 256);
     dst = (int64_t)(a.n_batches + 1) * kMaxCand + which;
   } else {
     const int j = b - n_x - a.n_cand - 2;
     const int32_t* p = a.cands + (int64_t)j * a.K;
     int n = 0;
-    for (int64_t i = threadIdx.x; i < a.K; i += 256) n += (p[i] != (int32_t)i);
+    int64_t i = threadIdx.x;
+    for (; i + 7 * 256 < a.K; i += 8 * 256) {
+      int32_t v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = p[i + u * 256];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) n += (v[u] != (int32_t)(i + u * 256));
+    }
+    for (; i < a.K; i += 256) n += (p[i] != (int32_t)i);
     s = (double)n;                                    // small integers: every sum below is exact
     dst = (int64_t)(a.n_batches + 1) * kMaxCand + 2 + j;
   }
