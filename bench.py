@@ -116,13 +116,12 @@ class Layer:
         self.sa.zero_(); self.sw.zero_(); self.amax_a.zero_(); self.amax_w.zero_()
         pq.pq_calib_moments_batched(self.xs, self.sa, self.amax_a, self.ws_mom)
         pq.pq_calib_moments(self.w, self.sw, self.amax_w, self.ws_mom)
-        ta = tw = 1.0
         if cfg.fmt == pq.FMT_NVFP4:
             pq.pq_tensor_scale(self.amax_a, self.ts_a)
             pq.pq_tensor_scale(self.amax_w, self.ts_w)
-            ta, tw = self.ts_a.item(), self.ts_w.item()      # host copies for the selection call
-        return pq.pq_select_perm(cfg.fmt, cfg.group, self.sa, self.sw, self.xs, self.w, ta, tw, self.perm,
-                                 workspace=self.ws_sel)
+        # the tensor scales stay on the device: nothing synchronises before the selection's own read-back
+        return pq.pq_select_perm_device_scales(cfg.fmt, cfg.group, self.sa, self.sw, self.xs, self.w, self.ts_a,
+                                               self.ts_w, self.perm, workspace=self.ws_sel)
 
     def prepare_weights(self):
         pq, cfg = self.pq, self.cfg

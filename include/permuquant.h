@@ -189,6 +189,19 @@ int pq_select_perm(pq_format fmt, int group, const double* act_sumsq, const doub
                    void* stream);
 
 /*
+ * pq_select_perm with the two NVFP4 tensor scales read from device memory (float [1] each, as
+ * pq_tensor_scale leaves them) instead of passed as host values: a calibration that computes the scales
+ * on the stream need not synchronise to fetch them before this call.  Ignored for INT (may be NULL).
+ * Everything else, the report included, as for pq_select_perm with the same two values.
+ */
+int pq_select_perm_device_scales(pq_format fmt, int group, const double* act_sumsq, const double* w_sumsq,
+                                 int64_t K, const void* const* x_calib, int n_batches, int64_t M,
+                                 const void* w_bf16, int64_t N, const float* act_tensor_scale,
+                                 const float* w_tensor_scale, const double* alphas, int n_alpha, double tau,
+                                 int32_t* perm_out, pq_select_report* report, void* workspace,
+                                 size_t workspace_bytes, void* stream);
+
+/*
  * The same selection with the layer-output error as the metric -- the other reading of "smallest
  * quantization error on the calibration data" (paper Sec. 3.3), in terms of Eq. 8:
  *     E_out(pi) = sum_b ||X_b W^T - Q(X_b P) Q(P^T W)^T||^2 / sum_b ||X_b W^T||^2.

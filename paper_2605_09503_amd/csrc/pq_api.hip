@@ -133,7 +133,8 @@ static int select_common(bool output_metric, pq_format fmt, int group, const dou
                          const double* w_sumsq, int64_t K, const void* const* x_calib, int n_batches, int64_t M,
                          const void* w_bf16, int64_t N, float act_tensor_scale, float w_tensor_scale,
                          const double* alphas, int n_alpha, double tau, int32_t* perm_out,
-                         pq_select_report* report, void* workspace, size_t workspace_bytes, void* stream) {
+                         pq_select_report* report, void* workspace, size_t workspace_bytes, void* stream,
+                         const float* act_ts_dev = nullptr, const float* w_ts_dev = nullptr) {
   const char* who = output_metric ? "pq_select_perm_output_error" : "pq_select_perm";
   if (!act_sumsq || !w_sumsq || !x_calib || !w_bf16 || !alphas || !perm_out || !report)
     return fail(PQ_ERR_NULL, "%s: a required pointer is NULL", who);
@@ -167,8 +168,22 @@ static int select_common(bool output_metric, pq_format fmt, int group, const dou
     return run_select_output(fmt, group, act_sumsq, w_sumsq, K, x_calib, n_batches, M, w_bf16, N, act_tensor_scale,
                              w_tensor_scale, alphas, n_alpha, tau, perm_out, report, workspace, as_stream(stream));
   return run_select(fmt, group, act_sumsq, w_sumsq, K, x_calib, n_batches, M, w_bf16, N,
-                    act_tensor_scale, w_tensor_scale, alphas, n_alpha, tau, perm_out, report,
+                    act_tensor_scale, w_tensor_scale, act_ts_dev, w_ts_dev, alphas, n_alpha, tau, perm_out, report,
                     workspace, as_stream(stream));
+}
+
+int pq_select_perm_device_scales(pq_format fmt, int group, const double* act_sumsq, const double* w_sumsq,
+                                 int64_t K, const void* const* x_calib, int n_batches, int64_t M,
+                                 const void* w_bf16, int64_t N, const float* act_tensor_scale,
+                                 const float* w_tensor_scale, const double* alphas, int n_alpha, double tau,
+                                 int32_t* perm_out, pq_select_report* report, void* workspace,
+                                 size_t workspace_bytes, void* stream) {
+  if (fmt == PQ_FMT_NVFP4 && (!act_tensor_scale || !w_tensor_scale))
+    return fail(PQ_ERR_NULL, "pq_select_perm_device_scales: NVFP4 needs both tensor scales");
+  const bool nv = fmt == PQ_FMT_NVFP4;
+  return select_common(false, fmt, group, act_sumsq, w_sumsq, K, x_calib, n_batches, M, w_bf16, N, 1.0f, 1.0f,
+                       alphas, n_alpha, tau, perm_out, report, workspace, workspace_bytes, stream,
+                       nv ? act_tensor_scale : nullptr, nv ? w_tensor_scale : nullptr);
 }
 
 int pq_select_perm(pq_format fmt, int group, const double* act_sumsq, const double* w_sumsq,

@@ -50,8 +50,8 @@ size_t select_workspace_bytes(int64_t M, int64_t N, int64_t K, int n_batches);
 size_t quant_error_workspace_bytes(int64_t rows);
 int run_select(pq_format fmt, int group, const double* act_sumsq, const double* w_sumsq, int64_t K,
                const void* const* x_calib, int n_batches, int64_t M, const void* w, int64_t N,
-               float act_ts, float w_ts, const double* alphas, int n_alpha, double tau,
-               int32_t* perm_out, pq_select_report* report, void* ws, hipStream_t st);
+               float act_ts, float w_ts, const float* act_ts_dev, const float* w_ts_dev, const double* alphas,
+               int n_alpha, double tau, int32_t* perm_out, pq_select_report* report, void* ws, hipStream_t st);
 int launch_candidate_orders(const double* act_sumsq, const double* w_sumsq, int64_t K, const double* alphas,
                             int n_alpha, double* keys, int32_t* rank, int32_t* cands, hipStream_t st);
 int launch_identity_order(int32_t* perm, int64_t K, hipStream_t st);

@@ -101,6 +101,12 @@ __global__ __launch_bounds__(256) void iota_kernel(int32_t* p, int K) {
   if (i < K) p[i] = i;
 }
 
+// NVFP4 tensor scale of a launch: a host value, or a device float read by the kernel (dev != nullptr)
+struct ScaleArg {
+  float value;
+  const float* dev;
+};
+
 // up to kMaxMomentBatches tensors of equal shape handled by one launch
 struct TensorList {
   const uint16_t* p[kMaxMomentBatches];
@@ -132,7 +138,7 @@ struct FloatVec<4> { typedef float type __attribute__((ext_vector_type(4))); };
 template <int FMT, int G, int R>
 __global__ __launch_bounds__(64 * kQeMaxWaves) void quant_error_kernel(TensorList xs, int rows, int K,
                                                           const int32_t* __restrict__ cands,
-                                                          int n_cand, int identity_first, float T,
+                                                          int n_cand, int identity_first, ScaleArg t_arg,
                                                           int rows_per_block,
                                                           double* __restrict__ part) {
   typedef typename FloatVec<R>::type vec_t;
@@ -146,6 +152,7 @@ __global__ __launch_bounds__(64 * kQeMaxWaves) void quant_error_kernel(TensorLis
   const int chunks = K / 8;
   const int wave_chunks = (chunks + 63) >> 6;
   const int n_items = n_cand * wave_chunks;
+  const float T = t_arg.dev ? *t_arg.dev : t_arg.value;           // uniform
   const float encT = (FMT == kNvfp4) ? nv4_enc_scale(T) : 0.0f;
   double acc = 0.0;
   for (int rg = row0; rg < row_end; rg += R) {
@@ -398,7 +405,7 @@ static QeShape qe_shape(int64_t rows, int64_t K, int n_tensors, int n_cand) {
 
 template <int FMT, int G, int R>
 static int launch_qe_r(const TensorList& xs, int n_tensors, int64_t rows, int K, const QeShape& q,
-                       const int32_t* cands, int n_cand, int identity_first, float T, double* part,
+                       const int32_t* cands, int n_cand, int identity_first, ScaleArg T, double* part,
                        hipStream_t st) {
   auto kern = quant_error_kernel<FMT, G, R>;
   // the attribute is per kernel instance and device; it is raised once per instance to the most any
@@ -419,7 +426,7 @@ static int launch_qe_r(const TensorList& xs, int n_tensors, int64_t rows, int K,
 
 template <int FMT, int G>
 static int launch_qe(const TensorList& xs, int n_tensors, int64_t rows, int K, const QeShape& q,
-                     const int32_t* cands, int n_cand, int identity_first, float T, double* part,
+                     const int32_t* cands, int n_cand, int identity_first, ScaleArg T, double* part,
                      hipStream_t st) {
   switch (q.r) {
     case 4: return launch_qe_r<FMT, G, 4>(xs, n_tensors, rows, K, q, cands, n_cand, identity_first, T, part, st);
@@ -431,7 +438,7 @@ static int launch_qe(const TensorList& xs, int n_tensors, int64_t rows, int K, c
 // part: [n_tensors][n_cand][q.parts()]
 static int launch_quant_error(pq_format fmt, int group, const TensorList& x, int n_tensors, int64_t rows,
                               int K, const QeShape& q, const int32_t* cands, int n_cand,
-                              int identity_first, float T, double* part, hipStream_t st) {
+                              int identity_first, ScaleArg T, double* part, hipStream_t st) {
   if (rows > 0x7FFFFFFF) return fail(PQ_ERR_SHAPE, "too many rows");
   if (q.shmem > 150 * 1024) return fail(PQ_ERR_SHAPE, "K=%d too large for the LDS-resident row", K);   // the entry points refuse this earlier
   if (fmt == PQ_FMT_NVFP4)
@@ -500,7 +507,7 @@ int run_quant_error(pq_format fmt, int group, const void* x, int64_t rows, int64
   TensorList tl;
   for (int b = 0; b < kMaxMomentBatches; ++b) tl.p[b] = (const uint16_t*)x;
   const QeShape q = qe_shape(rows, K, 1, 1);
-  int rc = launch_quant_error(fmt, group, tl, 1, rows, (int)K, q, perm, 1, perm ? 0 : 1, ts, part, st);
+  int rc = launch_quant_error(fmt, group, tl, 1, rows, (int)K, q, perm, 1, perm ? 0 : 1, ScaleArg{ts, nullptr}, part, st);
   if (rc) return rc;
   hipLaunchKernelGGL(reduce_rows_kernel, dim3(1, 1), dim3(256), 0, st, part, (int64_t)q.parts(), 1, 1, err_out);
   return check_hip(hipGetLastError(), "reduce_rows_kernel");
@@ -596,8 +603,8 @@ double* pinned_doubles(size_t n) {
 
 int run_select(pq_format fmt, int group, const double* act_sumsq, const double* w_sumsq, int64_t K,
                const void* const* x_calib, int n_batches, int64_t M, const void* w, int64_t N,
-               float act_ts, float w_ts, const double* alphas, int n_alpha, double tau,
-               int32_t* perm_out, pq_select_report* report, void* ws, hipStream_t st) {
+               float act_ts, float w_ts, const float* act_ts_dev, const float* w_ts_dev, const double* alphas,
+               int n_alpha, double tau, int32_t* perm_out, pq_select_report* report, void* ws, hipStream_t st) {
   SelectWs W;
   carve_select(ws, M, N, K, n_batches, &W);
   const int n_cand = n_alpha + 1;            // candidate 0 is the original order
@@ -610,7 +617,7 @@ int run_select(pq_format fmt, int group, const double* act_sumsq, const double* 
     const int nb = n_batches - b0 < kMaxMomentBatches ? n_batches - b0 : kMaxMomentBatches;
     TensorList tl;
     for (int b = 0; b < kMaxMomentBatches; ++b) tl.p[b] = (const uint16_t*)x_calib[b0 + (b < nb ? b : 0)];
-    rc = launch_quant_error(fmt, group, tl, nb, M, (int)K, qa, W.cands, n_cand, 1, act_ts,
+    rc = launch_quant_error(fmt, group, tl, nb, M, (int)K, qa, W.cands, n_cand, 1, ScaleArg{act_ts, act_ts_dev},
                             W.row_err + (size_t)b0 * qa.parts() * n_cand, st);
     if (rc) return rc;
   }
@@ -618,7 +625,7 @@ int run_select(pq_format fmt, int group, const double* act_sumsq, const double* 
   const QeShape qw = qe_shape(N, K, 1, n_cand);
   TensorList wl;
   for (int b = 0; b < kMaxMomentBatches; ++b) wl.p[b] = (const uint16_t*)w;
-  rc = launch_quant_error(fmt, group, wl, 1, N, (int)K, qw, W.cands, n_cand, 1, w_ts, w_part, st);
+  rc = launch_quant_error(fmt, group, wl, 1, N, (int)K, qw, W.cands, n_cand, 1, ScaleArg{w_ts, w_ts_dev}, w_part, st);
   if (rc) return rc;
   TailArgs ta{W.row_err, w_part, act_sumsq, w_sumsq, W.cands, qa.parts(), qw.parts(), K, n_cand, n_batches, n_alpha};
   hipLaunchKernelGGL(select_tail_kernel, dim3((unsigned)(n_cand * (n_batches + 1) + 2 + n_alpha)), dim3(256), 0,

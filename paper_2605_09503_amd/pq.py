@@ -73,6 +73,9 @@ def load():
                                    C.c_float, C.c_float, C.POINTER(C.c_double), i32, C.c_double,
                                    vp, C.POINTER(_Report), vp, sz, vp]
     lib.pq_select_perm_output_error.argtypes = lib.pq_select_perm.argtypes
+    lib.pq_select_perm_device_scales.argtypes = [i32, i32, vp, vp, i64, C.POINTER(vp), i32, i64, vp, i64,
+                                                 vp, vp, C.POINTER(C.c_double), i32, C.c_double,
+                                                 vp, C.POINTER(_Report), vp, sz, vp]
     lib.pq_quant_error.argtypes = [i32, i32, vp, i64, i64, vp, C.c_float, vp, vp, sz, vp]
     lib.pq_quantize_weights.argtypes = [i32, i32, vp, i64, i64, vp, vp, vp, vp, vp]
     lib.pq_quantize_act.argtypes = [i32, i32, vp, i64, i64, i64, vp, vp, vp, vp, vp]
@@ -216,8 +219,12 @@ def _select(entry: str, op: int, fmt, group, act_sumsq, w_sumsq, x_calib, w, act
     ptrs = (C.c_void_p * nb)(*[xb.data_ptr() for xb in x_calib])
     al = (C.c_double * len(alphas))(*[float(a) for a in alphas])
     rep = _Report()
+    if entry == "pq_select_perm_device_scales":
+        ta, tw = _ptr(act_tensor_scale), _ptr(w_tensor_scale)
+    else:
+        ta, tw = float(act_tensor_scale), float(w_tensor_scale)
     _check(getattr(load(), entry)(fmt, group, _ptr(act_sumsq), _ptr(w_sumsq), K, ptrs, nb, M, _ptr(w), N,
-                                  float(act_tensor_scale), float(w_tensor_scale), al, len(alphas),
+                                  ta, tw, al, len(alphas),
                                   float(tau), _ptr(perm_out), C.byref(rep), _ptr(workspace),
                                   0 if workspace is None else workspace.numel(), _stream()))
     return SelectReport(bool(rep.accepted), rep.alpha_index, rep.e_orig, rep.e_best,
@@ -230,6 +237,16 @@ def pq_select_perm(fmt: int, group: int, act_sumsq: torch.Tensor, w_sumsq: torch
                    alphas: Sequence[float] = DEFAULT_ALPHAS, tau: float = 0.0,
                    workspace: Optional[torch.Tensor] = None) -> SelectReport:
     return _select("pq_select_perm", OP_SELECT_PERM, fmt, group, act_sumsq, w_sumsq, x_calib, w,
+                   act_tensor_scale, w_tensor_scale, perm_out, alphas, tau, workspace)
+
+
+def pq_select_perm_device_scales(fmt: int, group: int, act_sumsq: torch.Tensor, w_sumsq: torch.Tensor,
+                                 x_calib: Sequence[torch.Tensor], w: torch.Tensor,
+                                 act_tensor_scale: Optional[torch.Tensor], w_tensor_scale: Optional[torch.Tensor],
+                                 perm_out: torch.Tensor, alphas: Sequence[float] = DEFAULT_ALPHAS, tau: float = 0.0,
+                                 workspace: Optional[torch.Tensor] = None) -> SelectReport:
+    """pq_select_perm with the NVFP4 tensor scales as device floats (no host copy needed before the call)."""
+    return _select("pq_select_perm_device_scales", OP_SELECT_PERM, fmt, group, act_sumsq, w_sumsq, x_calib, w,
                    act_tensor_scale, w_tensor_scale, perm_out, alphas, tau, workspace)
 
 

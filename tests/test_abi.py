@@ -143,6 +143,13 @@ def test_select_and_error_validation(lib):
     assert call(xs=(C.c_void_p * 1)(None)) == PQ_ERR_NULL
     assert call(wsb=16) == PQ_ERR_WORKSPACE
     assert call(ws=None) == PQ_ERR_WORKSPACE
+    # the variant with the tensor scales in device memory: NVFP4 needs both pointers, the integer formats none
+    f = lib.pq_select_perm_device_scales
+    assert call(fmt=pq.FMT_NVFP4, group=16, ta=None, tw=FAKE) == PQ_ERR_NULL
+    assert call(fmt=pq.FMT_NVFP4, group=16, ta=FAKE, tw=None) == PQ_ERR_NULL
+    assert "tensor scales" in pq.pq_last_error()
+    assert call(ta=None, tw=None, wsb=16) == PQ_ERR_WORKSPACE       # past the pointer check, stopped later
+    assert call(ta=None, tw=None, na=0) == PQ_ERR_SHAPE
     e = lib.pq_quant_error
     assert e(pq.FMT_INT3, 32, None, 4, 64, None, 1.0, FAKE, FAKE, 1 << 20, None) == PQ_ERR_NULL
     assert e(pq.FMT_INT3, 32, FAKE, 4, 64, None, 1.0, FAKE, FAKE, 8, None) == PQ_ERR_WORKSPACE

@@ -292,6 +292,13 @@ def test_select_perm_matches_oracle(name, fmt, g, M, N, K, nb):
         pq.pq_order_by_score(sa, sw, a, order)
         torch.cuda.synchronize()
         np.testing.assert_array_equal(order.cpu().numpy(), p_ref)
+    # the variant that reads the tensor scales from device memory: the same numbers bit for bit
+    perm_dev = torch.empty(K, dtype=torch.int32, device=DEV)
+    ta_d = torch.tensor([ts_a], dtype=torch.float32, device=DEV)
+    tw_d = torch.tensor([ts_w], dtype=torch.float32, device=DEV)
+    rep_d = pq.pq_select_perm_device_scales(fmt, g, sa, sw, xs, w, ta_d, tw_d, perm_dev)
+    torch.cuda.synchronize()
+    assert rep_d == rep and torch.equal(perm_dev, perm_out)
     # acceptance never raises the calibration error
     assert rep.e_best <= rep.e_orig or not rep.accepted
     # tau above the realised gain rejects and returns the identity
