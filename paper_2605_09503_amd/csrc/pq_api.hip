@@ -56,7 +56,7 @@ size_t pq_workspace_bytes(pq_op op, pq_format fmt, int group, int64_t M, int64_t
       return select_workspace_bytes(M, N, K, n_batches);
     case PQ_OP_QUANT_ERROR:
       if (M <= 0 || K > kSelectMaxK) return 0;
-      return quant_error_workspace_bytes(M);
+      return quant_error_workspace_bytes(M, K);
     case PQ_OP_CHANNEL_STATS:
       if (M <= 0 || K <= 0) return 0;
       return channel_stats_workspace_bytes(M, K);
@@ -219,7 +219,7 @@ int pq_quant_error(pq_format fmt, int group, const void* x, int64_t rows, int64_
     return fail(PQ_ERR_SHAPE, "pq_quant_error: K=%lld above the supported %lld (a row must fit the kernel's LDS)",
                 (long long)K, (long long)kSelectMaxK);
   if (!aligned16(x)) return fail(PQ_ERR_SHAPE, "pq_quant_error: x must be 16-byte aligned");
-  size_t need = quant_error_workspace_bytes(rows);
+  size_t need = quant_error_workspace_bytes(rows, K);
   if (!workspace || workspace_bytes < need)
     return fail(PQ_ERR_WORKSPACE, "pq_quant_error: workspace of %zu bytes needed, %zu given", need,
                 workspace ? workspace_bytes : (size_t)0);

@@ -47,13 +47,14 @@ int launch_quantize_rows(pq_format fmt, int group, const void* x, int64_t rows, 
 // 150 KB a workgroup may take.
 constexpr int64_t kSelectMaxK = 34128;      // largest multiple of 16 with 4.5 K <= 150 * 1024
 size_t select_workspace_bytes(int64_t M, int64_t N, int64_t K, int n_batches);
-size_t quant_error_workspace_bytes(int64_t rows);
+size_t quant_error_workspace_bytes(int64_t rows, int64_t K);
 int run_select(pq_format fmt, int group, const double* act_sumsq, const double* w_sumsq, int64_t K,
                const void* const* x_calib, int n_batches, int64_t M, const void* w, int64_t N,
                float act_ts, float w_ts, const float* act_ts_dev, const float* w_ts_dev, const double* alphas,
                int n_alpha, double tau, int32_t* perm_out, pq_select_report* report, void* ws, hipStream_t st);
 int launch_candidate_orders(const double* act_sumsq, const double* w_sumsq, int64_t K, const double* alphas,
-                            int n_alpha, double* keys, int32_t* rank, int32_t* cands, hipStream_t st);
+                            int n_alpha, double* keys, int32_t* rank, int32_t* cands, hipStream_t st,
+                            int32_t* offs = nullptr, int slot_bytes = 0);
 int launch_identity_order(int32_t* perm, int64_t K, hipStream_t st);
 double* pinned_doubles(size_t n);     // the calling thread's pinned host buffer, kept for the process lifetime
 int launch_round_robin(const int32_t* order, int64_t K, int group, int32_t* perm, hipStream_t st);

@@ -88,12 +88,16 @@ __global__ __launch_bounds__(256) void rank_count_kernel(const double* __restric
   atomicAdd(&rank[(int64_t)blockIdx.z * K + i], before);
 }
 
-// perm[z][rank(i)] = i
+// perm[z][rank(i)] = i; with offs, also the LDS byte offset of channel i's slot in the error evaluation
+// (slot i + i / 8, slot_bytes each) at the same position
 __global__ __launch_bounds__(256) void rank_scatter_kernel(const int32_t* __restrict__ rank, int K,
-                                                           int32_t* __restrict__ perms) {
+                                                           int32_t* __restrict__ perms,
+                                                           int32_t* __restrict__ offs, int slot_bytes) {
   const int i = blockIdx.x * 256 + threadIdx.x;
   if (i >= K) return;
-  perms[(int64_t)blockIdx.y * K + rank[(int64_t)blockIdx.y * K + i]] = i;
+  const int64_t at = (int64_t)blockIdx.y * K + rank[(int64_t)blockIdx.y * K + i];
+  perms[at] = i;
+  if (offs) offs[at] = (i + (i >> 3)) * slot_bytes;
 }
 
 __global__ __launch_bounds__(256) void iota_kernel(int32_t* p, int K) {
@@ -126,22 +130,37 @@ struct FloatVec<2> { typedef float type __attribute__((ext_vector_type(2))); };
 template <>
 struct FloatVec<4> { typedef float type __attribute__((ext_vector_type(4))); };
 
+// channels of one work item of a lane: a whole NVFP4 group (its scale then needs no lane exchange and is
+// worked out once), eight for the integer formats, whose groups span lanes
+template <int FMT>
+struct QeChunk { static constexpr int value = FMT == kNvfp4 ? 16 : 8; };
+
+// byte offset of channel e's slot in the LDS image of R resident rows: slot e + e / 8 (the spare slot per
+// eight channels spreads the staging writes over the banks), R floats per slot
+__host__ __device__ constexpr int qe_slot_bytes(int r) { return r * 4; }
+
 // Workgroup (x, y) evaluates rows [x * rows_per_block, (x + 1) * rows_per_block) of tensor y of
 // the list (equal shapes) for every candidate order.  R rows at a time are staged in LDS as
-// fp32, channel-major with the R rows of a channel adjacent (slot of channel e: e + e / 8, the
-// extra slot per 8 channels spreads the staging writes over the banks).  For a candidate, a
-// lane reads the eight channel indices of its chunk once and gathers the R rows of each channel
-// with one LDS read; the quantizer is the lane-cooperative one of the runtime kernels; squared
-// errors are accumulated in fp64 (every product below is exact in fp64).  Lane c of every wave
+// fp32, channel-major with the R rows of a channel adjacent; the rows after them are already on
+// their way from memory into registers while the resident ones are evaluated.  A candidate order
+// comes as the byte offsets of its channels' slots (offs[cand][position]), so a lane reads the
+// offsets of its chunk and gathers the R rows of each channel with one LDS read, no address
+// arithmetic; the quantizer is the lane-cooperative one of the runtime kernels; squared errors are
+// accumulated in fp64 (every product below is exact in fp64).  Every wave owns a fixed run of work
+// items (candidate, block of 64 chunks), candidate-major, sums a candidate's errors per lane and
+// reduces them over the wave once per candidate and set of resident rows.  Lane c of every wave
 // ends up with the wave's total for candidate c: part[y][c][x * waves + wave] (candidate-major, so
 // that the sums over the workgroups read contiguous memory).
 template <int FMT, int G, int R>
 __global__ __launch_bounds__(64 * kQeMaxWaves) void quant_error_kernel(TensorList xs, int rows, int K,
-                                                          const int32_t* __restrict__ cands,
+                                                          const int32_t* __restrict__ offs,
                                                           int n_cand, int identity_first, ScaleArg t_arg,
                                                           int rows_per_block,
                                                           double* __restrict__ part) {
   typedef typename FloatVec<R>::type vec_t;
+  constexpr int C = QeChunk<FMT>::value;
+  constexpr int PF = 4 / R;                // staging chunks (8 channels x R rows) a thread fetches ahead
+  constexpr bool kOffsetsAhead = R < 4;    // the next item's offsets are loaded during the current item
   extern __shared__ __attribute__((aligned(16))) float slots[];     // (K + K / 8) * R floats
   const int tid = threadIdx.x, nthr = blockDim.x;
   const int lane = tid & 63, n_waves = nthr >> 6;
@@ -149,130 +168,213 @@ __global__ __launch_bounds__(64 * kQeMaxWaves) void quant_error_kernel(TensorLis
   const uint16_t* x = xs.p[blockIdx.y];
   const int row0 = blockIdx.x * rows_per_block;
   const int row_end = min(rows, row0 + rows_per_block);
-  const int chunks = K / 8;
+  const int chunks8 = K / 8;               // staging granularity: one 16-byte load
+  const int chunks = K / C;
   const int wave_chunks = (chunks + 63) >> 6;
   const int n_items = n_cand * wave_chunks;
+  const int per_wave = (n_items + n_waves - 1) / n_waves;
+  const int it0 = wave * per_wave, it1 = min(n_items, it0 + per_wave);
+  const int cand0 = it0 / wave_chunks, blk0 = it0 - cand0 * wave_chunks;     // uniform over the wave
   const float T = t_arg.dev ? *t_arg.dev : t_arg.value;           // uniform
   const float encT = (FMT == kNvfp4) ? nv4_enc_scale(T) : 0.0f;
+  // The offsets are used as LDS addresses as they are: the staged rows are the kernel's only LDS object and
+  // start at address 0 (adding a base would cost one instruction per gathered channel).  Should a
+  // toolchain ever place them elsewhere, every partial sum of the launch is made a NaN.
+  typedef const __attribute__((address_space(3))) vec_t* lds_vec_ptr;
+  const bool lds_at_zero = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) float*)slots == 0u;
+
+  // rows past the end count as zero rows: error 0
+  auto fetch_row = [&](int r, int c) {
+    uint4 p = make_uint4(0u, 0u, 0u, 0u);
+    if (r < row_end) p = *reinterpret_cast<const uint4*>(x + (int64_t)r * K + (int64_t)c * 8);
+    return p;
+  };
+  auto put = [&](int c, const uint4 (&p)[R]) {
+    float v[R][8];
+#pragma unroll
+    for (int rr = 0; rr < R; ++rr) {
+      v[rr][0] = bf16_lo(p[rr].x); v[rr][1] = bf16_hi(p[rr].x); v[rr][2] = bf16_lo(p[rr].y); v[rr][3] = bf16_hi(p[rr].y);
+      v[rr][4] = bf16_lo(p[rr].z); v[rr][5] = bf16_hi(p[rr].z); v[rr][6] = bf16_lo(p[rr].w); v[rr][7] = bf16_hi(p[rr].w);
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      vec_t o;
+      if constexpr (R == 1) o = v[0][j];
+      else {
+#pragma unroll
+        for (int rr = 0; rr < R; ++rr) o[rr] = v[rr][j];
+      }
+      *reinterpret_cast<vec_t*>(slots + (size_t)(9 * c + j) * R) = o;
+    }
+  };
+  uint4 ahead[PF][R];
+  auto fetch_ahead = [&](int rg) {
+#pragma unroll
+    for (int f = 0; f < PF; ++f) {
+      const int c = tid + f * nthr;
+#pragma unroll
+      for (int rr = 0; rr < R; ++rr) ahead[f][rr] = c < chunks8 ? fetch_row(rg + rr, c) : make_uint4(0u, 0u, 0u, 0u);
+    }
+  };
+
+  // the slot offsets of the C channels of work item (cand, blk) of this lane
+  auto load_offsets = [&](int cand, int blk, int (&o)[C]) {
+    const int c_lane = blk * 64 + lane;
+    const int c = c_lane < chunks ? c_lane : 0;
+    if (!(identity_first && cand == 0)) {
+      const int4* po = reinterpret_cast<const int4*>(offs + (int64_t)(cand - identity_first) * K + c * C);
+#pragma unroll
+      for (int j = 0; j < C; j += 4) {
+        const int4 q = po[j / 4];
+        o[j] = q.x; o[j + 1] = q.y; o[j + 2] = q.z; o[j + 3] = q.w;
+      }
+    } else {
+      const int base = c * (C / 8 * 9) * qe_slot_bytes(R);
+#pragma unroll
+      for (int j = 0; j < C; ++j) o[j] = base + ((j / 8) * 9 + (j & 7)) * qe_slot_bytes(R);
+    }
+  };
+
   double acc = 0.0;
+  fetch_ahead(row0);
   for (int rg = row0; rg < row_end; rg += R) {
     __syncthreads();                       // the previous rows have been read by every wave
-    for (int c = tid; c < chunks; c += nthr) {
-      float v[R][8];
 #pragma unroll
-      for (int rr = 0; rr < R; ++rr) {
-        uint4 p = make_uint4(0u, 0u, 0u, 0u);       // rows past the end count as zero rows: error 0
-        if (rg + rr < row_end) p = *reinterpret_cast<const uint4*>(x + (int64_t)(rg + rr) * K + (int64_t)c * 8);
-        v[rr][0] = bf16_lo(p.x); v[rr][1] = bf16_hi(p.x); v[rr][2] = bf16_lo(p.y); v[rr][3] = bf16_hi(p.y);
-        v[rr][4] = bf16_lo(p.z); v[rr][5] = bf16_hi(p.z); v[rr][6] = bf16_lo(p.w); v[rr][7] = bf16_hi(p.w);
-      }
+    for (int f = 0; f < PF; ++f) {
+      const int c = tid + f * nthr;
+      if (c < chunks8) put(c, ahead[f]);
+    }
+    for (int c = tid + PF * nthr; c < chunks8; c += nthr) {     // wider rows than the registers hold ahead
+      uint4 p[R];
 #pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        vec_t o;
-        if constexpr (R == 1) o = v[0][j];
-        else {
-#pragma unroll
-          for (int rr = 0; rr < R; ++rr) o[rr] = v[rr][j];
-        }
-        *reinterpret_cast<vec_t*>(slots + (size_t)(9 * c + j) * R) = o;
-      }
+      for (int rr = 0; rr < R; ++rr) p[rr] = fetch_row(rg + rr, c);
+      put(c, p);
     }
     __syncthreads();
-    // work items (candidate, block of 64 chunks), candidate-major, dealt to the waves in turn: the
-    // number of waves is free of K, and a group (at most 32 lanes) never leaves its wave
-    for (int item = wave; item < n_items; item += n_waves) {
-      const int cand = item / wave_chunks;          // uniform over the wave
-      const int32_t* perm = nullptr;
-      if (!(identity_first && cand == 0)) perm = cands + (int64_t)(cand - identity_first) * K;
+    // Loads return in issue order, so the order below matters: the offsets of the first item go out
+    // before the rows fetched ahead (they are needed at once), those of every later item while the item
+    // before it is evaluated (at its start when four rows are resident: the registers do not hold both
+    // then, and a second workgroup of the compute unit covers the wait), by which time the rows have
+    // long arrived.
+    int cand = cand0, blk = blk0;
+    int o_ahead[kOffsetsAhead ? C : 1];
+    if constexpr (kOffsetsAhead) {
+      if (it0 < it1) load_offsets(cand, blk, o_ahead);
+    }
+    if (rg + R < row_end) fetch_ahead(rg + R);     // in flight during the evaluation below
+    double run = 0.0;                      // this lane's error of the current candidate
+    for (int it = it0; it < it1; ++it) {
+      // every lane runs the group reduction; a lane past the last chunk (its whole group is, K being a
+      // multiple of the group size) works on chunk 0 and its result is dropped
+      const bool live = blk * 64 + lane < chunks;
+      int o[C];
+      if constexpr (kOffsetsAhead) {
+#pragma unroll
+        for (int j = 0; j < C; ++j) o[j] = o_ahead[j];
+      } else {
+        load_offsets(cand, blk, o);
+      }
+      float v[R][C];
+#pragma unroll
+      for (int j = 0; j < C; ++j) {
+        const vec_t g = *(lds_vec_ptr)(uint32_t)o[j];
+        if constexpr (R == 1) v[0][j] = g;
+        else {
+#pragma unroll
+          for (int rr = 0; rr < R; ++rr) v[rr][j] = g[rr];
+        }
+      }
+      const bool cand_done = blk + 1 == wave_chunks || it + 1 == it1;     // uniform
+      if constexpr (kOffsetsAhead) {
+        if (it + 1 < it1) load_offsets(cand_done ? cand + 1 : cand, cand_done ? 0 : blk + 1, o_ahead);
+      }
       double errs[R];                               // one chain per resident row
 #pragma unroll
       for (int rr = 0; rr < R; ++rr) errs[rr] = 0.0;
-      // every lane runs the group reduction; a lane past the last chunk (its whole group is, K being a
-      // multiple of the group size) works on chunk 0 and its result is dropped
-      const int c_lane = (item - cand * wave_chunks) * 64 + lane;
-      const bool live = c_lane < chunks;
-      {
-        const int c = live ? c_lane : 0;
-        float v[R][8];
-        {
-          int slot[8];
-          if (perm) {
-            const int4* pp = reinterpret_cast<const int4*>(perm + c * 8);
-            const int4 i0 = pp[0], i1 = pp[1];
-            const int idx[8] = {i0.x, i0.y, i0.z, i0.w, i1.x, i1.y, i1.z, i1.w};
+      constexpr bool kRows4 = FMT != kNvfp4 && R == 4 && G >= 32;    // scales shared out over a quad
+      float amax[R];
 #pragma unroll
-            for (int j = 0; j < 8; ++j) slot[j] = idx[j] + (idx[j] >> 3);
-          } else {
+      for (int rr = 0; rr < R; ++rr) {
+        float a = 0.0f;
 #pragma unroll
-            for (int j = 0; j < 8; ++j) slot[j] = 9 * c + j;
-          }
-#pragma unroll
-          for (int j = 0; j < 8; ++j) {
-            const vec_t g = *reinterpret_cast<const vec_t*>(slots + (size_t)slot[j] * R);
-            if constexpr (R == 1) v[0][j] = g;
-            else {
-#pragma unroll
-              for (int rr = 0; rr < R; ++rr) v[rr][j] = g[rr];
-            }
-          }
-        }
-        constexpr bool kRows4 = FMT != kNvfp4 && R == 4 && G >= 32;    // scales shared out over a quad
-        float amax[R];
+        for (int j = 0; j < C; ++j) a = fmaxf(a, fabsf(v[rr][j]));
+        amax[rr] = kRows4 ? a : group_max<G / C>(a);
+      }
+      if constexpr (FMT == kNvfp4) {
+        Nv4Scale s[R];
+        nv4_scales<R>(amax, T, encT, s);
 #pragma unroll
         for (int rr = 0; rr < R; ++rr) {
-          float a = 0.0f;
+          const double d = (double)s[rr].value * (double)T;   // exact: 4 + 24 bits
 #pragma unroll
-          for (int j = 0; j < 8; ++j) a = fmaxf(a, fabsf(v[rr][j]));
-          amax[rr] = kRows4 ? a : group_max<G / 8>(a);
-        }
-        if constexpr (FMT == kNvfp4) {
-          Nv4Scale s[R];
-          nv4_scales<R>(amax, T, encT, s);
+          for (int j = 0; j < C; j += 8) {
+            // quantize eight elements on the conversion unit (a byte of `codes` per pair) and decode them
+            // again: q = +-E2M1 value
+            const float inv = s[rr].inv;
+            uint32_t codes = 0u;
+            codes = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(codes, v[rr][j] * inv, v[rr][j + 1] * inv, 1.0f, 0);
+            codes = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(codes, v[rr][j + 2] * inv, v[rr][j + 3] * inv, 1.0f, 1);
+            codes = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(codes, v[rr][j + 4] * inv, v[rr][j + 5] * inv, 1.0f, 2);
+            codes = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(codes, v[rr][j + 6] * inv, v[rr][j + 7] * inv, 1.0f, 3);
+            const auto q0 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(codes, 1.0f, 0);
+            const auto q1 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(codes, 1.0f, 1);
+            const auto q2 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(codes, 1.0f, 2);
+            const auto q3 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(codes, 1.0f, 3);
+            const float q[8] = {q0[0], q0[1], q1[0], q1[1], q2[0], q2[1], q3[0], q3[1]};
 #pragma unroll
-          for (int rr = 0; rr < R; ++rr) {
-            const double d = (double)s[rr].value * (double)T;   // exact: 4 + 24 bits
-#pragma unroll
-            for (int j = 0; j < 8; j += 2) {
-              // quantize two elements on the conversion unit and decode them again: q = +-E2M1 value
-              const uint32_t byte = nv4_code_pair(v[rr][j], v[rr][j + 1], s[rr].inv);
-              const auto q = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(byte, 1.0f, 0);
-              const double e0 = fma(-(double)q[0], d, (double)v[rr][j]);      // product exact: 2 + 28 bits
-              const double e1 = fma(-(double)q[1], d, (double)v[rr][j + 1]);
-              errs[rr] = fma(e0, e0, errs[rr]);
-              errs[rr] = fma(e1, e1, errs[rr]);
-            }
-          }
-        } else {
-          IntScale s[R];
-          if constexpr (kRows4) int_scales_rows4<FMT, G / 8>(amax, lane, s);
-          else int_scales<FMT, R>(amax, s);
-#pragma unroll
-          for (int rr = 0; rr < R; ++rr) {
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-              // The clip of the quantizer cannot act here: amax is the true maximum of the group, so
-              // |x * inv| <= Q (1 + 3 * 2^-24) < Q + 1/2 and the rounding already lands on +-Q
-              // (inv = 0 gives 0).  v_rndne_f32 rounds to the nearest integer, ties to even.
-              const float t = __builtin_rintf(v[rr][j] * s[rr].inv);
-              // v - s t is exact in binary32: for t != 0 both terms are multiples of the last place
-              // of s and the difference is at most about s / 2, so it needs no more than 24 bits;
-              // the fused multiply-add returns it unrounded
-              const float e32 = __builtin_fmaf(-s[rr].s, t, v[rr][j]);
-              const double e = (double)e32;
+            for (int u = 0; u < 8; ++u) {
+              const double e = fma(-(double)q[u], d, (double)v[rr][j + u]);      // product exact: 2 + 28 bits
               errs[rr] = fma(e, e, errs[rr]);
             }
+          }
+        }
+      } else {
+        IntScale s[R];
+        if constexpr (kRows4) int_scales_rows4<FMT, G / C>(amax, lane, s);
+        else int_scales<FMT, R>(amax, s);
+#pragma unroll
+        for (int rr = 0; rr < R; ++rr) {
+#pragma unroll
+          for (int j = 0; j < C; ++j) {
+            // The clip of the quantizer cannot act here: amax is the true maximum of the group, so
+            // |x * inv| <= Q (1 + 3 * 2^-24) < Q + 1/2 and the rounding already lands on +-Q
+            // (inv = 0 gives 0).  v_rndne_f32 rounds to the nearest integer, ties to even.
+            const float t = __builtin_rintf(v[rr][j] * s[rr].inv);
+            // v - s t is exact in binary32: for t != 0 both terms are multiples of the last place
+            // of s and the difference is at most about s / 2, so it needs no more than 24 bits;
+            // the fused multiply-add returns it unrounded
+            const float e32 = __builtin_fmaf(-s[rr].s, t, v[rr][j]);
+            const double e = (double)e32;
+            errs[rr] = fma(e, e, errs[rr]);
           }
         }
       }
       double err = errs[0];
 #pragma unroll
       for (int rr = 1; rr < R; ++rr) err += errs[rr];
-      err = wave_sum(live ? err : 0.0);    // fixed xor-tree order
-      if (lane == cand) acc += err;
+      run += live ? err : 0.0;
+      ++blk;
+      if (cand_done) {                               // the candidate's last item of this wave
+        const double total = wave_sum(run);          // fixed xor-tree order
+        if (lane == cand) acc += total;
+        run = 0.0;
+        blk = 0;
+        ++cand;
+      }
     }
   }
+  if (!lds_at_zero) acc = __builtin_nan("");
   if (lane < n_cand)
     part[((int64_t)blockIdx.y * n_cand + lane) * ((int64_t)gridDim.x * n_waves) + (int64_t)blockIdx.x * n_waves + wave] = acc;
+}
+
+// offs[i] = byte offset of channel perm[i]'s slot for R resident rows (the error evaluation of one given order)
+__global__ __launch_bounds__(256) void perm_to_offsets_kernel(const int32_t* __restrict__ perm, int K, int slot_bytes,
+                                                              int32_t* __restrict__ offs) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= K) return;
+  const int e = perm[i];
+  offs[i] = (e + (e >> 3)) * slot_bytes;
 }
 
 // out[seg][c] = sum over the rows of segment seg of row_err[r][c]; one workgroup per
@@ -380,32 +482,44 @@ struct QeShape {
   int parts() const { return blocks * (threads / 64); }    // partial sums per tensor and candidate
 };
 
-static QeShape qe_shape(int64_t rows, int64_t K, int n_tensors, int n_cand) {
+static QeShape qe_shape(pq_format fmt, int64_t rows, int64_t K, int n_tensors, int n_cand) {
   QeShape q;
+  const bool nv = fmt == PQ_FMT_NVFP4;
+  const int chunk = nv ? QeChunk<kNvfp4>::value : QeChunk<kInt4>::value;
   const size_t slot_floats = (size_t)(K + K / 8);
   q.r = slot_floats * 16 <= 64 * 1024 ? 4 : slot_floats * 8 <= 128 * 1024 ? 2 : 1;
   q.shmem = slot_floats * q.r * sizeof(float);
-  // waves: the work items of a set of resident rows (candidate x block of 64 chunks) are dealt to the
-  // waves in turn; take the fewest waves that need the fewest turns.  Two workgroups share a compute
-  // unit when their rows fit its LDS twice (one stages while the other computes): twelve waves each
-  // then, sixteen otherwise.
-  const int items = n_cand * (int)((K / 8 + 63) / 64);
-  const int max_waves = 2 * q.shmem <= 160 * 1024 ? 12 : kQeMaxWaves;
+  // waves: the work items of a set of resident rows (candidate x block of 64 chunks) are shared out
+  // evenly; take the fewest waves that need the fewest turns.  Two workgroups share a compute unit when
+  // their rows fit its LDS twice (one stages while the other computes): half of the waves the unit's
+  // registers hold each then (the NVFP4 instances need up to 128 registers a lane: sixteen waves a unit;
+  // the integer ones up to 96: twenty), sixteen otherwise.
+  const int items = n_cand * (int)((K / chunk + 63) / 64);
+  const int max_waves = 2 * q.shmem <= 160 * 1024 ? (nv ? 8 : 10) : kQeMaxWaves;
   const int turns = (items + max_waves - 1) / max_waves;
   q.threads = 64 * ((items + turns - 1) / turns);
-  // enough workgroups to fill the chip several times over, at least kQeMinRowsPerBlock rows each
-  int64_t rpb = rows * n_tensors / 2048;
-  rpb = rpb / q.r * q.r;
-  if (rpb < kQeMinRowsPerBlock) rpb = kQeMinRowsPerBlock;
-  if (rpb > 64) rpb = 64;
-  q.rows_per_block = (int)rpb;
-  q.blocks = (int)((rows + rpb - 1) / rpb);
+  // Rows per workgroup: the workgroups run in rounds of as many as the chip holds at once (256 compute
+  // units, one or two each), every round lasts about as long as a workgroup's rows plus a fixed start-up
+  // (taken as half a row); among kQeMinRowsPerBlock .. 64 rows take the smallest size whose total is
+  // within 2 % of the shortest (smaller workgroups even out better when their times differ).
+  const int64_t resident = (2 * q.shmem <= 160 * 1024 ? 2 : 1) * 256;
+  const int64_t lo = (kQeMinRowsPerBlock + q.r - 1) / q.r * q.r;
+  auto cost_of = [&](int64_t rpb) {
+    const int64_t wgs = (rows + rpb - 1) / rpb * n_tensors;
+    return (double)((wgs + resident - 1) / resident) * ((double)rpb + 0.5);
+  };
+  double best_cost = cost_of(lo);
+  for (int64_t rpb = lo; rpb <= 64; rpb += q.r) best_cost = cost_of(rpb) < best_cost ? cost_of(rpb) : best_cost;
+  int64_t best_rpb = lo;
+  while (cost_of(best_rpb) > 1.02 * best_cost) best_rpb += q.r;
+  q.rows_per_block = (int)best_rpb;
+  q.blocks = (int)((rows + best_rpb - 1) / best_rpb);
   return q;
 }
 
 template <int FMT, int G, int R>
 static int launch_qe_r(const TensorList& xs, int n_tensors, int64_t rows, int K, const QeShape& q,
-                       const int32_t* cands, int n_cand, int identity_first, ScaleArg T, double* part,
+                       const int32_t* offs, int n_cand, int identity_first, ScaleArg T, double* part,
                        hipStream_t st) {
   auto kern = quant_error_kernel<FMT, G, R>;
   // the attribute is per kernel instance and device; it is raised once per instance to the most any
@@ -420,36 +534,36 @@ static int launch_qe_r(const TensorList& xs, int n_tensors, int64_t rows, int K,
     if (dev >= 0 && dev < kMaxDevicesSeen) raised[dev].store(true, std::memory_order_release);
   }
   hipLaunchKernelGGL(kern, dim3((unsigned)q.blocks, (unsigned)n_tensors), dim3(q.threads), q.shmem, st, xs,
-                     (int)rows, K, cands, n_cand, identity_first, T, q.rows_per_block, part);
+                     (int)rows, K, offs, n_cand, identity_first, T, q.rows_per_block, part);
   return check_hip(hipGetLastError(), "quant_error_kernel");
 }
 
 template <int FMT, int G>
 static int launch_qe(const TensorList& xs, int n_tensors, int64_t rows, int K, const QeShape& q,
-                     const int32_t* cands, int n_cand, int identity_first, ScaleArg T, double* part,
+                     const int32_t* offs, int n_cand, int identity_first, ScaleArg T, double* part,
                      hipStream_t st) {
   switch (q.r) {
-    case 4: return launch_qe_r<FMT, G, 4>(xs, n_tensors, rows, K, q, cands, n_cand, identity_first, T, part, st);
-    case 2: return launch_qe_r<FMT, G, 2>(xs, n_tensors, rows, K, q, cands, n_cand, identity_first, T, part, st);
-    default: return launch_qe_r<FMT, G, 1>(xs, n_tensors, rows, K, q, cands, n_cand, identity_first, T, part, st);
+    case 4: return launch_qe_r<FMT, G, 4>(xs, n_tensors, rows, K, q, offs, n_cand, identity_first, T, part, st);
+    case 2: return launch_qe_r<FMT, G, 2>(xs, n_tensors, rows, K, q, offs, n_cand, identity_first, T, part, st);
+    default: return launch_qe_r<FMT, G, 1>(xs, n_tensors, rows, K, q, offs, n_cand, identity_first, T, part, st);
   }
 }
 
-// part: [n_tensors][n_cand][q.parts()]
+// part: [n_tensors][n_cand][q.parts()]; offs: the candidate orders as slot offsets for q.r resident rows
 static int launch_quant_error(pq_format fmt, int group, const TensorList& x, int n_tensors, int64_t rows,
-                              int K, const QeShape& q, const int32_t* cands, int n_cand,
+                              int K, const QeShape& q, const int32_t* offs, int n_cand,
                               int identity_first, ScaleArg T, double* part, hipStream_t st) {
   if (rows > 0x7FFFFFFF) return fail(PQ_ERR_SHAPE, "too many rows");
   if (q.shmem > 150 * 1024) return fail(PQ_ERR_SHAPE, "K=%d too large for the LDS-resident row", K);   // the entry points refuse this earlier
   if (fmt == PQ_FMT_NVFP4)
-    return launch_qe<kNvfp4, 16>(x, n_tensors, rows, K, q, cands, n_cand, identity_first, T, part, st);
+    return launch_qe<kNvfp4, 16>(x, n_tensors, rows, K, q, offs, n_cand, identity_first, T, part, st);
 #define PQ_INT_CASE(F, FE)                                                                                  \
   if (fmt == F) {                                                                                           \
     switch (group) {                                                                                        \
-      case 32: return launch_qe<FE, 32>(x, n_tensors, rows, K, q, cands, n_cand, identity_first, T, part, st);   \
-      case 64: return launch_qe<FE, 64>(x, n_tensors, rows, K, q, cands, n_cand, identity_first, T, part, st);   \
-      case 128: return launch_qe<FE, 128>(x, n_tensors, rows, K, q, cands, n_cand, identity_first, T, part, st); \
-      case 256: return launch_qe<FE, 256>(x, n_tensors, rows, K, q, cands, n_cand, identity_first, T, part, st); \
+      case 32: return launch_qe<FE, 32>(x, n_tensors, rows, K, q, offs, n_cand, identity_first, T, part, st);   \
+      case 64: return launch_qe<FE, 64>(x, n_tensors, rows, K, q, offs, n_cand, identity_first, T, part, st);   \
+      case 128: return launch_qe<FE, 128>(x, n_tensors, rows, K, q, offs, n_cand, identity_first, T, part, st); \
+      case 256: return launch_qe<FE, 256>(x, n_tensors, rows, K, q, offs, n_cand, identity_first, T, part, st); \
     }                                                                                                       \
   }
   PQ_INT_CASE(PQ_FMT_INT4, kInt4)
@@ -463,6 +577,7 @@ struct SelectWs {
   double* keys;      // [PQ_MAX_ALPHAS][K]
   int32_t* cands;    // [PQ_MAX_ALPHAS][K]
   int32_t* rank;     // [PQ_MAX_ALPHAS][K] position of every channel in the sorted order
+  int32_t* offs;     // [PQ_MAX_ALPHAS][K] the candidates as LDS slot offsets of the error evaluation
   double* row_err;   // partial error sums: [n_batches][n_cand][parts(M)], then [n_cand][parts(N)]
   double* sums;      // [(n_batches + 1) * kMaxCand + 2 + PQ_MAX_ALPHAS]: per-batch errors, weight
                      // errors, |X|^2, |W|^2, moved-channel counts
@@ -480,6 +595,7 @@ static size_t carve_select(void* base, int64_t M, int64_t N, int64_t K, int n_ba
   size_t o_keys = take((size_t)PQ_MAX_ALPHAS * K * 8);
   size_t o_cands = take((size_t)PQ_MAX_ALPHAS * K * 4);
   size_t o_rank = take((size_t)PQ_MAX_ALPHAS * K * 4);
+  size_t o_offs = take((size_t)PQ_MAX_ALPHAS * K * 4);
   // a workgroup covers at least kQeMinRowsPerBlock rows with at most kQeMaxWaves waves: no more
   // partial sums than kQeParts(rows) per tensor
   size_t o_rowerr = take((size_t)((int64_t)n_batches * kQeParts(M) + kQeParts(N)) * kMaxCand * 8);
@@ -489,6 +605,7 @@ static size_t carve_select(void* base, int64_t M, int64_t N, int64_t K, int n_ba
     w->keys = (double*)(b + o_keys);
     w->cands = (int32_t*)(b + o_cands);
     w->rank = (int32_t*)(b + o_rank);
+    w->offs = (int32_t*)(b + o_offs);
     w->row_err = (double*)(b + o_rowerr);
     w->sums = (double*)(b + o_sums);
   }
@@ -499,15 +616,24 @@ size_t select_workspace_bytes(int64_t M, int64_t N, int64_t K, int n_batches) {
   return carve_select(nullptr, M, N, K, n_batches, nullptr);
 }
 
-size_t quant_error_workspace_bytes(int64_t rows) { return align_up((size_t)kQeParts(rows) * 8, 256); }
+// partial sums, then the given order as slot offsets
+size_t quant_error_workspace_bytes(int64_t rows, int64_t K) {
+  return align_up((size_t)kQeParts(rows) * 8, 256) + align_up((size_t)K * 4, 256);
+}
 
 int run_quant_error(pq_format fmt, int group, const void* x, int64_t rows, int64_t K,
                     const int32_t* perm, float ts, double* err_out, void* ws, hipStream_t st) {
   double* part = (double*)ws;
   TensorList tl;
   for (int b = 0; b < kMaxMomentBatches; ++b) tl.p[b] = (const uint16_t*)x;
-  const QeShape q = qe_shape(rows, K, 1, 1);
-  int rc = launch_quant_error(fmt, group, tl, 1, rows, (int)K, q, perm, 1, perm ? 0 : 1, ScaleArg{ts, nullptr}, part, st);
+  const QeShape q = qe_shape(fmt, rows, K, 1, 1);
+  int32_t* offs = nullptr;
+  if (perm) {
+    offs = (int32_t*)((char*)ws + align_up((size_t)kQeParts(rows) * 8, 256));
+    hipLaunchKernelGGL(perm_to_offsets_kernel, dim3((unsigned)((K + 255) / 256)), dim3(256), 0, st, perm, (int)K,
+                       qe_slot_bytes(q.r), offs);
+  }
+  int rc = launch_quant_error(fmt, group, tl, 1, rows, (int)K, q, offs, 1, perm ? 0 : 1, ScaleArg{ts, nullptr}, part, st);
   if (rc) return rc;
   hipLaunchKernelGGL(reduce_rows_kernel, dim3(1, 1), dim3(256), 0, st, part, (int64_t)q.parts(), 1, 1, err_out);
   return check_hip(hipGetLastError(), "reduce_rows_kernel");
@@ -515,15 +641,18 @@ int run_quant_error(pq_format fmt, int group, const void* x, int64_t rows, int64
 
 // The candidate orders of the alpha grid (joint score, descending stable sort) into
 // cands[n_alpha][K]; keys [PQ_MAX_ALPHAS][K] doubles and rank [PQ_MAX_ALPHAS][K] ints are scratch.
+// With offs ([n_alpha][K]), the same orders are also written as slot offsets of slot_bytes a slot.
 int launch_candidate_orders(const double* act_sumsq, const double* w_sumsq, int64_t K, const double* alphas,
-                            int n_alpha, double* keys, int32_t* rank, int32_t* cands, hipStream_t st) {
+                            int n_alpha, double* keys, int32_t* rank, int32_t* cands, hipStream_t st,
+                            int32_t* offs, int slot_bytes) {
   const unsigned kb = (unsigned)((K + 255) / 256);
   const int chunks = rank_chunks(K);
   AlphaList al;
   for (int j = 0; j < PQ_MAX_ALPHAS; ++j) al.a[j] = j < n_alpha ? alphas[j] : 0.0;
   hipLaunchKernelGGL(key_kernel, dim3(kb, n_alpha), dim3(256), 0, st, act_sumsq, w_sumsq, K, al, keys, rank);
   hipLaunchKernelGGL(rank_count_kernel, dim3(kb, chunks, n_alpha), dim3(256), 0, st, keys, (int)K, rank);
-  hipLaunchKernelGGL(rank_scatter_kernel, dim3(kb, n_alpha), dim3(256), 0, st, rank, (int)K, cands);
+  hipLaunchKernelGGL(rank_scatter_kernel, dim3(kb, n_alpha), dim3(256), 0, st, rank, (int)K, cands, offs,
+                     slot_bytes);
   return check_hip(hipGetLastError(), "key/rank kernels");
 }
 
@@ -564,7 +693,8 @@ int launch_random_order(uint64_t seed, int64_t K, int32_t* perm, void* ws, hipSt
   const unsigned kb = (unsigned)((K + 255) / 256);
   hipLaunchKernelGGL(random_key_kernel, dim3(kb), dim3(256), 0, st, seed, (int)K, keys, rank);
   hipLaunchKernelGGL(rank_count_kernel, dim3(kb, rank_chunks(K), 1), dim3(256), 0, st, keys, (int)K, rank);
-  hipLaunchKernelGGL(rank_scatter_kernel, dim3(kb, 1), dim3(256), 0, st, rank, (int)K, perm);
+  hipLaunchKernelGGL(rank_scatter_kernel, dim3(kb, 1), dim3(256), 0, st, rank, (int)K, perm,
+                     (int32_t*)nullptr, 0);
   return check_hip(hipGetLastError(), "random order kernels");
 }
 
@@ -609,23 +739,25 @@ int run_select(pq_format fmt, int group, const double* act_sumsq, const double* 
   carve_select(ws, M, N, K, n_batches, &W);
   const int n_cand = n_alpha + 1;            // candidate 0 is the original order
   int rc;
-  if ((rc = launch_candidate_orders(act_sumsq, w_sumsq, K, alphas, n_alpha, W.keys, W.rank, W.cands, st))) return rc;
-  double* sums = W.sums;
   // activations: all batches of a launch share one grid (up to kMaxMomentBatches per launch)
-  const QeShape qa = qe_shape(M, K, n_batches < kMaxMomentBatches ? n_batches : kMaxMomentBatches, n_cand);
+  const QeShape qa = qe_shape(fmt, M, K, n_batches < kMaxMomentBatches ? n_batches : kMaxMomentBatches, n_cand);
+  const QeShape qw = qe_shape(fmt, N, K, 1, n_cand);       // the same resident rows (a function of K): one set of offsets
+  if ((rc = launch_candidate_orders(act_sumsq, w_sumsq, K, alphas, n_alpha, W.keys, W.rank, W.cands, st, W.offs,
+                                    qe_slot_bytes(qa.r))))
+    return rc;
+  double* sums = W.sums;
   for (int b0 = 0; b0 < n_batches; b0 += kMaxMomentBatches) {
     const int nb = n_batches - b0 < kMaxMomentBatches ? n_batches - b0 : kMaxMomentBatches;
     TensorList tl;
     for (int b = 0; b < kMaxMomentBatches; ++b) tl.p[b] = (const uint16_t*)x_calib[b0 + (b < nb ? b : 0)];
-    rc = launch_quant_error(fmt, group, tl, nb, M, (int)K, qa, W.cands, n_cand, 1, ScaleArg{act_ts, act_ts_dev},
+    rc = launch_quant_error(fmt, group, tl, nb, M, (int)K, qa, W.offs, n_cand, 1, ScaleArg{act_ts, act_ts_dev},
                             W.row_err + (size_t)b0 * qa.parts() * n_cand, st);
     if (rc) return rc;
   }
   double* w_part = W.row_err + (size_t)n_batches * qa.parts() * n_cand;
-  const QeShape qw = qe_shape(N, K, 1, n_cand);
   TensorList wl;
   for (int b = 0; b < kMaxMomentBatches; ++b) wl.p[b] = (const uint16_t*)w;
-  rc = launch_quant_error(fmt, group, wl, 1, N, (int)K, qw, W.cands, n_cand, 1, ScaleArg{w_ts, w_ts_dev}, w_part, st);
+  rc = launch_quant_error(fmt, group, wl, 1, N, (int)K, qw, W.offs, n_cand, 1, ScaleArg{w_ts, w_ts_dev}, w_part, st);
   if (rc) return rc;
   TailArgs ta{W.row_err, w_part, act_sumsq, w_sumsq, W.cands, qa.parts(), qw.parts(), K, n_cand, n_batches, n_alpha};
   hipLaunchKernelGGL(select_tail_kernel, dim3((unsigned)(n_cand * (n_batches + 1) + 2 + n_alpha)), dim3(256), 0,
