@@ -168,10 +168,69 @@ __device__ __forceinline__ void paley_pass(float* slab, int n_fibres, int lane) 
   team_sync<TEAM>();
 }
 
-// `lane` is the thread's index inside its team (0 .. 64 TEAM - 1)
+// The Paley pass of order 12 on the matrix unit, straight from the bf16 row in memory into the fp32 slab:
+// sixteen fibres (16 x 12 contiguous values) times P_12 padded to 16 x 16 is one v_mfma_f32_16x16x16_bf16.
+// Inputs and the +-1 entries are exact in bf16 and the products are accumulated in fp32, as on the
+// vector unit.  Operand layout of the instruction: lane l holds A[l % 16][4 (l / 16) + i] (a fibre's
+// values 4j .. 4j + 3: eight contiguous bytes), B[4 (l / 16) + i][l % 16] and D[4 (l / 16) + i][l % 16].
+// negative entries of rows 4j .. 4j + 3 of P_12: bit 16 i + n for entry (4j + i, n)
+constexpr uint64_t paley12_negatives(int j) {
+  uint64_t mask = 0;
+  for (int i = 0; i < 4; ++i)
+    for (int n = 0; n < 12; ++n)
+      if (paley_entry<12>(4 * j + i, n) < 0) mask |= (uint64_t)1 << (16 * i + n);
+  return mask;
+}
 template <int TEAM>
-__device__ __forceinline__ void hadamard_row(float* slab, int K, int pow2, int m, int lane) {
-  if (m == 12) paley_pass<12, TEAM>(slab, pow2, lane);
+__device__ __forceinline__ void paley12_pass_from_memory(const uint16_t* __restrict__ xr, float* slab, int n_fibres,
+                                                         int tl) {
+  typedef short bf16x4_bits __attribute__((ext_vector_type(4)));
+  typedef float f32x4 __attribute__((ext_vector_type(4)));
+  const int lane = tl & 63, wv = tl >> 6;
+  const int n = lane & 15, j = lane >> 4;
+  constexpr uint64_t kNeg0 = paley12_negatives(0), kNeg1 = paley12_negatives(1), kNeg2 = paley12_negatives(2);
+  const uint64_t neg = j == 0 ? kNeg0 : j == 1 ? kNeg1 : kNeg2;
+  const bool in_matrix = j < 3 && n < 12;                    // the padding rows and columns are zero
+  uint32_t bw[2];
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const uint32_t e0 = ((neg >> (32 * h + n)) & 1) ? 0xBF80u : 0x3F80u;
+    const uint32_t e1 = ((neg >> (32 * h + 16 + n)) & 1) ? 0xBF80u : 0x3F80u;
+    bw[h] = in_matrix ? (e0 | (e1 << 16)) : 0u;
+  }
+  const bf16x4_bits b = __builtin_bit_cast(bf16x4_bits, make_uint2(bw[0], bw[1]));
+  const int groups = n_fibres / 16;
+  constexpr int kInFlight = 8;
+  for (int g0 = wv; g0 < groups; g0 += TEAM * kInFlight) {
+    uint2 a[kInFlight];
+#pragma unroll
+    for (int t = 0; t < kInFlight; ++t) {
+      const int g = g0 + t * TEAM;
+      a[t] = make_uint2(0u, 0u);
+      if (g < groups && j < 3) a[t] = *reinterpret_cast<const uint2*>(xr + (size_t)(g * 16 + n) * 12 + 4 * j);
+    }
+#pragma unroll
+    for (int t = 0; t < kInFlight; ++t) {
+      const int g = g0 + t * TEAM;
+      if (g >= groups) break;                                // wave-uniform
+      const f32x4 d = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(bf16x4_bits, a[t]), b,
+                                                                (f32x4){0.0f, 0.0f, 0.0f, 0.0f}, 0, 0, 0);
+      if (n < 12) {
+        float* out = slab + (size_t)(g * 16 + 4 * j) * 12 + n;
+        out[0] = d[0];
+        out[12] = d[1];
+        out[24] = d[2];
+        out[36] = d[3];
+      }
+    }
+  }
+  team_sync<TEAM>();
+}
+
+// `lane` is the thread's index inside its team (0 .. 64 TEAM - 1); paley_done: the Paley pass has been applied
+template <int TEAM>
+__device__ __forceinline__ void hadamard_row(float* slab, int K, int pow2, int m, int lane, bool paley_done = false) {
+  if (m == 12 && !paley_done) paley_pass<12, TEAM>(slab, pow2, lane);
   if (m == 20) paley_pass<20, TEAM>(slab, pow2, lane);
   int inner = m;                       // weight of the current Sylvester digit, in elements
   int rem = pow2;
@@ -353,7 +412,9 @@ __global__ __launch_bounds__(64 * kNormMaxWaves) void norm_rows_kernel(
   if constexpr (NORM == kHadamard) {
     // ---- 1. the row as fp32 in the wave's slab, transformed in place
     constexpr int kInFlight = 8;
-    for (int c0 = 0; c0 < k_chunks; c0 += kInFlight * TL) {
+    const bool paley_on_mfma = na.had_m == 12 && na.had_pow2 >= 16;      // uniform
+    if (paley_on_mfma) paley12_pass_from_memory<TEAM>(xr, slab_f, na.had_pow2, tl);
+    for (int c0 = 0; c0 < (paley_on_mfma ? 0 : k_chunks); c0 += kInFlight * TL) {
       uint4 lines[kInFlight];
 #pragma unroll
       for (int t = 0; t < kInFlight; ++t) {
@@ -371,7 +432,7 @@ __global__ __launch_bounds__(64 * kNormMaxWaves) void norm_rows_kernel(
       }
     }
     team_sync<TEAM>();
-    hadamard_row<TEAM>(slab_f, Ki, na.had_pow2, na.had_m, tl);
+    hadamard_row<TEAM>(slab_f, Ki, na.had_pow2, na.had_m, tl, paley_on_mfma);
     rstd = na.had_scale;
   } else {
   // ---- 1. the row: statistics, and a copy in the wave's slab
