@@ -12,8 +12,9 @@
 //   quant_error_kernel a workgroup stages a few rows in LDS at a time; for every candidate order
 //                     their channels are gathered from LDS (one read serves all resident rows),
 //                     quantized with the same lane-cooperative quantizer as the runtime kernels,
-//                     dequantized, and the squared error accumulated in fp64.  HBM traffic is one
-//                     read of the tensor for all candidates.
+//                     and the squared error of the dequantized values accumulated in fp64 (NVFP4:
+//                     from exact fp32 group sums).  HBM traffic is one read of the tensor for all
+//                     candidates.
 //   select_tail_kernel fixed-order sums of the per-wave partial errors, of the moments and of the
 //                     moved-channel counts (deterministic), one launch.
 // The final argmin / acceptance decision is a handful of scalar operations and runs on the host.
@@ -145,8 +146,12 @@ __host__ __device__ constexpr int qe_slot_bytes(int r) { return r * 4; }
 // their way from memory into registers while the resident ones are evaluated.  A candidate order
 // comes as the byte offsets of its channels' slots (offs[cand][position]), so a lane reads the
 // offsets of its chunk and gathers the R rows of each channel with one LDS read, no address
-// arithmetic; the quantizer is the lane-cooperative one of the runtime kernels; squared errors are
-// accumulated in fp64 (every product below is exact in fp64).  Every wave owns a fixed run of work
+// arithmetic; the quantizer is the lane-cooperative one of the runtime kernels.  Integer formats: the
+// error v - s t of an element is exact in fp32 and its square is accumulated in fp64.  NVFP4: the squared
+// error of a group is sum v^2 - 2 d A + d^2 B (A = sum v q, B = sum q^2, d the group's scale): A and B are
+// exact fp32 sums, the rest is fp64, and sum v^2 -- the same for every order -- is taken once when the rows
+// are staged; the difference loses the bits by which sum v^2 exceeds the error (two decimal digits of
+// fp64's sixteen for data that fill the format; an absolute 1e-15 of sum v^2 at worst).  Every wave owns a fixed run of work
 // items (candidate, block of 64 chunks), candidate-major, sums a candidate's errors per lane and
 // reduces them over the wave once per candidate and set of resident rows.  Lane c of every wave
 // ends up with the wave's total for candidate c: part[y][c][x * waves + wave] (candidate-major, so
@@ -189,12 +194,17 @@ __global__ __launch_bounds__(64 * kQeMaxWaves) void quant_error_kernel(TensorLis
     if (r < row_end) p = *reinterpret_cast<const uint4*>(x + (int64_t)r * K + (int64_t)c * 8);
     return p;
   };
+  double v_sq = 0.0;                       // NVFP4: this thread's share of the sum of squares of the rows
   auto put = [&](int c, const uint4 (&p)[R]) {
     float v[R][8];
 #pragma unroll
     for (int rr = 0; rr < R; ++rr) {
       v[rr][0] = bf16_lo(p[rr].x); v[rr][1] = bf16_hi(p[rr].x); v[rr][2] = bf16_lo(p[rr].y); v[rr][3] = bf16_hi(p[rr].y);
       v[rr][4] = bf16_lo(p[rr].z); v[rr][5] = bf16_hi(p[rr].z); v[rr][6] = bf16_lo(p[rr].w); v[rr][7] = bf16_hi(p[rr].w);
+      if constexpr (FMT == kNvfp4) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v_sq = fma((double)v[rr][j], (double)v[rr][j], v_sq);
+      }
     }
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
@@ -301,30 +311,67 @@ __global__ __launch_bounds__(64 * kQeMaxWaves) void quant_error_kernel(TensorLis
         amax[rr] = kRows4 ? a : group_max<G / C>(a);
       }
       if constexpr (FMT == kNvfp4) {
+        // A group's error is sum (v - q d)^2 = sum v^2 - 2 d A + d^2 B with A = sum v q and B = sum q^2
+        // (q = +-E2M1 value, d = block scale x tensor scale).  sum v^2 does not depend on the order: it is
+        // added once per row (v_sq below); the lane accumulates A and B in fp32, which is exact: an element
+        // with q != 0 has |v| > d / 4, so every product v q is a multiple of U > d 2^-11 (bf16 v, q a
+        // multiple of 1/2), and |A| <= 16 * 6 * amax < 2^24 U as long as amax <= 48 d -- true unless the block
+        // scale saturated far beyond its largest value (a tensor scale much too small for the data: the
+        // wave then takes the element-wise fp64 sum instead).  B <= 16 * 36 in steps of 1/4.
         Nv4Scale s[R];
         nv4_scales<R>(amax, T, encT, s);
+        bool far_saturated = false;
 #pragma unroll
-        for (int rr = 0; rr < R; ++rr) {
-          const double d = (double)s[rr].value * (double)T;   // exact: 4 + 24 bits
+        for (int rr = 0; rr < R; ++rr) far_saturated = far_saturated || amax[rr] * encT > 6.0f * 448.0f * 7.0f;
+        const bool exact_sums = !__any(far_saturated);          // uniform
+        // eight elements on the conversion unit (a byte of `codes` per pair), decoded again
+        auto quantize8 = [&](const float* x, float inv, float (&q)[8]) {
+          uint32_t codes = 0u;
+          codes = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(codes, x[0] * inv, x[1] * inv, 1.0f, 0);
+          codes = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(codes, x[2] * inv, x[3] * inv, 1.0f, 1);
+          codes = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(codes, x[4] * inv, x[5] * inv, 1.0f, 2);
+          codes = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(codes, x[6] * inv, x[7] * inv, 1.0f, 3);
+          const auto q0 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(codes, 1.0f, 0);
+          const auto q1 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(codes, 1.0f, 1);
+          const auto q2 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(codes, 1.0f, 2);
+          const auto q3 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(codes, 1.0f, 3);
+          q[0] = q0[0]; q[1] = q0[1]; q[2] = q1[0]; q[3] = q1[1];
+          q[4] = q2[0]; q[5] = q2[1]; q[6] = q3[0]; q[7] = q3[1];
+        };
+        if (__builtin_expect(exact_sums, 1)) {
 #pragma unroll
-          for (int j = 0; j < C; j += 8) {
-            // quantize eight elements on the conversion unit (a byte of `codes` per pair) and decode them
-            // again: q = +-E2M1 value
-            const float inv = s[rr].inv;
-            uint32_t codes = 0u;
-            codes = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(codes, v[rr][j] * inv, v[rr][j + 1] * inv, 1.0f, 0);
-            codes = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(codes, v[rr][j + 2] * inv, v[rr][j + 3] * inv, 1.0f, 1);
-            codes = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(codes, v[rr][j + 4] * inv, v[rr][j + 5] * inv, 1.0f, 2);
-            codes = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(codes, v[rr][j + 6] * inv, v[rr][j + 7] * inv, 1.0f, 3);
-            const auto q0 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(codes, 1.0f, 0);
-            const auto q1 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(codes, 1.0f, 1);
-            const auto q2 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(codes, 1.0f, 2);
-            const auto q3 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(codes, 1.0f, 3);
-            const float q[8] = {q0[0], q0[1], q1[0], q1[1], q2[0], q2[1], q3[0], q3[1]};
+          for (int rr = 0; rr < R; ++rr) {
+            float A = 0.0f, B = 0.0f;
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
-              const double e = fma(-(double)q[u], d, (double)v[rr][j + u]);      // product exact: 2 + 28 bits
-              errs[rr] = fma(e, e, errs[rr]);
+            for (int j = 0; j < C; j += 8) {
+              float q[8];
+              quantize8(&v[rr][j], s[rr].inv, q);
+#pragma unroll
+              for (int u = 0; u < 8; ++u) {
+                A = __builtin_fmaf(v[rr][j + u], q[u], A);
+                B = __builtin_fmaf(q[u], q[u], B);
+              }
+            }
+            // - 2 d A + d^2 B = d (d B - 2 A): d (4 + 24 bits) is exact, so are d B (+ 10 bits) and the
+            // difference; one rounding in the last product
+            const double d = (double)s[rr].value * (double)T;
+            errs[rr] = d * fma(d, (double)B, -2.0 * (double)A);
+          }
+        } else {
+#pragma unroll
+          for (int rr = 0; rr < R; ++rr) {
+            const double d = (double)s[rr].value * (double)T;
+#pragma unroll
+            for (int j = 0; j < C; j += 8) {
+              float q[8];
+              quantize8(&v[rr][j], s[rr].inv, q);
+#pragma unroll
+              for (int u = 0; u < 8; ++u) {
+                const double x = (double)v[rr][j + u];
+                const double e = fma(-(double)q[u], d, x);      // product exact: 2 + 28 bits
+                errs[rr] = fma(e, e, errs[rr]);
+                errs[rr] = fma(-x, x, errs[rr]);                // the part counted by v_sq
+              }
             }
           }
         }
@@ -363,6 +410,11 @@ __global__ __launch_bounds__(64 * kQeMaxWaves) void quant_error_kernel(TensorLis
       }
     }
   }
+  if constexpr (FMT == kNvfp4) {
+    // every candidate's error contains the rows' sum of squares: the wave's share goes to each
+    const double share = wave_sum(v_sq);
+    if (lane < n_cand) acc += share;
+  }
   if (!lds_at_zero) acc = __builtin_nan("");
   if (lane < n_cand)
     part[((int64_t)blockIdx.y * n_cand + lane) * ((int64_t)gridDim.x * n_waves) + (int64_t)blockIdx.x * n_waves + wave] = acc;
@@ -378,10 +430,12 @@ __global__ __launch_bounds__(256) void perm_to_offsets_kernel(const int32_t* __r
 }
 
 // out[seg][c] = sum over the rows of segment seg of row_err[r][c]; one workgroup per
-// (candidate, segment), fixed order.  Segments are consecutive runs of seg_rows rows.
+// (candidate, segment), fixed order.  Segments are consecutive runs of seg_rows rows.  not_below_zero: a
+// sum that comes out negative (NVFP4's error of data the format holds exactly is zero up to the rounding
+// of a difference) is returned as zero.
 __global__ __launch_bounds__(256) void reduce_rows_kernel(const double* __restrict__ row_err,
                                                           int64_t seg_rows, int n_cand, int out_stride,
-                                                          double* __restrict__ out) {
+                                                          int not_below_zero, double* __restrict__ out) {
   __shared__ double red[256];
   const int c = blockIdx.x;
   const double* base = row_err + (int64_t)blockIdx.y * seg_rows * n_cand;
@@ -393,7 +447,7 @@ __global__ __launch_bounds__(256) void reduce_rows_kernel(const double* __restri
     if (threadIdx.x < st) red[threadIdx.x] += red[threadIdx.x + st];
     __syncthreads();
   }
-  if (threadIdx.x == 0) out[(int64_t)blockIdx.y * out_stride + c] = red[0];
+  if (threadIdx.x == 0) out[(int64_t)blockIdx.y * out_stride + c] = not_below_zero && red[0] < 0.0 ? 0.0 : red[0];
 }
 
 // Everything the host needs for the decision, in one launch.  Workgroup b of the grid computes
@@ -635,7 +689,8 @@ int run_quant_error(pq_format fmt, int group, const void* x, int64_t rows, int64
   }
   int rc = launch_quant_error(fmt, group, tl, 1, rows, (int)K, q, offs, 1, perm ? 0 : 1, ScaleArg{ts, nullptr}, part, st);
   if (rc) return rc;
-  hipLaunchKernelGGL(reduce_rows_kernel, dim3(1, 1), dim3(256), 0, st, part, (int64_t)q.parts(), 1, 1, err_out);
+  hipLaunchKernelGGL(reduce_rows_kernel, dim3(1, 1), dim3(256), 0, st, part, (int64_t)q.parts(), 1, 1,
+                     fmt == PQ_FMT_NVFP4 ? 1 : 0, err_out);
   return check_hip(hipGetLastError(), "reduce_rows_kernel");
 }
 
@@ -777,6 +832,12 @@ int run_select(pq_format fmt, int group, const double* act_sumsq, const double* 
     double ex = 0.0;
     for (int b = 0; b < n_batches; ++b) ex += h[(size_t)b * kMaxCand + c];
     double ew = h[(size_t)n_batches * kMaxCand + c];
+    if (fmt == PQ_FMT_NVFP4) {
+      // NVFP4 errors are differences known to about 1e-15 of the tensor's sum of squares: below 1e-13 of it
+      // they are not told from zero (data the format holds exactly), and are reported as zero
+      if (ex < 1e-13 * sum_x2) ex = 0.0;
+      if (ew < 1e-13 * sum_w2) ew = 0.0;
+    }
     E[c] = ex / sum_x2 + ew / sum_w2;
   }
   int best = 0;

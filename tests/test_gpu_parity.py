@@ -415,6 +415,67 @@ def test_quant_error_launch_variants(fmt, g, rows, K):
         np.testing.assert_allclose(out.item(), ref, rtol=T.ERRSUM_RTOL)
 
 
+@pytest.mark.parametrize("shrink", [2.0, 5.0, 64.0, 4096.0, 1e9])
+def test_quant_error_nvfp4_tensor_scale_too_small(shrink):
+    """A tensor scale smaller than the data calls for saturates block scales at 448: up to a factor 7
+    the kernel keeps its exact fp32 group sums, beyond it the wave takes the element-wise fp64 sum;
+    either way the error is the oracle's (which clips the block scale the same way)."""
+    rows, K = 41, 1536
+    _say("quant_error nvfp4 shrunken tensor scale / %g" % shrink)
+    rng = np.random.default_rng(1700)
+    bits = _rand_bits(rng, rows, K)
+    x = _to_dev(bits)
+    x64 = OF.bf16_bits_to_f64(bits)
+    ts = float(np.float32(float(OQ.nvfp4_tensor_scale(OC.absmax(x64))) / shrink))
+    perm = rng.permutation(K).astype(np.int32)
+    out = torch.zeros(1, dtype=torch.float64, device=DEV)
+    for p in (None, perm):
+        pq.pq_quant_error(pq.FMT_NVFP4, 16, x, None if p is None else torch.from_numpy(p).to(DEV), ts, out)
+        torch.cuda.synchronize()
+        ref = OC.squared_error(pq.FMT_NVFP4, 16, x64, p, np.float32(ts))
+        np.testing.assert_allclose(out.item(), ref, rtol=T.ERRSUM_RTOL)
+
+
+def test_nvfp4_error_of_exactly_representable_data_is_zero():
+    """Tensors made of E2M1 values times a power-of-two block scale times the tensor scale quantize
+    without loss in the original order (every group carries its own 6 s T); a reorder mixes block scales
+    inside groups and does lose.  NVFP4 errors are computed as a difference (sum of squares minus the
+    cross terms), so the kernel's raw sum is zero only up to a rounding of that difference:
+    pq_quant_error returns it clamped at zero (at most 1e-13 of the sum of squares), pq_select_perm
+    reports exactly 0, as the oracle does, and keeps the original order."""
+    K, M, N, g = 512, 48, 32, 16
+    rng = np.random.default_rng(4242)
+    e2m1 = np.array([0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0])
+    ts = 2.0 ** -7
+
+    def exact(rows, t):
+        q = rng.choice(e2m1, size=(rows, K)) * rng.choice([-1.0, 1.0], size=(rows, K))
+        q[:, ::g] = 6.0                                         # every group's maximum fixes its scale
+        scale = 2.0 ** rng.integers(-3, 4, size=(rows, K // g))
+        scale[0, 0] = 448.0                                     # the tensor's maximum is 6 * 448 * t
+        return synth.f64_to_bf16_bits(q * np.repeat(scale, g, axis=1) * t)
+
+    ts_w = 2.0 ** -10
+    xb, wb = exact(M, ts), exact(N, ts_w)
+    x64, w64 = OF.bf16_bits_to_f64(xb), OF.bf16_bits_to_f64(wb)
+    assert float(OQ.nvfp4_tensor_scale(OC.absmax(w64))) == ts_w      # the scale the oracle derives for W
+    assert OC.squared_error(pq.FMT_NVFP4, g, x64, None, np.float32(ts)) == 0.0
+    out = torch.zeros(1, dtype=torch.float64, device=DEV)
+    pq.pq_quant_error(pq.FMT_NVFP4, g, _to_dev(xb), None, ts, out)
+    torch.cuda.synchronize()
+    assert 0.0 <= out.item() <= 1e-13 * np.sum(x64 * x64)
+    xs, w = [_to_dev(xb)], _to_dev(wb)
+    sa, sw, _, _ = _gpu_moments(xs, w, K)
+    perm_out = torch.empty(K, dtype=torch.int32, device=DEV)
+    rep = pq.pq_select_perm(pq.FMT_NVFP4, g, sa, sw, xs, w, ts, ts_w, perm_out)
+    torch.cuda.synchronize()
+    ref = OC.select_permutation(pq.FMT_NVFP4, g, [x64], w64, act_tensor_scale=np.float32(ts))
+    assert rep.e_orig == 0.0 and ref.e_orig == 0.0 and not rep.accepted and not ref.accepted
+    np.testing.assert_allclose(rep.e_cand, ref.e_cand, rtol=1e-10, atol=1e-13)
+    assert min(rep.e_cand) > 1e-6                              # every reorder loses
+    np.testing.assert_array_equal(perm_out.cpu().numpy(), np.arange(K))
+
+
 def test_select_perm_equal_keys_across_sort_chunks():
     """Two key values alternating over 1280 channels (five 256-key chunks of the counting sort):
     the stable descending order is all even channels, then all odd ones.  Every alpha gives the
