@@ -61,8 +61,9 @@ def _check_close(got_bits, ref64, label, min_same=0.995):
 
 
 # widths: powers of two with every last-pass radix (2, 4, 8, 16), the Paley factors 12 and 20 alone and
-# combined with Sylvester digits, the FLUX widths
-WIDTHS = [8, 16, 32, 64, 128, 512, 4096, 24, 48, 96, 768, 3072, 40, 160, 2560,
+# combined with Sylvester digits (12 * 2^k from 192 on takes the Paley pass on the matrix unit, below that
+# on the vector unit), the FLUX widths
+WIDTHS = [8, 16, 32, 64, 128, 512, 4096, 24, 48, 96, 192, 768, 3072, 40, 160, 2560,
           8192, 12288, 5120, 24576]          # wider than 4096: four waves share a row
 
 
@@ -87,7 +88,7 @@ def test_hadamard_reorder_matches_oracle(K, with_perm):
 def test_unit_vectors_give_the_rows_of_the_matrix():
     """Row i of the identity is mapped to row i of H: every entry +-1/sqrt(K) with the oracle's sign
     (pins the index conventions of the fast transform: digit order, Paley orientation)."""
-    for K in (48, 160, 256):
+    for K in (48, 160, 192, 256, 768):
         x_bits = _bits(np.eye(K) * 4.0)
         y = pq.pq_hadamard_reorder(_dev(x_bits))
         torch.cuda.synchronize()

@@ -299,6 +299,10 @@ def test_select_perm_matches_oracle(name, fmt, g, M, N, K, nb):
     rep_d = pq.pq_select_perm_device_scales(fmt, g, sa, sw, xs, w, ta_d, tw_d, perm_dev)
     torch.cuda.synchronize()
     assert rep_d == rep and torch.equal(perm_dev, perm_out)
+    if fmt != pq.FMT_NVFP4:                 # the integer formats have no tensor scale: the pointers may be NULL
+        rep_n = pq.pq_select_perm_device_scales(fmt, g, sa, sw, xs, w, None, None, perm_dev)
+        torch.cuda.synchronize()
+        assert rep_n == rep and torch.equal(perm_dev, perm_out)
     # acceptance never raises the calibration error
     assert rep.e_best <= rep.e_orig or not rep.accepted
     # tau above the realised gain rejects and returns the identity
