@@ -54,7 +54,7 @@ int run_select(pq_format fmt, int group, const double* act_sumsq, const double* 
                int n_alpha, double tau, int32_t* perm_out, pq_select_report* report, void* ws, hipStream_t st);
 int launch_candidate_orders(const double* act_sumsq, const double* w_sumsq, int64_t K, const double* alphas,
                             int n_alpha, double* keys, int32_t* rank, int32_t* cands, hipStream_t st,
-                            int32_t* offs = nullptr, int slot_bytes = 0);
+                            int32_t* offs = nullptr, int slot_bytes = 0, uint32_t* differs = nullptr);
 int launch_identity_order(int32_t* perm, int64_t K, hipStream_t st);
 double* pinned_doubles(size_t n);     // the calling thread's pinned host buffer, kept for the process lifetime
 int launch_round_robin(const int32_t* order, int64_t K, int group, int32_t* perm, hipStream_t st);

@@ -38,8 +38,9 @@ struct AlphaList {
 __global__ __launch_bounds__(256) void key_kernel(const double* __restrict__ sa,
                                                   const double* __restrict__ sw, int64_t K,
                                                   AlphaList alphas, double* __restrict__ key,
-                                                  int32_t* __restrict__ rank) {
+                                                  int32_t* __restrict__ rank, uint32_t* __restrict__ differs) {
   int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (differs && i == 0) differs[blockIdx.y] = 0u;    // same_order_kernel ORs into it
   if (i >= K) return;
   rank[(int64_t)blockIdx.y * K + i] = 0;          // the counting pass adds to it
   const double alpha = alphas.a[blockIdx.y];
@@ -101,6 +102,37 @@ __global__ __launch_bounds__(256) void rank_scatter_kernel(const int32_t* __rest
   if (offs) offs[at] = (i + (i >> 3)) * slot_bytes;
 }
 
+// Which candidate orders repeat an earlier one.  Candidate 0 is the original order, candidate 1 + j the order
+// of alpha_j.  differs[j] collects a bit per earlier candidate c <= j that differs from order j somewhere
+// (integer OR: no order dependence); workgroup (x, j) looks at 256 positions.  differs[] is zeroed by
+// key_kernel, which runs before on the same stream.
+__global__ __launch_bounds__(256) void same_order_kernel(const int32_t* __restrict__ perms, int K,
+                                                         uint32_t* __restrict__ differs) {
+  __shared__ unsigned block_bits;
+  const int j = blockIdx.y;
+  if (threadIdx.x == 0) block_bits = 0u;
+  __syncthreads();
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  unsigned d = 0u;
+  if (i < K) {
+    const int32_t v = perms[(int64_t)j * K + i];
+    d |= v != i ? 1u : 0u;                           // bit 0: the original order
+    for (int e = 0; e < j; ++e) d |= (perms[(int64_t)e * K + i] != v ? 1u : 0u) << (1 + e);
+  }
+  if (d) atomicOr(&block_bits, d);
+  __syncthreads();
+  if (threadIdx.x == 0 && block_bits) atomicOr(&differs[j], block_bits);
+}
+// the first candidate with the same order as candidate c (c itself if none before it)
+__device__ __forceinline__ int first_same_order(const uint32_t* __restrict__ differs, int c) {
+  if (c == 0) return 0;
+  const uint32_t bits = differs[c - 1];
+  int first = c;
+  for (int e = c - 1; e >= 0; --e)
+    if (!((bits >> e) & 1u)) first = e;
+  return first;
+}
+
 __global__ __launch_bounds__(256) void iota_kernel(int32_t* p, int K) {
   int i = blockIdx.x * 256 + threadIdx.x;
   if (i < K) p[i] = i;
@@ -160,7 +192,7 @@ template <int FMT, int G, int R>
 __global__ __launch_bounds__(64 * kQeMaxWaves) void quant_error_kernel(TensorList xs, int rows, int K,
                                                           const int32_t* __restrict__ offs,
                                                           int n_cand, int identity_first, ScaleArg t_arg,
-                                                          int rows_per_block,
+                                                          int rows_per_block, const uint32_t* __restrict__ differs,
                                                           double* __restrict__ part) {
   typedef typename FloatVec<R>::type vec_t;
   constexpr int C = QeChunk<FMT>::value;
@@ -176,10 +208,10 @@ __global__ __launch_bounds__(64 * kQeMaxWaves) void quant_error_kernel(TensorLis
   const int chunks8 = K / 8;               // staging granularity: one 16-byte load
   const int chunks = K / C;
   const int wave_chunks = (chunks + 63) >> 6;
-  const int n_items = n_cand * wave_chunks;
-  const int per_wave = (n_items + n_waves - 1) / n_waves;
-  const int it0 = wave * per_wave, it1 = min(n_items, it0 + per_wave);
-  const int cand0 = it0 / wave_chunks, blk0 = it0 - cand0 * wave_chunks;     // uniform over the wave
+  // Candidates that repeat an earlier order are left out.  Lane c works out whether candidate c does (one
+  // load); the answer is used after the first rows have been requested (see below).
+  int same_as_lane = lane;
+  if (differs && lane < n_cand) same_as_lane = first_same_order(differs, lane);
   const float T = t_arg.dev ? *t_arg.dev : t_arg.value;           // uniform
   const float encT = (FMT == kNvfp4) ? nv4_enc_scale(T) : 0.0f;
   // The offsets are used as LDS addresses as they are: the staged rows are the kernel's only LDS object and
@@ -247,6 +279,22 @@ __global__ __launch_bounds__(64 * kQeMaxWaves) void quant_error_kernel(TensorLis
 
   double acc = 0.0;
   fetch_ahead(row0);
+  // the orders to evaluate, four bits each (at most 16 candidates); the work items run over that list
+  unsigned long long order_list = 0;
+  int n_orders = 0;
+  {
+    const unsigned long long keep = __ballot(lane < n_cand && same_as_lane == lane);     // uniform
+    for (int c = 0; c < n_cand; ++c) {
+      if (!((keep >> c) & 1ull)) continue;
+      order_list |= (unsigned long long)c << (4 * n_orders);
+      ++n_orders;
+    }
+  }
+  const int n_items = n_orders * wave_chunks;
+  const int per_wave = (n_items + n_waves - 1) / n_waves;
+  const int it0 = wave * per_wave, it1 = min(n_items, it0 + per_wave);
+  const int ord0 = it0 / wave_chunks, blk0 = it0 - ord0 * wave_chunks;       // uniform over the wave
+  auto cand_of = [&](int ord) { return (int)((order_list >> (4 * ord)) & 15u); };
   for (int rg = row0; rg < row_end; rg += R) {
     __syncthreads();                       // the previous rows have been read by every wave
 #pragma unroll
@@ -266,7 +314,8 @@ __global__ __launch_bounds__(64 * kQeMaxWaves) void quant_error_kernel(TensorLis
     // before it is evaluated (at its start when four rows are resident: the registers do not hold both
     // then, and a second workgroup of the compute unit covers the wait), by which time the rows have
     // long arrived.
-    int cand = cand0, blk = blk0;
+    int ord = ord0, blk = blk0;
+    int cand = cand_of(ord);
     int o_ahead[kOffsetsAhead ? C : 1];
     if constexpr (kOffsetsAhead) {
       if (it0 < it1) load_offsets(cand, blk, o_ahead);
@@ -287,7 +336,7 @@ __global__ __launch_bounds__(64 * kQeMaxWaves) void quant_error_kernel(TensorLis
       float v[R][C];
 #pragma unroll
       for (int j = 0; j < C; ++j) {
-        const vec_t g = *(lds_vec_ptr)(uint32_t)o[j];
+        const vec_t g = *(lds_vec_ptr)(uintptr_t)(uint32_t)o[j];
         if constexpr (R == 1) v[0][j] = g;
         else {
 #pragma unroll
@@ -296,7 +345,7 @@ __global__ __launch_bounds__(64 * kQeMaxWaves) void quant_error_kernel(TensorLis
       }
       const bool cand_done = blk + 1 == wave_chunks || it + 1 == it1;     // uniform
       if constexpr (kOffsetsAhead) {
-        if (it + 1 < it1) load_offsets(cand_done ? cand + 1 : cand, cand_done ? 0 : blk + 1, o_ahead);
+        if (it + 1 < it1) load_offsets(cand_done ? cand_of(ord + 1) : cand, cand_done ? 0 : blk + 1, o_ahead);
       }
       double errs[R];                               // one chain per resident row
 #pragma unroll
@@ -406,7 +455,8 @@ __global__ __launch_bounds__(64 * kQeMaxWaves) void quant_error_kernel(TensorLis
         if (lane == cand) acc += total;
         run = 0.0;
         blk = 0;
-        ++cand;
+        ++ord;
+        cand = cand_of(ord);
       }
     }
   }
@@ -463,6 +513,7 @@ struct TailArgs {
   const double* act_sumsq;
   const double* w_sumsq;
   const int32_t* cands;     // [n_alpha][K]
+  const uint32_t* differs;  // per alpha: which earlier candidates differ; a repeated order takes the first one's sums
   int64_t x_parts, w_parts, K;
   int n_cand, n_batches, n_alpha;
 };
@@ -494,7 +545,7 @@ __global__ __launch_bounds__(256) void select_tail_kernel(TailArgs a, double* __
     const int seg = is_w ? 0 : b / a.n_cand, c = is_w ? b - n_x : b % a.n_cand;
     const int64_t n = is_w ? a.w_parts : a.x_parts;
     const double* base = is_w ? a.w_part : a.x_part + (int64_t)seg * n * a.n_cand;
-    s = strided_sum(base + (int64_t)c * n, threadIdx.x, n, 256);
+    s = strided_sum(base + (int64_t)first_same_order(a.differs, c) * n, threadIdx.x, n, 256);
     dst = (int64_t)(is_w ? a.n_batches : seg) * kMaxCand + c;
   } else if (b < n_x + a.n_cand + 2) {
     const int which = b - n_x - a.n_cand;
@@ -573,8 +624,8 @@ static QeShape qe_shape(pq_format fmt, int64_t rows, int64_t K, int n_tensors, i
 
 template <int FMT, int G, int R>
 static int launch_qe_r(const TensorList& xs, int n_tensors, int64_t rows, int K, const QeShape& q,
-                       const int32_t* offs, int n_cand, int identity_first, ScaleArg T, double* part,
-                       hipStream_t st) {
+                       const int32_t* offs, int n_cand, int identity_first, ScaleArg T, const uint32_t* same_as,
+                       double* part, hipStream_t st) {
   auto kern = quant_error_kernel<FMT, G, R>;
   // the attribute is per kernel instance and device; it is raised once per instance to the most any
   // launch may ask for, not on every call
@@ -588,36 +639,37 @@ static int launch_qe_r(const TensorList& xs, int n_tensors, int64_t rows, int K,
     if (dev >= 0 && dev < kMaxDevicesSeen) raised[dev].store(true, std::memory_order_release);
   }
   hipLaunchKernelGGL(kern, dim3((unsigned)q.blocks, (unsigned)n_tensors), dim3(q.threads), q.shmem, st, xs,
-                     (int)rows, K, offs, n_cand, identity_first, T, q.rows_per_block, part);
+                     (int)rows, K, offs, n_cand, identity_first, T, q.rows_per_block, same_as, part);
   return check_hip(hipGetLastError(), "quant_error_kernel");
 }
 
 template <int FMT, int G>
 static int launch_qe(const TensorList& xs, int n_tensors, int64_t rows, int K, const QeShape& q,
-                     const int32_t* offs, int n_cand, int identity_first, ScaleArg T, double* part,
-                     hipStream_t st) {
+                     const int32_t* offs, int n_cand, int identity_first, ScaleArg T, const uint32_t* same_as,
+                     double* part, hipStream_t st) {
   switch (q.r) {
-    case 4: return launch_qe_r<FMT, G, 4>(xs, n_tensors, rows, K, q, offs, n_cand, identity_first, T, part, st);
-    case 2: return launch_qe_r<FMT, G, 2>(xs, n_tensors, rows, K, q, offs, n_cand, identity_first, T, part, st);
-    default: return launch_qe_r<FMT, G, 1>(xs, n_tensors, rows, K, q, offs, n_cand, identity_first, T, part, st);
+    case 4: return launch_qe_r<FMT, G, 4>(xs, n_tensors, rows, K, q, offs, n_cand, identity_first, T, same_as, part, st);
+    case 2: return launch_qe_r<FMT, G, 2>(xs, n_tensors, rows, K, q, offs, n_cand, identity_first, T, same_as, part, st);
+    default: return launch_qe_r<FMT, G, 1>(xs, n_tensors, rows, K, q, offs, n_cand, identity_first, T, same_as, part, st);
   }
 }
 
 // part: [n_tensors][n_cand][q.parts()]; offs: the candidate orders as slot offsets for q.r resident rows
 static int launch_quant_error(pq_format fmt, int group, const TensorList& x, int n_tensors, int64_t rows,
                               int K, const QeShape& q, const int32_t* offs, int n_cand,
-                              int identity_first, ScaleArg T, double* part, hipStream_t st) {
+                              int identity_first, ScaleArg T, const uint32_t* same_as, double* part,
+                              hipStream_t st) {
   if (rows > 0x7FFFFFFF) return fail(PQ_ERR_SHAPE, "too many rows");
   if (q.shmem > 150 * 1024) return fail(PQ_ERR_SHAPE, "K=%d too large for the LDS-resident row", K);   // the entry points refuse this earlier
   if (fmt == PQ_FMT_NVFP4)
-    return launch_qe<kNvfp4, 16>(x, n_tensors, rows, K, q, offs, n_cand, identity_first, T, part, st);
+    return launch_qe<kNvfp4, 16>(x, n_tensors, rows, K, q, offs, n_cand, identity_first, T, same_as, part, st);
 #define PQ_INT_CASE(F, FE)                                                                                  \
   if (fmt == F) {                                                                                           \
     switch (group) {                                                                                        \
-      case 32: return launch_qe<FE, 32>(x, n_tensors, rows, K, q, offs, n_cand, identity_first, T, part, st);   \
-      case 64: return launch_qe<FE, 64>(x, n_tensors, rows, K, q, offs, n_cand, identity_first, T, part, st);   \
-      case 128: return launch_qe<FE, 128>(x, n_tensors, rows, K, q, offs, n_cand, identity_first, T, part, st); \
-      case 256: return launch_qe<FE, 256>(x, n_tensors, rows, K, q, offs, n_cand, identity_first, T, part, st); \
+      case 32: return launch_qe<FE, 32>(x, n_tensors, rows, K, q, offs, n_cand, identity_first, T, same_as, part, st);   \
+      case 64: return launch_qe<FE, 64>(x, n_tensors, rows, K, q, offs, n_cand, identity_first, T, same_as, part, st);   \
+      case 128: return launch_qe<FE, 128>(x, n_tensors, rows, K, q, offs, n_cand, identity_first, T, same_as, part, st); \
+      case 256: return launch_qe<FE, 256>(x, n_tensors, rows, K, q, offs, n_cand, identity_first, T, same_as, part, st); \
     }                                                                                                       \
   }
   PQ_INT_CASE(PQ_FMT_INT4, kInt4)
@@ -632,6 +684,7 @@ struct SelectWs {
   int32_t* cands;    // [PQ_MAX_ALPHAS][K]
   int32_t* rank;     // [PQ_MAX_ALPHAS][K] position of every channel in the sorted order
   int32_t* offs;     // [PQ_MAX_ALPHAS][K] the candidates as LDS slot offsets of the error evaluation
+  uint32_t* same_as; // [PQ_MAX_ALPHAS] per alpha: a bit per earlier candidate whose order differs (same_order_kernel)
   double* row_err;   // partial error sums: [n_batches][n_cand][parts(M)], then [n_cand][parts(N)]
   double* sums;      // [(n_batches + 1) * kMaxCand + 2 + PQ_MAX_ALPHAS]: per-batch errors, weight
                      // errors, |X|^2, |W|^2, moved-channel counts
@@ -650,6 +703,7 @@ static size_t carve_select(void* base, int64_t M, int64_t N, int64_t K, int n_ba
   size_t o_cands = take((size_t)PQ_MAX_ALPHAS * K * 4);
   size_t o_rank = take((size_t)PQ_MAX_ALPHAS * K * 4);
   size_t o_offs = take((size_t)PQ_MAX_ALPHAS * K * 4);
+  size_t o_same = take((size_t)kMaxCand * 4);
   // a workgroup covers at least kQeMinRowsPerBlock rows with at most kQeMaxWaves waves: no more
   // partial sums than kQeParts(rows) per tensor
   size_t o_rowerr = take((size_t)((int64_t)n_batches * kQeParts(M) + kQeParts(N)) * kMaxCand * 8);
@@ -660,6 +714,7 @@ static size_t carve_select(void* base, int64_t M, int64_t N, int64_t K, int n_ba
     w->cands = (int32_t*)(b + o_cands);
     w->rank = (int32_t*)(b + o_rank);
     w->offs = (int32_t*)(b + o_offs);
+    w->same_as = (uint32_t*)(b + o_same);
     w->row_err = (double*)(b + o_rowerr);
     w->sums = (double*)(b + o_sums);
   }
@@ -687,7 +742,8 @@ int run_quant_error(pq_format fmt, int group, const void* x, int64_t rows, int64
     hipLaunchKernelGGL(perm_to_offsets_kernel, dim3((unsigned)((K + 255) / 256)), dim3(256), 0, st, perm, (int)K,
                        qe_slot_bytes(q.r), offs);
   }
-  int rc = launch_quant_error(fmt, group, tl, 1, rows, (int)K, q, offs, 1, perm ? 0 : 1, ScaleArg{ts, nullptr}, part, st);
+  int rc = launch_quant_error(fmt, group, tl, 1, rows, (int)K, q, offs, 1, perm ? 0 : 1, ScaleArg{ts, nullptr},
+                              nullptr, part, st);
   if (rc) return rc;
   hipLaunchKernelGGL(reduce_rows_kernel, dim3(1, 1), dim3(256), 0, st, part, (int64_t)q.parts(), 1, 1,
                      fmt == PQ_FMT_NVFP4 ? 1 : 0, err_out);
@@ -699,15 +755,17 @@ int run_quant_error(pq_format fmt, int group, const void* x, int64_t rows, int64
 // With offs ([n_alpha][K]), the same orders are also written as slot offsets of slot_bytes a slot.
 int launch_candidate_orders(const double* act_sumsq, const double* w_sumsq, int64_t K, const double* alphas,
                             int n_alpha, double* keys, int32_t* rank, int32_t* cands, hipStream_t st,
-                            int32_t* offs, int slot_bytes) {
+                            int32_t* offs, int slot_bytes, uint32_t* differs) {
   const unsigned kb = (unsigned)((K + 255) / 256);
   const int chunks = rank_chunks(K);
   AlphaList al;
   for (int j = 0; j < PQ_MAX_ALPHAS; ++j) al.a[j] = j < n_alpha ? alphas[j] : 0.0;
-  hipLaunchKernelGGL(key_kernel, dim3(kb, n_alpha), dim3(256), 0, st, act_sumsq, w_sumsq, K, al, keys, rank);
+  hipLaunchKernelGGL(key_kernel, dim3(kb, n_alpha), dim3(256), 0, st, act_sumsq, w_sumsq, K, al, keys, rank, differs);
   hipLaunchKernelGGL(rank_count_kernel, dim3(kb, chunks, n_alpha), dim3(256), 0, st, keys, (int)K, rank);
   hipLaunchKernelGGL(rank_scatter_kernel, dim3(kb, n_alpha), dim3(256), 0, st, rank, (int)K, cands, offs,
                      slot_bytes);
+  if (differs)          // which orders repeat an earlier candidate (or the original order)
+    hipLaunchKernelGGL(same_order_kernel, dim3(kb, n_alpha), dim3(256), 0, st, cands, (int)K, differs);
   return check_hip(hipGetLastError(), "key/rank kernels");
 }
 
@@ -798,7 +856,7 @@ int run_select(pq_format fmt, int group, const double* act_sumsq, const double* 
   const QeShape qa = qe_shape(fmt, M, K, n_batches < kMaxMomentBatches ? n_batches : kMaxMomentBatches, n_cand);
   const QeShape qw = qe_shape(fmt, N, K, 1, n_cand);       // the same resident rows (a function of K): one set of offsets
   if ((rc = launch_candidate_orders(act_sumsq, w_sumsq, K, alphas, n_alpha, W.keys, W.rank, W.cands, st, W.offs,
-                                    qe_slot_bytes(qa.r))))
+                                    qe_slot_bytes(qa.r), W.same_as)))
     return rc;
   double* sums = W.sums;
   for (int b0 = 0; b0 < n_batches; b0 += kMaxMomentBatches) {
@@ -806,15 +864,17 @@ int run_select(pq_format fmt, int group, const double* act_sumsq, const double* 
     TensorList tl;
     for (int b = 0; b < kMaxMomentBatches; ++b) tl.p[b] = (const uint16_t*)x_calib[b0 + (b < nb ? b : 0)];
     rc = launch_quant_error(fmt, group, tl, nb, M, (int)K, qa, W.offs, n_cand, 1, ScaleArg{act_ts, act_ts_dev},
-                            W.row_err + (size_t)b0 * qa.parts() * n_cand, st);
+                            W.same_as, W.row_err + (size_t)b0 * qa.parts() * n_cand, st);
     if (rc) return rc;
   }
   double* w_part = W.row_err + (size_t)n_batches * qa.parts() * n_cand;
   TensorList wl;
   for (int b = 0; b < kMaxMomentBatches; ++b) wl.p[b] = (const uint16_t*)w;
-  rc = launch_quant_error(fmt, group, wl, 1, N, (int)K, qw, W.offs, n_cand, 1, ScaleArg{w_ts, w_ts_dev}, w_part, st);
+  rc = launch_quant_error(fmt, group, wl, 1, N, (int)K, qw, W.offs, n_cand, 1, ScaleArg{w_ts, w_ts_dev}, W.same_as,
+                          w_part, st);
   if (rc) return rc;
-  TailArgs ta{W.row_err, w_part, act_sumsq, w_sumsq, W.cands, qa.parts(), qw.parts(), K, n_cand, n_batches, n_alpha};
+  TailArgs ta{W.row_err, w_part, act_sumsq, w_sumsq, W.cands, W.same_as, qa.parts(), qw.parts(), K, n_cand, n_batches,
+              n_alpha};
   hipLaunchKernelGGL(select_tail_kernel, dim3((unsigned)(n_cand * (n_batches + 1) + 2 + n_alpha)), dim3(256), 0,
                      st, ta, sums);
   if ((rc = check_hip(hipGetLastError(), "select_tail_kernel"))) return rc;

@@ -480,6 +480,38 @@ def test_nvfp4_error_of_exactly_representable_data_is_zero():
     np.testing.assert_array_equal(perm_out.cpu().numpy(), np.arange(K))
 
 
+@pytest.mark.parametrize("fmt,g", [(pq.FMT_INT4, 32), (pq.FMT_NVFP4, 16)])
+def test_select_perm_repeated_orders(fmt, g):
+    """Weights whose columns all have the same second moment: alpha = 0 sorts equal keys, i.e. keeps the
+    original order, and every alpha > 0 sorts by the activations' moments alone -- five times the same
+    order.  The library evaluates an order once and hands its error to the repeats: e_cand[0] is e_orig
+    bit for bit, e_cand[1..5] are one number, and everything equals the oracle, which evaluates all seven."""
+    K, M, N = 768, 40, 24
+    _say("select repeated orders fmt=%d" % fmt)
+    rng = np.random.default_rng(808 + fmt)
+    col = 1.03 ** rng.permutation(K)                           # well separated column scales
+    xb = synth.f64_to_bf16_bits(rng.standard_normal((M, K)) * col[None, :])
+    wb = synth.f64_to_bf16_bits(np.sign(rng.standard_normal((N, K))))      # every column: N ones
+    xs, w = [_to_dev(xb)], _to_dev(wb)
+    x64, w64 = OF.bf16_bits_to_f64(xb), OF.bf16_bits_to_f64(wb)
+    sa, sw, _, _ = _gpu_moments(xs, w, K)
+    assert torch.all(sw == float(N))
+    ts_a = float(OQ.nvfp4_tensor_scale(OC.absmax(x64))) if fmt == pq.FMT_NVFP4 else 1.0
+    ts_w = float(OQ.nvfp4_tensor_scale(OC.absmax(w64))) if fmt == pq.FMT_NVFP4 else 1.0
+    perm_out = torch.empty(K, dtype=torch.int32, device=DEV)
+    rep = pq.pq_select_perm(fmt, g, sa, sw, xs, w, ts_a, ts_w, perm_out)
+    torch.cuda.synchronize()
+    ref = OC.select_permutation(fmt, g, [x64], w64)
+    np.testing.assert_array_equal(ref.cand_perms[0], np.arange(K))
+    for j in range(2, 6):
+        np.testing.assert_array_equal(ref.cand_perms[j], ref.cand_perms[1])
+    assert rep.e_cand[0] == rep.e_orig and len(set(rep.e_cand[1:6])) == 1
+    np.testing.assert_allclose(rep.e_orig, ref.e_orig, rtol=1e-10)
+    np.testing.assert_allclose(rep.e_cand, ref.e_cand, rtol=1e-10)
+    assert rep.accepted == ref.accepted and rep.alpha_index == ref.alpha_index
+    np.testing.assert_array_equal(perm_out.cpu().numpy(), ref.perm)
+
+
 def test_select_perm_equal_keys_across_sort_chunks():
     """Two key values alternating over 1280 channels (five 256-key chunks of the counting sort):
     the stable descending order is all even channels, then all odd ones.  Every alpha gives the
