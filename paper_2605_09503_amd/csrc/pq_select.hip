@@ -9,6 +9,8 @@
 //                     (key_j == key_i and j < i)}; perm[rank(i)] = i.  O(K^2) compares, K <= 65536,
 //                     split over (channel block, key chunk, candidate) workgroups, integer
 //                     counts added atomically, fully deterministic.
+//   same_order_kernel  which candidate orders repeat an earlier one (or the original order): those are
+//                     evaluated once.
 //   quant_error_kernel a workgroup stages a few rows in LDS at a time; for every candidate order
 //                     their channels are gathered from LDS (one read serves all resident rows),
 //                     quantized with the same lane-cooperative quantizer as the runtime kernels,
