@@ -225,6 +225,10 @@ int pq_select_perm_output_error(pq_format fmt, int group, const double* act_sums
  * permutation" reports):   err_out[0] = sum_{r,k} (x[r, perm[k]] - xhat)^2   (fp64).
  * x: bf16 [rows, K] contiguous.  perm: int32 [K] or NULL (identity).  tensor_scale: host float,
  * NVFP4 only.  err_out: double [1] device, overwritten.  K <= 34128 as for pq_select_perm.
+ * Accuracy: the integer formats sum exact element errors in fp64.  The NVFP4 error is formed as
+ * sum x^2 minus exact cross terms and is known to about 1e-15 of sum x^2 absolutely (a relative 1e-13
+ * for data that fill the format): a sum that comes out negative is returned as 0, and pq_select_perm
+ * reports a tensor's error as exactly 0 when it is below 1e-13 of the tensor's sum of squares.
  */
 int pq_quant_error(pq_format fmt, int group, const void* x_bf16, int64_t rows, int64_t K,
                    const int32_t* perm, float tensor_scale, double* err_out, void* workspace,
